@@ -1,0 +1,25 @@
+"""Float64 CPU oracle for the selective-recompute prefill path (TEST INFRASTRUCTURE).
+
+A plain, slow and deliberately unoptimised statement of what the path computes,
+written from the paper's description of the linker and of selective attention
+(Sec. 3.1, Sec. 4.1-4.2, Fig. 7, App. A) and from the position rule of the build
+target (cached keys are rotated by the RoPE angle of their chunk's global offset).
+
+It exists only to check the HIP library.  Nothing in the product path may import
+it: only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg do.
+It shares no code with the HIP path and never receives values from it.
+
+Pin status of every function (see tests/test_oracle_*.py):
+  plan.build_plan        pinned: hand-derived layout of the tiny config, closed-form
+                         counts, brute-force set construction on random layouts
+  rope.rotate            pinned: complex-multiplication form of RoPE, group laws
+  link.link_kv           pinned: consistent-cache case reproduces full prefill
+  attend.attend          pinned: loop transcription of App. A, library SDPA in the
+                         recompute-all case, closed forms (zero queries, one-hot V)
+The paper prints no worked numeric example of this path, so beyond those pins the
+values are unpinned by the paper itself.
+"""
+from .plan import build_plan            # noqa: F401
+from .rope import rotate                # noqa: F401
+from .link import link_kv, to_slots     # noqa: F401
+from .attend import attend, attend_loops  # noqa: F401

@@ -1,0 +1,38 @@
+"""Linking of stored chunk caches and fresh rows into one context (oracle side).
+
+Fig. 7 step 2 and Sec. 4.1: the K (and V) rows of the selected tokens are replaced
+by the freshly generated ones; every other row comes from the stored cache of its
+image.  Stored keys are moved from chunk-local to global positions with
+rope.rotate; values carry no position and are copied.
+"""
+import numpy as np
+from .rope import rotate
+
+
+def link_kv(plan, chunk_k, chunk_v, fresh_k, fresh_v, theta, interleaved=False):
+    """chunk_k / chunk_v: mapping source id -> float64 array [L][Hkv][D];
+    fresh_k / fresh_v: float64 [Nq][Hkv][D].  Returns (K, V) in logical order
+    [N][Hkv][D] (requests one after the other), float64."""
+    n = int(plan["ctx_off"][-1])
+    fresh_k = np.asarray(fresh_k, dtype=np.float64)
+    fresh_v = np.asarray(fresh_v, dtype=np.float64)
+    K = np.empty((n,) + fresh_k.shape[1:], dtype=np.float64)
+    V = np.empty_like(K)
+    for g in range(n):
+        inst, row = int(plan["src_inst"][g]), int(plan["src_row"][g])
+        if inst < 0:
+            K[g] = fresh_k[row]
+            V[g] = fresh_v[row]
+        else:
+            src = int(plan["inst_src"][inst])
+            shift = float(plan["inst_delta"][inst])
+            K[g] = rotate(np.asarray(chunk_k[src][row], dtype=np.float64), shift, theta, interleaved)
+            V[g] = np.asarray(chunk_v[src][row], dtype=np.float64)
+    return K, V
+
+
+def to_slots(x_logical, dst_slot, n_slots, fill=np.nan):
+    """Place logical rows at their physical slots (paged layout); unused slots = fill."""
+    out = np.full((n_slots,) + x_logical.shape[1:], fill, dtype=x_logical.dtype)
+    out[np.asarray(dst_slot, dtype=np.int64)] = x_logical
+    return out

@@ -1,0 +1,234 @@
+"""Pins of oracle.rope / oracle.link / oracle.attend (CPU only).
+
+Each test checks the oracle against something other than itself: the complex-number
+statement of rotary embedding, group laws, closed forms, a loop transcription of
+the attention definition of App. A, and a library SDPA for the case in which every
+token is recomputed (which is ordinary causal prefill, Sec. 2.2).
+"""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from oracle import attend, attend_loops, build_plan, link_kv, rotate, to_slots
+
+RNG = np.random.default_rng(1234)
+
+
+# ----------------------------------------------------------------- rotation
+def _rope_complex(x, pos, theta, interleaved):
+    """Textbook RoPE: each coordinate pair is a complex number times exp(i*pos*w)."""
+    D = x.shape[-1]
+    w = theta ** (-np.arange(0, D, 2, dtype=np.float64) / D)
+    if interleaved:
+        z = x[..., 0::2] + 1j * x[..., 1::2]
+    else:
+        z = x[..., : D // 2] + 1j * x[..., D // 2:]
+    z = z * np.exp(1j * pos * w)
+    y = np.empty_like(x)
+    if interleaved:
+        y[..., 0::2], y[..., 1::2] = z.real, z.imag
+    else:
+        y[..., : D // 2], y[..., D // 2:] = z.real, z.imag
+    return y
+
+
+@pytest.mark.parametrize("interleaved", [False, True])
+@pytest.mark.parametrize("theta,D", [(1e4, 64), (1e6, 128)])
+def test_rotate_matches_complex_form(theta, D, interleaved):
+    x = RNG.standard_normal((5, 3, D))
+    for pos in (0, 1, 17, 2432, 75839):
+        np.testing.assert_allclose(rotate(x, pos, theta, interleaved),
+                                   _rope_complex(x, pos, theta, interleaved), rtol=0, atol=1e-11)
+
+
+@pytest.mark.parametrize("interleaved", [False, True])
+def test_rotate_group_laws(interleaved):
+    theta, D = 1e4, 64
+    x = RNG.standard_normal((4, 2, D))
+    assert np.array_equal(rotate(x, 0, theta, interleaved), x)            # zero shift = identity
+    ab = rotate(rotate(x, 88, theta, interleaved), 16, theta, interleaved)
+    np.testing.assert_allclose(ab, rotate(x, 104, theta, interleaved), atol=1e-12)
+    np.testing.assert_allclose(rotate(rotate(x, 7, theta, interleaved), -7, theta, interleaved), x, atol=1e-12)
+    y = rotate(x, 1234, theta, interleaved)
+    np.testing.assert_allclose((y ** 2).sum(-1), (x ** 2).sum(-1), rtol=1e-12)
+
+
+def test_rotate_relative_position_law():
+    theta, D = 1e6, 128
+    q0, k0 = RNG.standard_normal(D), RNG.standard_normal(D)
+    ref = rotate(q0, 40, theta) @ rotate(k0, 10, theta)
+    for shift in (1, 2304, 70000):
+        got = rotate(q0, 40 + shift, theta) @ rotate(k0, 10 + shift, theta)
+        assert abs(got - ref) < 1e-9
+    # a different relative distance gives a different logit
+    assert abs(rotate(q0, 41, theta) @ rotate(k0, 10, theta) - ref) > 1e-6
+
+
+def test_rotate_per_row_shifts_and_sign():
+    theta, D = 1e4, 8
+    # e_0 turned by a quarter of the slowest..fastest pair: the fastest pair (i=0) has w=1
+    x = np.zeros(D); x[0] = 1.0
+    y = rotate(x, np.pi / 2, theta)
+    np.testing.assert_allclose(y[[0, D // 2]], [0.0, 1.0], atol=1e-12)   # counter-clockwise
+    xs = RNG.standard_normal((3, D))
+    ys = rotate(xs, np.array([0.0, 5.0, 9.0]), theta)
+    for i, d in enumerate((0.0, 5.0, 9.0)):
+        np.testing.assert_allclose(ys[i], rotate(xs[i], d, theta), atol=1e-13)
+
+
+# ----------------------------------------------------------------- attention
+def _tiny_problem(seed=0, hq=4, hkv=2, d=8):
+    reqs = [[("text", 3), ("chunk", 0, 6, None), ("text", 2), ("chunk", 1, 5, 3), ("text", 1)],
+            [("chunk", 1, 5, None), ("text", 4)]]
+    plan = build_plan(reqs, 2)
+    rng = np.random.default_rng(seed)
+    n, nq = int(plan["ctx_off"][-1]), len(plan["q_pos"])
+    q = rng.standard_normal((nq, hq, d))
+    k = rng.standard_normal((n, hkv, d))
+    v = rng.standard_normal((n, hkv, d))
+    return reqs, plan, q, k, v
+
+
+def test_attend_matches_loop_transcription():
+    _, plan, q, k, v = _tiny_problem()
+    o, lse = attend(q, k, v, plan, 0.37)
+    np.testing.assert_allclose(o, attend_loops(q, k, v, plan, 0.37), rtol=1e-12, atol=1e-13)
+
+
+def test_attend_tiny_config_matches_loops():
+    sh = workloads.shape(1)
+    reqs, _, _ = workloads.layout(1)
+    plan = build_plan(reqs, sh.default_k)
+    rng = np.random.default_rng(5)
+    q = rng.standard_normal((48, 4, 64)); k = rng.standard_normal((160, 4, 64)); v = rng.standard_normal((160, 4, 64))
+    rows = [0, 23, 24, 39, 47]
+    o, _ = attend(q, k, v, plan, sh.softmax_scale, rows=rows)
+    ref = attend_loops(q, k, v, plan, sh.softmax_scale)
+    np.testing.assert_allclose(o[rows], ref[rows], rtol=1e-12, atol=1e-13)
+    assert np.isnan(o[1]).all()
+
+
+def test_softmax_rows_sum_to_one_and_lse():
+    _, plan, q, k, v = _tiny_problem(1)
+    ones = np.ones_like(v)
+    o, lse = attend(q, k, ones, plan, 0.5)
+    np.testing.assert_allclose(o, 1.0, rtol=0, atol=1e-14)
+    # LSE against its definition, row by row
+    for r in (0, 5, len(q) - 1):
+        base = int(plan["ctx_off"][plan["q_req"][r]]); p = int(plan["q_pos"][r])
+        s = 0.5 * k[base:base + p + 1, 1] @ q[r, 3]
+        assert abs(lse[r, 3] - np.log(np.exp(s).sum())) < 1e-12
+
+
+def test_weights_exposed_by_one_hot_values_are_causal_by_position():
+    reqs, plan, q, k, _ = _tiny_problem(2, hq=2, hkv=2, d=17)
+    n = int(plan["ctx_off"][-1])
+    # request 0 has 17 positions: value row j = e_j, so the output IS the weight vector
+    v = np.zeros((n, 2, 17))
+    for j in range(17):
+        v[j, :, j] = 1.0
+    o, _ = attend(q, k, v, plan, 1.0)
+    for r in range(int(plan["q_off"][1])):
+        p = int(plan["q_pos"][r])
+        w = o[r, 0]
+        assert abs(w.sum() - 1.0) < 1e-13 and (w[: p + 1] > 0).all() and (w[p + 1:] == 0).all()
+        s = k[: p + 1, 0] @ q[r, 0]
+        np.testing.assert_allclose(w[: p + 1], np.exp(s) / np.exp(s).sum(), rtol=1e-12)
+
+
+def test_zero_queries_give_prefix_means():
+    _, plan, q, k, v = _tiny_problem(3)
+    o, lse = attend(np.zeros_like(q), k, v, plan, 1.0)
+    for r in range(len(q)):
+        base = int(plan["ctx_off"][plan["q_req"][r]]); p = int(plan["q_pos"][r])
+        np.testing.assert_allclose(o[r, 2], v[base:base + p + 1, 1].mean(0), atol=1e-13)
+        assert abs(lse[r, 2] - np.log(p + 1)) < 1e-13
+
+
+def test_gqa_equals_mha_with_repeated_heads_and_batch_equals_alone():
+    reqs, plan, q, k, v = _tiny_problem(4)
+    o, lse = attend(q, k, v, plan, 0.3)
+    o2, lse2 = attend(q, np.repeat(k, 2, axis=1), np.repeat(v, 2, axis=1), plan, 0.3)
+    np.testing.assert_allclose(o, o2, atol=1e-14); np.testing.assert_allclose(lse, lse2, atol=1e-14)
+    # second request alone
+    p1 = build_plan(reqs[1:], 2)
+    c0, q0 = int(plan["ctx_off"][1]), int(plan["q_off"][1])
+    o1, _ = attend(q[q0:], k[c0:], v[c0:], p1, 0.3)
+    np.testing.assert_allclose(o1, o[q0:], atol=1e-14)
+
+
+def _sdpa(q, k, v, scale, group):
+    """Library causal attention on [n][h][d] tensors, float64."""
+    tq = torch.from_numpy(q).permute(1, 0, 2)[None]
+    tk = torch.from_numpy(np.repeat(k, group, axis=1)).permute(1, 0, 2)[None]
+    tv = torch.from_numpy(np.repeat(v, group, axis=1)).permute(1, 0, 2)[None]
+    o = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=True, scale=scale)
+    return o[0].permute(1, 0, 2).numpy()
+
+
+def test_recompute_everything_is_plain_causal_prefill():
+    """k >= L for every chunk: the linked cache is the fresh K/V and the result is
+    ordinary causal attention (the arithmetic of prefix caching, Sec. 2.2)."""
+    reqs = [[("text", 5), ("chunk", 0, 9, None), ("text", 3), ("chunk", 1, 7, None)]]
+    plan = build_plan(reqs, 1000)
+    n, hq, hkv, d = 24, 6, 2, 16
+    assert len(plan["q_pos"]) == n
+    rng = np.random.default_rng(6)
+    q, fk, fv = rng.standard_normal((n, hq, d)), rng.standard_normal((n, hkv, d)), rng.standard_normal((n, hkv, d))
+    junk = {0: rng.standard_normal((9, hkv, d)), 1: rng.standard_normal((7, hkv, d))}
+    K, V = link_kv(plan, junk, junk, fk, fv, 1e4)
+    assert np.array_equal(K, fk) and np.array_equal(V, fv)
+    o, _ = attend(q, K, V, plan, 0.25)
+    np.testing.assert_allclose(o, _sdpa(q, fk, fv, 0.25, hq // hkv), rtol=1e-11, atol=1e-12)
+
+
+@pytest.mark.parametrize("interleaved", [False, True])
+@pytest.mark.parametrize("k", [0, 2, 5])
+def test_consistent_cache_reproduces_full_prefill(k, interleaved):
+    """If the stored chunks and the fresh rows come from the same position-free base
+    K0/V0 (stored = rotated at local positions, fresh = rotated at global positions),
+    linking rebuilds the full-prefill K/V exactly, so the selected rows of selective
+    attention equal the same rows of full causal prefill -- for any k."""
+    theta, hq, hkv, d = 1e4, 4, 2, 16
+    reqs = [[("text", 4), ("chunk", 0, 8, None), ("text", 3), ("chunk", 1, 6, None), ("text", 2)]]
+    plan = build_plan(reqs, k)
+    n = int(plan["ctx_off"][-1])
+    rng = np.random.default_rng(7)
+    k0, v0, q0 = rng.standard_normal((n, hkv, d)), rng.standard_normal((n, hkv, d)), rng.standard_normal((n, hq, d))
+    pos = np.arange(n, dtype=np.float64)[:, None]
+    k_full = rotate(k0, pos, theta, interleaved)
+    q_full = rotate(q0, pos, theta, interleaved)
+    chunk_k, chunk_v = {}, {}
+    for inst in range(len(plan["inst_src"])):
+        off, L, src = int(plan["inst_delta"][inst]), int(plan["inst_len"][inst]), int(plan["inst_src"][inst])
+        local = np.arange(L, dtype=np.float64)[:, None]
+        chunk_k[src] = rotate(k0[off:off + L], local, theta, interleaved)
+        chunk_v[src] = v0[off:off + L]
+    sel = plan["q_pos"]
+    K, V = link_kv(plan, chunk_k, chunk_v, k_full[sel], v0[sel], theta, interleaved)
+    np.testing.assert_allclose(K, k_full, atol=1e-12)
+    assert np.array_equal(V, v0)
+    o, _ = attend(q_full[sel], K, V, plan, 0.25)
+    full = _sdpa(q_full, k_full, v0, 0.25, hq // hkv)
+    np.testing.assert_allclose(o, full[sel], rtol=1e-10, atol=1e-11)
+
+
+def test_link_replaces_rows_and_shifts_by_chunk_offset():
+    reqs = [[("text", 2), ("chunk", 3, 4, None), ("chunk", 3, 4, None)]]   # same chunk twice
+    plan = build_plan(reqs, 1)
+    rng = np.random.default_rng(8)
+    ck = {3: rng.standard_normal((4, 1, 8))}; cv = {3: rng.standard_normal((4, 1, 8))}
+    fk, fv = rng.standard_normal((4, 1, 8)), rng.standard_normal((4, 1, 8))
+    K, V = link_kv(plan, ck, cv, fk, fv, 1e4)
+    assert plan["q_pos"].tolist() == [0, 1, 2, 6]
+    assert np.array_equal(K[[0, 1, 2, 6]], fk) and np.array_equal(V[[0, 1, 2, 6]], fv)
+    np.testing.assert_allclose(K[3:6], rotate(ck[3][1:4], 2, 1e4), atol=0)
+    np.testing.assert_allclose(K[7:10], rotate(ck[3][1:4], 6, 1e4), atol=0)
+    assert np.array_equal(V[3:6], cv[3][1:4]) and np.array_equal(V[7:10], cv[3][1:4])
+
+
+def test_to_slots_places_rows():
+    x = np.arange(12, dtype=np.float64).reshape(6, 2)
+    out = to_slots(x, [4, 5, 0, 1, 8, 9], 12)
+    assert np.array_equal(out[[4, 5, 0, 1, 8, 9]], x) and np.isnan(out[[2, 3, 6, 7, 10, 11]]).all()
