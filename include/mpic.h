@@ -1,0 +1,215 @@
+/*
+ * libmpic -- selective-recompute prefill for position-independent multimodal
+ * context caching, for one AMD MI355X (gfx950).
+ *
+ * The library implements the data-parallel hot path of the method: the linker
+ * that joins stored per-image KV caches and freshly computed rows into one
+ * request context (Sec. 3.1 item 5, Sec. 4.1, Fig. 7 steps 1-2), and selective
+ * attention of the recomputed tokens over that linked cache (Fig. 7 step 3,
+ * App. A).  The paper leaves positional embedding out of Fig. 7; here a stored key
+ * that was computed at chunk-local position t is moved to its global position by
+ * a rotary shift of its chunk's offset in the request.
+ *
+ * General conventions
+ *   - Plain C ABI.  Every call returns an int: MPIC_OK (0) or a negative
+ *     mpic_status.  Nothing throws or aborts across the boundary.
+ *   - All arguments are validated on the host first; a call that fails enqueues
+ *     no GPU work.
+ *   - Tensors are token-major, innermost dimension contiguous:
+ *     [tokens][heads][head_dim], element type given by mpic_config.dtype.
+ *   - The caller owns every data buffer and must keep it alive and unchanged
+ *     until the work enqueued on `stream` has completed.  The library owns what it
+ *     creates (context, plans, staging buffers, its side stream and events).
+ *   - `stream` arguments are hipStream_t values passed as void* (NULL = the
+ *     default stream).  Calls are stream-ordered and return without waiting.
+ *   - Pointers documented "device" must be device-accessible on the GPU that is
+ *     current when the call is made; pointers documented "host" are ordinary host
+ *     memory unless "pinned" is stated.
+ *   - A context and its plans may be used from one host thread at a time.
+ */
+#ifndef MPIC_H
+#define MPIC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct mpic_ctx mpic_ctx;   /* opaque: configuration, side stream, events, staging */
+typedef struct mpic_plan mpic_plan; /* opaque: host and device copies of the integer plan   */
+
+typedef enum mpic_status {
+  MPIC_OK = 0,
+  MPIC_ERR_INVALID = -1,     /* an argument violates the documented contract   */
+  MPIC_ERR_UNSUPPORTED = -2, /* valid request that this build has no kernel for */
+  MPIC_ERR_OOM = -3,         /* host or device allocation failed                */
+  MPIC_ERR_HIP = -4          /* a HIP runtime call failed (see mpic_last_error) */
+} mpic_status;
+
+typedef enum mpic_dtype { MPIC_F32 = 0, MPIC_BF16 = 1 } mpic_dtype;
+
+typedef struct mpic_config {
+  int32_t n_q_heads;        /* query heads Hq                                        */
+  int32_t n_kv_heads;       /* key/value heads Hkv; Hq % Hkv == 0 (grouped queries)  */
+  int32_t head_dim;         /* D; F32: 64 or 128, BF16: 128                          */
+  int32_t dtype;            /* mpic_dtype of Q, K, V, the context and the output     */
+  double rope_theta;        /* rotary base; pair i turns by shift * theta^(-2i/D)    */
+  int32_t rope_interleaved; /* 0: pairs (i, i+D/2) "rotate-half"; 1: pairs (2i,2i+1) */
+  int32_t page_size;        /* 0: contiguous context; >0: tokens per physical page   */
+} mpic_config;
+
+/* One segment of a request, in prompt order. */
+typedef struct mpic_segment {
+  int32_t kind;  /* 0 = text (always recomputed), 1 = cached chunk                       */
+  int32_t len;   /* tokens, >= 0                                                         */
+  int32_t chunk; /* kind 1: index into the srcs[] array given to mpic_assemble_kv        */
+  int32_t k;     /* kind 1: tokens recomputed at the head of the chunk; < 0 = default_k; */
+                 /*         >= len recomputes the whole chunk (a cache that is missing   */
+                 /*         or failed to load, Sec. 3.2)                                 */
+} mpic_segment;
+
+/* Stored cache of one chunk for the layer being assembled. */
+typedef struct mpic_chunk_src {
+  const void* k;   /* [len][Hkv][D], keys already rotated for chunk-local positions 0..len-1 */
+  const void* v;   /* [len][Hkv][D]                                                          */
+  int32_t len;     /* must equal the len of every segment that refers to this source         */
+  int32_t on_host; /* 0: device memory; 1: pinned host memory, staged over the side stream   */
+} mpic_chunk_src;
+
+/* Selectors for mpic_plan_get.  All arrays are int32. */
+enum {
+  MPIC_PLAN_CTX_OFF = 0,  /* [B+1]  prefix sums of request context lengths N_b               */
+  MPIC_PLAN_Q_OFF = 1,    /* [B+1]  prefix sums of recompute-set sizes Nq_b                  */
+  MPIC_PLAN_Q_POS = 2,    /* [Nq]   position id (inside its request) of each fresh row       */
+  MPIC_PLAN_Q_REQ = 3,    /* [Nq]   request of each fresh row                                */
+  MPIC_PLAN_SLOT_MAP = 4, /* [Nq]   physical context slot each fresh row is written to       */
+  MPIC_PLAN_SRC_INST = 5, /* [N]    chunk instance that feeds a position, -1 = fresh row     */
+  MPIC_PLAN_SRC_ROW = 6,  /* [N]    row inside that chunk, or index of the fresh row         */
+  MPIC_PLAN_DST_SLOT = 7, /* [N]    physical context slot of a position                      */
+  MPIC_PLAN_INST_SRC = 8, /* [n_inst] srcs[] index of each chunk instance                    */
+  MPIC_PLAN_INST_DELTA = 9,  /* [n_inst] rotary shift = position of the instance's first token */
+  MPIC_PLAN_INST_LEN = 10,   /* [n_inst] tokens                                                */
+  MPIC_PLAN_INST_K = 11,     /* [n_inst] effective k = min(k, len)                             */
+  MPIC_PLAN_INST_REQ = 12,   /* [n_inst] owning request                                        */
+  MPIC_PLAN_RUNS = 13,       /* [n_runs][4] (request, first fresh row, length, first position) */
+  MPIC_PLAN_ATTN_TILES = 14  /* [n_tiles][8] launch order of the attention kernel: (request,   */
+                             /* kv head, first flattened row, rows, keys, 0, 0, 0); flattened  */
+                             /* row = (fresh row - q_off[request]) * (Hq/Hkv) + head in group  */
+};
+
+/*
+ * Create a context.  Host only: no GPU call is made until the first
+ * mpic_assemble_kv / mpic_selective_attn, which binds the context to the GPU that
+ * is current at that moment.
+ * Errors: MPIC_ERR_INVALID (null pointer, non-positive sizes, Hq % Hkv != 0, odd
+ * head_dim, theta <= 0, page_size < 0), MPIC_ERR_UNSUPPORTED (dtype / head_dim).
+ */
+int mpic_create(mpic_ctx** out, const mpic_config* config);
+
+/* Destroy a context after all of its plans.  Waits for the side stream.  NULL is allowed. */
+void mpic_destroy(mpic_ctx* ctx);
+
+/*
+ * Build the integer plan of a batch of requests (Sec. 4.2: the recompute set is
+ * every text token plus the first k tokens of every chunk; Fig. 7 step 2: those
+ * rows replace the stored ones, every other row comes from its chunk).  Host only.
+ *
+ *   n_requests        B >= 1
+ *   seg_off  [B+1]    host; request b owns segs[seg_off[b] .. seg_off[b+1])
+ *   segs              host; see mpic_segment
+ *   default_k         >= 0
+ *   page_table        host, or NULL when config.page_size == 0.  Physical page ids
+ *                     (0 <= id < n_pool_pages), all requests concatenated.
+ *   page_table_off [B+1]  host; request b owns page_table[off[b] .. off[b+1]), which
+ *                     must cover ceil(N_b / page_size) pages.  No page id may be used
+ *                     twice inside the batch.
+ *   n_pool_pages      pages in the pool the tables index (ignored when contiguous)
+ *
+ * Contiguous layout: the context buffers hold the requests one after the other,
+ * request b at slots ctx_off[b] .. ctx_off[b+1).  Paged layout: position p of
+ * request b lives at slot table_b[p / page_size] * page_size + p % page_size.
+ * The plan can be reused for every layer of the batch.
+ * Errors: MPIC_ERR_INVALID for any violation above (negative len, bad kind, chunk
+ * index < 0, table too short, duplicate or out-of-range page id, totals >= 2^31).
+ */
+int mpic_plan_create(mpic_ctx* ctx, int32_t n_requests, const int32_t* seg_off,
+                     const mpic_segment* segs, int32_t default_k, const int32_t* page_table,
+                     const int32_t* page_table_off, int64_t n_pool_pages, mpic_plan** out);
+
+/* Borrow one host array of the plan; valid until mpic_plan_destroy. */
+int mpic_plan_get(const mpic_plan* plan, int32_t what, const int32_t** host_ptr, size_t* n);
+
+/*
+ * Borrow the rotary tables of the plan: cos and sin of shift * theta^(-2i/D),
+ * [n_inst][D/2] floats each, evaluated in double precision and rounded once.
+ */
+int mpic_plan_get_rope(const mpic_plan* plan, const float** cos_tab, const float** sin_tab,
+                       size_t* n);
+
+/* Destroy a plan (device copies included).  The caller must have synchronised every
+ * stream that still uses it.  NULL is allowed. */
+void mpic_plan_destroy(mpic_plan* plan);
+
+/*
+ * Link one layer's context (Sec. 3.1 item 5; Fig. 7 step 2; parallel transfer of
+ * Sec. 3.2 for sources that are not on the GPU).
+ * For every context position exactly one of:
+ *   - position in the recompute set:  K_ctx[slot] = fresh_k[row], V_ctx[slot] = fresh_v[row]
+ *   - otherwise (row t of chunk instance c): V_ctx[slot] = V_c[t] and
+ *     K_ctx[slot] = K_c[t] rotated head by head by the instance's shift
+ *     (pair (x, y) -> (x cos - y sin, x sin + y cos)), computed in fp32 and rounded
+ *     once to the storage type.
+ * Slots that belong to no position (tail of a last page, unused pool pages) are not
+ * touched.
+ *
+ *   srcs [n_srcs]     host array; every chunk index used by the plan must be < n_srcs
+ *                     and srcs[i].len must match.  k / v: device, or pinned host when
+ *                     on_host != 0 (copied on the library's side stream into library
+ *                     staging, overlapped with the linking of other rows).
+ *   fresh_k, fresh_v  device [n_fresh_rows][Hkv][D]; may be NULL only if the plan
+ *                     has no fresh row.  Keys already carry their global position.
+ *   n_fresh_rows      must equal the plan's total recompute-set size
+ *   k_ctx, v_ctx      device [n_ctx_slots][Hkv][D], written
+ *   n_ctx_slots       slots in k_ctx / v_ctx; must cover every slot of the plan
+ *                     (contiguous: >= total N; paged: >= n_pool_pages * page_size)
+ * Errors: MPIC_ERR_INVALID, MPIC_ERR_OOM (staging), MPIC_ERR_HIP.
+ */
+int mpic_assemble_kv(mpic_ctx* ctx, mpic_plan* plan, const mpic_chunk_src* srcs, int32_t n_srcs,
+                     const void* fresh_k, const void* fresh_v, int64_t n_fresh_rows, void* k_ctx,
+                     void* v_ctx, int64_t n_ctx_slots, void* stream);
+
+/*
+ * Selective attention (Fig. 7 step 3; App. A): for every fresh row r at position p
+ * of its request and every query head h (kv head h / (Hq/Hkv)):
+ *   s_j = softmax_scale * <fresh_q[r][h], K_ctx[slot(j)][kv]>   for positions j = 0..p
+ *   out[r][h] = sum_j softmax(s)_j * V_ctx[slot(j)][kv]
+ *   lse[r][h] = log sum_j exp(s_j)                               (optional)
+ * BF16: products on the matrix cores with fp32 accumulation, softmax in fp32,
+ * probabilities rounded to bf16 before the second product, one final rounding of
+ * out.  F32: fp32 throughout.
+ *
+ *   fresh_q           device [n_fresh_rows][Hq][D], already rotated for its position
+ *   k_ctx, v_ctx      device [n_ctx_slots][Hkv][D] as written by mpic_assemble_kv
+ *   softmax_scale     finite, > 0 (1/sqrt(D) for the definition of App. A)
+ *   out               device [n_fresh_rows][Hq][D], written
+ *   lse               device float [n_fresh_rows][Hq], written; may be NULL
+ * A plan with no fresh row is a no-op that returns MPIC_OK.
+ * Errors: MPIC_ERR_INVALID, MPIC_ERR_HIP.
+ */
+int mpic_selective_attn(mpic_ctx* ctx, mpic_plan* plan, const void* fresh_q, int64_t n_fresh_rows,
+                        const void* k_ctx, const void* v_ctx, int64_t n_ctx_slots,
+                        double softmax_scale, void* out, float* lse, void* stream);
+
+/* Static description of a status code. */
+const char* mpic_strerror(int status);
+
+/* Detail of the last failing call on this context (empty string if none).  The
+ * pointer stays valid until the next call on the context. */
+const char* mpic_last_error(const mpic_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MPIC_H */

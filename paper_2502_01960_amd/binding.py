@@ -1,0 +1,246 @@
+"""ctypes binding of libmpic.so.  The functions carry the names of the C entry points
+declared in include/mpic.h and only marshal arguments; Context / Plan are thin
+owners of the opaque handles.  There is no fallback: a missing library raises."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+MPIC_F32, MPIC_BF16 = 0, 1
+
+PLAN_FIELDS = dict(ctx_off=0, q_off=1, q_pos=2, q_req=3, slot_map=4, src_inst=5, src_row=6,
+                   dst_slot=7, inst_src=8, inst_delta=9, inst_len=10, inst_k=11, inst_req=12,
+                   runs=13, attn_tiles=14)
+
+
+class MpicError(RuntimeError):
+    def __init__(self, status, detail=""):
+        self.status = status
+        super().__init__(f"libmpic status {status} ({mpic_strerror(status)}): {detail}")
+
+
+class _Config(C.Structure):
+    _fields_ = [("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("dtype", C.c_int32), ("rope_theta", C.c_double), ("rope_interleaved", C.c_int32),
+                ("page_size", C.c_int32)]
+
+
+class _Segment(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("len", C.c_int32), ("chunk", C.c_int32), ("k", C.c_int32)]
+
+
+class _ChunkSrc(C.Structure):
+    _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("len", C.c_int32), ("on_host", C.c_int32)]
+
+
+def lib_path():
+    return os.path.join(_HERE, "libmpic.so")
+
+
+_lib = None
+
+
+def load_library():
+    """Load libmpic.so (built by paper_2502_01960_amd/build.py).  Raises if it is absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = lib_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} not found: build it with `python paper_2502_01960_amd/build.py`")
+    lib = C.CDLL(path)
+    vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    lib.mpic_create.argtypes = [C.POINTER(vp), C.POINTER(_Config)]
+    lib.mpic_create.restype = C.c_int
+    lib.mpic_destroy.argtypes = [vp]
+    lib.mpic_destroy.restype = None
+    lib.mpic_plan_create.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(_Segment), i32,
+                                     C.POINTER(i32), C.POINTER(i32), i64, C.POINTER(vp)]
+    lib.mpic_plan_create.restype = C.c_int
+    lib.mpic_plan_get.argtypes = [vp, i32, C.POINTER(C.POINTER(i32)), C.POINTER(C.c_size_t)]
+    lib.mpic_plan_get.restype = C.c_int
+    lib.mpic_plan_get_rope.argtypes = [vp, C.POINTER(C.POINTER(C.c_float)),
+                                       C.POINTER(C.POINTER(C.c_float)), C.POINTER(C.c_size_t)]
+    lib.mpic_plan_get_rope.restype = C.c_int
+    lib.mpic_plan_destroy.argtypes = [vp]
+    lib.mpic_plan_destroy.restype = None
+    lib.mpic_assemble_kv.argtypes = [vp, vp, C.POINTER(_ChunkSrc), i32, vp, vp, i64, vp, vp, i64, vp]
+    lib.mpic_assemble_kv.restype = C.c_int
+    lib.mpic_selective_attn.argtypes = [vp, vp, vp, i64, vp, vp, i64, C.c_double, vp, vp, vp]
+    lib.mpic_selective_attn.restype = C.c_int
+    lib.mpic_strerror.argtypes = [C.c_int]
+    lib.mpic_strerror.restype = C.c_char_p
+    lib.mpic_last_error.argtypes = [vp]
+    lib.mpic_last_error.restype = C.c_char_p
+    _lib = lib
+    return lib
+
+
+# ---------------------------------------------------------------- C entry points
+def mpic_strerror(status):
+    return load_library().mpic_strerror(int(status)).decode()
+
+
+def mpic_last_error(ctx):
+    return load_library().mpic_last_error(ctx).decode()
+
+
+def _check(rc, ctx=None):
+    if rc != 0:
+        raise MpicError(rc, mpic_last_error(ctx) if ctx else "")
+
+
+def mpic_create(n_q_heads, n_kv_heads, head_dim, dtype, rope_theta, rope_interleaved=0, page_size=0):
+    cfg = _Config(n_q_heads, n_kv_heads, head_dim, dtype, rope_theta, rope_interleaved, page_size)
+    h = C.c_void_p()
+    _check(load_library().mpic_create(C.byref(h), C.byref(cfg)))
+    return h
+
+
+def mpic_destroy(ctx):
+    load_library().mpic_destroy(ctx)
+
+
+def _i32_array(values):
+    arr = np.ascontiguousarray(values, dtype=np.int32)
+    return arr, arr.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+def mpic_plan_create(ctx, requests, default_k, page_tables=None, n_pool_pages=0):
+    """requests: list of segment lists, ("text", L) / ("chunk", src, L, k or None)."""
+    seg_off, flat = [0], []
+    for segs in requests:
+        for s in segs:
+            if s[0] == "text":
+                flat.append(_Segment(0, s[1], 0, -1))
+            elif s[0] == "chunk":
+                flat.append(_Segment(1, s[2], s[1], -1 if s[3] is None else s[3]))
+            else:
+                raise ValueError(f"unknown segment kind {s[0]!r}")
+        seg_off.append(len(flat))
+    segs_c = (_Segment * max(1, len(flat)))(*flat)
+    off_keep, off_p = _i32_array(seg_off)
+    if page_tables is not None:
+        pt_off = np.cumsum([0] + [len(t) for t in page_tables])
+        pt_keep, pt_p = _i32_array(np.concatenate([np.asarray(t, dtype=np.int32) for t in page_tables])
+                                   if len(page_tables) else [])
+        pto_keep, pto_p = _i32_array(pt_off)
+    else:
+        pt_p = pto_p = None
+    h = C.c_void_p()
+    rc = load_library().mpic_plan_create(ctx, len(requests), off_p, segs_c, default_k, pt_p, pto_p,
+                                         n_pool_pages, C.byref(h))
+    _check(rc, ctx)
+    return h
+
+
+def mpic_plan_get(plan, what):
+    """Copy of one int32 array of the plan (runs -> [n][4], attn_tiles -> [n][8])."""
+    code = PLAN_FIELDS[what] if isinstance(what, str) else int(what)
+    p = C.POINTER(C.c_int32)()
+    n = C.c_size_t()
+    _check(load_library().mpic_plan_get(plan, code, C.byref(p), C.byref(n)))
+    out = np.ctypeslib.as_array(p, shape=(n.value,)).copy() if n.value else np.zeros(0, np.int32)
+    if code == PLAN_FIELDS["runs"]:
+        out = out.reshape(-1, 4)
+    elif code == PLAN_FIELDS["attn_tiles"]:
+        out = out.reshape(-1, 8)
+    return out
+
+
+def mpic_plan_get_rope(plan):
+    c, s, n = C.POINTER(C.c_float)(), C.POINTER(C.c_float)(), C.c_size_t()
+    _check(load_library().mpic_plan_get_rope(plan, C.byref(c), C.byref(s), C.byref(n)))
+    if not n.value:
+        return np.zeros(0, np.float32), np.zeros(0, np.float32)
+    return (np.ctypeslib.as_array(c, shape=(n.value,)).copy(),
+            np.ctypeslib.as_array(s, shape=(n.value,)).copy())
+
+
+def mpic_plan_destroy(plan):
+    load_library().mpic_plan_destroy(plan)
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    return C.c_void_p(getattr(stream, "cuda_stream", stream))
+
+
+def mpic_assemble_kv(ctx, plan, srcs, fresh_k, fresh_v, k_ctx, v_ctx, stream=None):
+    """srcs: list of (k_tensor, v_tensor) per source id; a pinned CPU tensor is staged
+    by the library, a device tensor is read in place.  Tensors are torch tensors."""
+    arr = (_ChunkSrc * max(1, len(srcs)))()
+    for i, (k, v) in enumerate(srcs):
+        if k is None:
+            arr[i] = _ChunkSrc(None, None, 0, 0)
+            continue
+        on_host = 0 if k.is_cuda else 1
+        if on_host and not (k.is_pinned() and v.is_pinned()):
+            raise ValueError("host chunk sources must be pinned")
+        arr[i] = _ChunkSrc(k.data_ptr(), v.data_ptr(), k.shape[0], on_host)
+    n_fresh = 0 if fresh_k is None else fresh_k.shape[0]
+    rc = load_library().mpic_assemble_kv(ctx, plan, arr, len(srcs), _ptr(fresh_k), _ptr(fresh_v), n_fresh,
+                                         _ptr(k_ctx), _ptr(v_ctx), k_ctx.shape[0], _stream(stream))
+    _check(rc, ctx)
+
+
+def mpic_selective_attn(ctx, plan, fresh_q, k_ctx, v_ctx, softmax_scale, out, lse=None, stream=None):
+    n_fresh = 0 if fresh_q is None else fresh_q.shape[0]
+    rc = load_library().mpic_selective_attn(ctx, plan, _ptr(fresh_q), n_fresh, _ptr(k_ctx), _ptr(v_ctx),
+                                            k_ctx.shape[0], float(softmax_scale), _ptr(out), _ptr(lse),
+                                            _stream(stream))
+    _check(rc, ctx)
+
+
+# ---------------------------------------------------------------- handle owners
+class Context:
+    def __init__(self, n_q_heads, n_kv_heads, head_dim, dtype, rope_theta, rope_interleaved=0, page_size=0):
+        self.handle = mpic_create(n_q_heads, n_kv_heads, head_dim, dtype, rope_theta, rope_interleaved, page_size)
+        self.n_q_heads, self.n_kv_heads, self.head_dim = n_q_heads, n_kv_heads, head_dim
+        self.dtype, self.page_size = dtype, page_size
+
+    def close(self):
+        if self.handle is not None:
+            mpic_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Plan:
+    def __init__(self, ctx: Context, requests, default_k, page_tables=None, n_pool_pages=0):
+        self.ctx = ctx  # keeps the context alive
+        self.handle = mpic_plan_create(ctx.handle, requests, default_k, page_tables, n_pool_pages)
+
+    def get(self, what):
+        return mpic_plan_get(self.handle, what)
+
+    def rope(self):
+        return mpic_plan_get_rope(self.handle)
+
+    def as_dict(self):
+        return {k: self.get(k) for k in PLAN_FIELDS}
+
+    def close(self):
+        if self.handle is not None:
+            mpic_plan_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

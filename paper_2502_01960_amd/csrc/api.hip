@@ -1,0 +1,310 @@
+// GPU-facing entry points of libmpic: argument validation, device copies of the
+// plan, the side-stream transfer of host-resident chunk caches (Sec. 3.2: transfer
+// and linking proceed concurrently) and the kernel launches.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+
+#include "common.h"
+
+namespace mpic {
+namespace {
+
+int bind_device(mpic_ctx* ctx) {
+  int dev = -1;
+  MPIC_HIP(ctx, hipGetDevice(&dev));
+  if (ctx->device < 0) {
+    ctx->device = dev;
+    MPIC_HIP(ctx, hipStreamCreateWithFlags(&ctx->side_stream, hipStreamNonBlocking));
+    MPIC_HIP(ctx, hipEventCreateWithFlags(&ctx->ev_main, hipEventDisableTiming));
+  } else if (ctx->device != dev) {
+    return fail(ctx, MPIC_ERR_INVALID, "context is bound to another GPU than the current one");
+  }
+  return MPIC_OK;
+}
+
+template <typename T>
+size_t padded(size_t n) {
+  return (n * sizeof(T) + 255) / 256 * 256;
+}
+
+// Copy the integer maps, rotary tables and tile list to the GPU (once per plan).
+int upload_plan(mpic_ctx* ctx, mpic_plan* p) {
+  if (p->dev.block) {
+    if (p->dev.device != ctx->device) return fail(ctx, MPIC_ERR_INVALID, "plan lives on another GPU");
+    return MPIC_OK;
+  }
+  const size_t n = p->n_ctx, nq = p->n_q, B = p->n_requests;
+  size_t total = 3 * padded<int32_t>(n) + padded<int32_t>(nq) + 2 * padded<int32_t>(B + 1) +
+                 2 * padded<float>(p->rope_cos.size()) + padded<AttnTile>(p->tiles.size()) + 256;
+  char* base = nullptr;
+  hipError_t e = hipMalloc(reinterpret_cast<void**>(&base), total);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return fail(ctx, MPIC_ERR_OOM, "device allocation of the plan failed");
+  }
+  size_t at = 0;
+  auto put = [&](const void* src, size_t bytes, size_t reserve) -> void* {
+    void* dst = base + at;
+    if (bytes) e = hipMemcpy(dst, src, bytes, hipMemcpyHostToDevice);
+    at += reserve;
+    return dst;
+  };
+  PlanDevice d;
+  e = hipSuccess;
+  d.src_inst = static_cast<int32_t*>(put(p->src_inst.data(), n * 4, padded<int32_t>(n)));
+  if (e == hipSuccess) d.src_row = static_cast<int32_t*>(put(p->src_row.data(), n * 4, padded<int32_t>(n)));
+  if (e == hipSuccess) d.dst_slot = static_cast<int32_t*>(put(p->dst_slot.data(), n * 4, padded<int32_t>(n)));
+  if (e == hipSuccess) d.q_pos = static_cast<int32_t*>(put(p->q_pos.data(), nq * 4, padded<int32_t>(nq)));
+  if (e == hipSuccess) d.q_off = static_cast<int32_t*>(put(p->q_off.data(), (B + 1) * 4, padded<int32_t>(B + 1)));
+  if (e == hipSuccess) d.ctx_off = static_cast<int32_t*>(put(p->ctx_off.data(), (B + 1) * 4, padded<int32_t>(B + 1)));
+  const size_t nr = p->rope_cos.size();
+  if (e == hipSuccess) d.rope_cos = static_cast<float*>(put(p->rope_cos.data(), nr * 4, padded<float>(nr)));
+  if (e == hipSuccess) d.rope_sin = static_cast<float*>(put(p->rope_sin.data(), nr * 4, padded<float>(nr)));
+  if (e == hipSuccess)
+    d.tiles = static_cast<AttnTile*>(put(p->tiles.data(), p->tiles.size() * sizeof(AttnTile),
+                                         padded<AttnTile>(p->tiles.size())));
+  if (e != hipSuccess) {
+    (void)hipFree(base);
+    return fail_hip(ctx, e, "upload of the plan");
+  }
+  d.block = base;
+  d.device = ctx->device;
+  p->dev = d;
+  return MPIC_OK;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+}  // namespace
+}  // namespace mpic
+
+using mpic::fail;
+
+extern "C" void mpic_destroy(mpic_ctx* ctx) {
+  if (!ctx) return;
+  if (ctx->device >= 0) {
+    int cur = -1;
+    (void)hipGetDevice(&cur);
+    (void)hipSetDevice(ctx->device);
+    if (ctx->side_stream) {
+      (void)hipStreamSynchronize(ctx->side_stream);
+      (void)hipStreamDestroy(ctx->side_stream);
+    }
+    if (ctx->ev_main) (void)hipEventDestroy(ctx->ev_main);
+    for (hipEvent_t ev : ctx->ev_copy) (void)hipEventDestroy(ev);
+    if (ctx->staging) (void)hipFree(ctx->staging);
+    if (cur >= 0) (void)hipSetDevice(cur);
+  }
+  delete ctx;
+}
+
+extern "C" void mpic_plan_destroy(mpic_plan* plan) {
+  if (!plan) return;
+  if (plan->dev.block) {
+    int cur = -1;
+    (void)hipGetDevice(&cur);
+    (void)hipSetDevice(plan->dev.device);
+    (void)hipFree(plan->dev.block);
+    if (cur >= 0) (void)hipSetDevice(cur);
+  }
+  delete plan;
+}
+
+extern "C" int mpic_assemble_kv(mpic_ctx* ctx, mpic_plan* plan, const mpic_chunk_src* srcs,
+                                int32_t n_srcs, const void* fresh_k, const void* fresh_v,
+                                int64_t n_fresh_rows, void* k_ctx, void* v_ctx, int64_t n_ctx_slots,
+                                void* stream_) {
+  if (!ctx) return MPIC_ERR_INVALID;
+  if (!plan || plan->ctx != ctx) return fail(ctx, MPIC_ERR_INVALID, "assemble_kv: plan does not belong to this context");
+  if (n_fresh_rows != plan->n_q) return fail(ctx, MPIC_ERR_INVALID, "assemble_kv: n_fresh_rows differs from the plan's recompute set");
+  if (plan->n_q > 0 && (!fresh_k || !fresh_v)) return fail(ctx, MPIC_ERR_INVALID, "assemble_kv: fresh_k / fresh_v missing");
+  if (plan->n_ctx == 0) return MPIC_OK;
+  if (!k_ctx || !v_ctx) return fail(ctx, MPIC_ERR_INVALID, "assemble_kv: k_ctx / v_ctx missing");
+  if (n_ctx_slots <= plan->max_slot) return fail(ctx, MPIC_ERR_INVALID, "assemble_kv: context buffers smaller than the plan's largest slot");
+  if (!mpic::aligned16(fresh_k) || !mpic::aligned16(fresh_v) || !mpic::aligned16(k_ctx) || !mpic::aligned16(v_ctx))
+    return fail(ctx, MPIC_ERR_INVALID, "assemble_kv: buffers must be 16-byte aligned");
+  const size_t n_inst = plan->inst_src.size();
+  if (n_inst > 0 && (!srcs || n_srcs <= plan->max_src)) return fail(ctx, MPIC_ERR_INVALID, "assemble_kv: srcs does not cover every chunk index of the plan");
+  bool any_host = false;
+  for (size_t i = 0; i < n_inst; ++i) {
+    const mpic_chunk_src& s = srcs[plan->inst_src[i]];
+    if (s.len != plan->inst_len[i]) return fail(ctx, MPIC_ERR_INVALID, "assemble_kv: chunk source length differs from its segment");
+    if (plan->inst_k[i] < plan->inst_len[i]) {  // some rows are actually read
+      if (!s.k || !s.v || !mpic::aligned16(s.k) || !mpic::aligned16(s.v))
+        return fail(ctx, MPIC_ERR_INVALID, "assemble_kv: chunk source pointer missing or not 16-byte aligned");
+      any_host = any_host || s.on_host != 0;
+    }
+  }
+  int rc = mpic::bind_device(ctx);
+  if (rc != MPIC_OK) return rc;
+  rc = mpic::upload_plan(ctx, plan);
+  if (rc != MPIC_OK) return rc;
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  const mpic_config& c = ctx->cfg;
+  const size_t elem = c.dtype == MPIC_F32 ? 4 : 2;
+  const size_t row_bytes = static_cast<size_t>(c.n_kv_heads) * c.head_dim * elem;
+
+  // ---- host-resident sources: where each lands in device staging ----
+  constexpr int kGroup = 4;  // sources per transfer group (one event each)
+  std::vector<int32_t> host_srcs;              // distinct host sources in order of first use
+  std::vector<size_t> stage_off(n_srcs > 0 ? n_srcs : 0, SIZE_MAX);
+  size_t need = 0;
+  if (any_host) {
+    for (size_t i = 0; i < n_inst; ++i) {
+      const int32_t s = plan->inst_src[i];
+      if (srcs[s].on_host && plan->inst_k[i] < plan->inst_len[i] && stage_off[s] == SIZE_MAX) {
+        stage_off[s] = need;
+        need += 2 * static_cast<size_t>(srcs[s].len) * row_bytes;
+        host_srcs.push_back(s);
+      }
+    }
+    if (need > ctx->staging_bytes) {
+      // growing the staging area is rare (first call / larger batch): drain and reallocate
+      MPIC_HIP(ctx, hipStreamSynchronize(ctx->side_stream));
+      MPIC_HIP(ctx, hipStreamSynchronize(stream));
+      if (ctx->staging) MPIC_HIP(ctx, hipFree(ctx->staging));
+      ctx->staging = nullptr;
+      ctx->staging_bytes = 0;
+      hipError_t e = hipMalloc(&ctx->staging, need);
+      if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(ctx, MPIC_ERR_OOM, "assemble_kv: device staging allocation failed");
+      }
+      ctx->staging_bytes = need;
+    }
+    const size_t n_groups = (host_srcs.size() + kGroup - 1) / kGroup;
+    while (ctx->ev_copy.size() < n_groups) {
+      hipEvent_t ev;
+      MPIC_HIP(ctx, hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+      ctx->ev_copy.push_back(ev);
+    }
+    // staging may still be read by linking work enqueued earlier on `stream`
+    MPIC_HIP(ctx, hipEventRecord(ctx->ev_main, stream));
+    MPIC_HIP(ctx, hipStreamWaitEvent(ctx->side_stream, ctx->ev_main, 0));
+    for (size_t i = 0; i < host_srcs.size(); ++i) {
+      const mpic_chunk_src& s = srcs[host_srcs[i]];
+      const size_t bytes = static_cast<size_t>(s.len) * row_bytes;
+      char* dst = static_cast<char*>(ctx->staging) + stage_off[host_srcs[i]];
+      MPIC_HIP(ctx, hipMemcpyAsync(dst, s.k, bytes, hipMemcpyHostToDevice, ctx->side_stream));
+      MPIC_HIP(ctx, hipMemcpyAsync(dst + bytes, s.v, bytes, hipMemcpyHostToDevice, ctx->side_stream));
+      if ((i + 1) % kGroup == 0 || i + 1 == host_srcs.size())
+        MPIC_HIP(ctx, hipEventRecord(ctx->ev_copy[i / kGroup], ctx->side_stream));
+    }
+  }
+
+  mpic::AssembleArgs a{};
+  a.src_inst = plan->dev.src_inst;
+  a.src_row = plan->dev.src_row;
+  a.dst_slot = plan->dev.dst_slot;
+  a.rope_cos = plan->dev.rope_cos;
+  a.rope_sin = plan->dev.rope_sin;
+  a.fresh_k = fresh_k;
+  a.fresh_v = fresh_v;
+  a.k_ctx = k_ctx;
+  a.v_ctx = v_ctx;
+  a.n_kv_heads = c.n_kv_heads;
+  a.head_dim = c.head_dim;
+  a.interleaved = c.rope_interleaved;
+
+  auto inst_first_pos = [&](size_t i) -> int64_t {
+    return static_cast<int64_t>(plan->ctx_off[plan->inst_req[i]]) + plan->inst_delta[i];
+  };
+  // Pass 1: fresh rows and device-resident chunks, at most kMaxInstPerLaunch instances per
+  // launch (their source pointers travel as kernel arguments).  Host-resident instances
+  // have a null entry and are skipped here.
+  for (size_t i0 = 0; i0 == 0 || i0 < n_inst; i0 += mpic::kMaxInstPerLaunch) {
+    const size_t i1 = std::min(n_inst, i0 + mpic::kMaxInstPerLaunch);
+    mpic::AssembleSrcTable tab{};
+    for (size_t i = i0; i < i1; ++i) {
+      const mpic_chunk_src& s = srcs[plan->inst_src[i]];
+      const bool deferred = s.on_host && plan->inst_k[i] < plan->inst_len[i];
+      tab.k[i - i0] = deferred ? nullptr : s.k;
+      tab.v[i - i0] = deferred ? nullptr : s.v;
+    }
+    a.pos_begin = i0 == 0 ? 0 : inst_first_pos(i0);
+    a.pos_end = i1 < n_inst ? inst_first_pos(i1) : plan->n_ctx;
+    a.inst_base = static_cast<int32_t>(i0);
+    a.n_inst = static_cast<int32_t>(i1 - i0);
+    a.skip_fresh = 0;
+    MPIC_HIP(ctx, mpic::launch_assemble(c.dtype, a, tab, stream));
+  }
+  // Pass 2: one launch per chunk instance fed from staging, as soon as its transfer group
+  // has landed.  Only that instance's rows are touched.
+  if (any_host) {
+    std::vector<int32_t> group_of(n_srcs, -1);
+    for (size_t i = 0; i < host_srcs.size(); ++i) group_of[host_srcs[i]] = static_cast<int32_t>(i / kGroup);
+    // instances ordered by the transfer group of their source
+    std::vector<size_t> order;
+    for (size_t i = 0; i < n_inst; ++i) {
+      const int32_t s = plan->inst_src[i];
+      if (srcs[s].on_host && plan->inst_k[i] < plan->inst_len[i]) order.push_back(i);
+    }
+    std::stable_sort(order.begin(), order.end(), [&](size_t x, size_t y) {
+      return group_of[plan->inst_src[x]] < group_of[plan->inst_src[y]];
+    });
+    int32_t waited = -1;
+    for (size_t i : order) {
+      const int32_t s = plan->inst_src[i];
+      if (group_of[s] > waited) {
+        waited = group_of[s];
+        MPIC_HIP(ctx, hipStreamWaitEvent(stream, ctx->ev_copy[waited], 0));
+      }
+      mpic::AssembleSrcTable tab{};
+      const size_t bytes = static_cast<size_t>(srcs[s].len) * row_bytes;
+      tab.k[0] = static_cast<char*>(ctx->staging) + stage_off[s];
+      tab.v[0] = static_cast<char*>(ctx->staging) + stage_off[s] + bytes;
+      a.pos_begin = inst_first_pos(i) + plan->inst_k[i];
+      a.pos_end = inst_first_pos(i) + plan->inst_len[i];
+      a.inst_base = static_cast<int32_t>(i);
+      a.n_inst = 1;
+      a.skip_fresh = 1;
+      MPIC_HIP(ctx, mpic::launch_assemble(c.dtype, a, tab, stream));
+    }
+  }
+  return MPIC_OK;
+}
+
+extern "C" int mpic_selective_attn(mpic_ctx* ctx, mpic_plan* plan, const void* fresh_q,
+                                   int64_t n_fresh_rows, const void* k_ctx, const void* v_ctx,
+                                   int64_t n_ctx_slots, double softmax_scale, void* out, float* lse,
+                                   void* stream_) {
+  if (!ctx) return MPIC_ERR_INVALID;
+  if (!plan || plan->ctx != ctx) return fail(ctx, MPIC_ERR_INVALID, "selective_attn: plan does not belong to this context");
+  if (n_fresh_rows != plan->n_q) return fail(ctx, MPIC_ERR_INVALID, "selective_attn: n_fresh_rows differs from the plan's recompute set");
+  if (!(softmax_scale > 0.0) || !std::isfinite(softmax_scale)) return fail(ctx, MPIC_ERR_INVALID, "selective_attn: softmax_scale must be finite and positive");
+  if (plan->n_q == 0) return MPIC_OK;
+  if (!fresh_q || !k_ctx || !v_ctx || !out) return fail(ctx, MPIC_ERR_INVALID, "selective_attn: null buffer");
+  if (n_ctx_slots <= plan->max_slot) return fail(ctx, MPIC_ERR_INVALID, "selective_attn: context buffers smaller than the plan's largest slot");
+  if (!mpic::aligned16(fresh_q) || !mpic::aligned16(k_ctx) || !mpic::aligned16(v_ctx) || !mpic::aligned16(out))
+    return fail(ctx, MPIC_ERR_INVALID, "selective_attn: buffers must be 16-byte aligned");
+  int rc = mpic::bind_device(ctx);
+  if (rc != MPIC_OK) return rc;
+  rc = mpic::upload_plan(ctx, plan);
+  if (rc != MPIC_OK) return rc;
+  const mpic_config& c = ctx->cfg;
+  mpic::AttnArgs a{};
+  a.tiles = plan->dev.tiles;
+  a.n_tiles = static_cast<int32_t>(plan->tiles.size());
+  a.q_pos = plan->dev.q_pos;
+  a.q_off = plan->dev.q_off;
+  a.ctx_off = plan->dev.ctx_off;
+  a.dst_slot = plan->dev.dst_slot;
+  a.q = fresh_q;
+  a.k_ctx = k_ctx;
+  a.v_ctx = v_ctx;
+  a.out = out;
+  a.lse = lse;
+  a.scale = static_cast<float>(softmax_scale);
+  a.n_q_heads = c.n_q_heads;
+  a.n_kv_heads = c.n_kv_heads;
+  a.head_dim = c.head_dim;
+  a.n_requests = plan->n_requests;
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  if (c.dtype == MPIC_F32) {
+    MPIC_HIP(ctx, mpic::launch_attn_f32(a, plan->n_q, stream));
+  } else {
+    MPIC_HIP(ctx, mpic::launch_attn_bf16(a, stream));
+  }
+  return MPIC_OK;
+}

@@ -1,0 +1,160 @@
+// KV linking kernel of libmpic (gfx950).
+//
+// Fig. 7 step 2 / Sec. 4.1: rows of the recompute set are replaced by the fresh
+// K/V, every other context row is taken from the stored cache of its image chunk
+// (Sec. 3.1 item 5).  Stored keys are moved from chunk-local to global positions by
+// a rotary shift of the chunk's offset; values are copied.  One launch covers a
+// range of batch-flattened context positions: gather, rotation and scatter are fused
+// and every destination row has exactly one source, so there is no ordering hazard.
+//
+// The kernel is bandwidth bound (3 flops per key element): each thread moves four
+// 16-byte units (a low/high pair of a key head and two value units), all loads are
+// issued before the first store, and consecutive lanes touch consecutive 16-byte
+// units of a row.
+#include "common.h"
+
+namespace mpic {
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+template <typename T>
+struct Unit;  // 16 bytes of storage type T and its fp32 image
+
+template <>
+struct Unit<float> {
+  static constexpr int kElems = 4;
+  using Raw = f32x4;
+  using Wide = f32x4;
+  __device__ static Wide widen(Raw r) { return r; }
+  __device__ static Raw narrow(Wide w) { return w; }
+};
+
+template <>
+struct Unit<__bf16> {
+  static constexpr int kElems = 8;
+  using Raw = bf16x8;
+  using Wide = f32x8;
+  __device__ static Wide widen(Raw r) { return __builtin_convertvector(r, Wide); }
+  __device__ static Raw narrow(Wide w) { return __builtin_convertvector(w, Raw); }  // round to nearest even
+};
+
+template <typename T, bool kInterleaved>
+__global__ __launch_bounds__(256) void assemble_kernel(AssembleArgs a, AssembleSrcTable tab) {
+  using U = Unit<T>;
+  using Raw = typename U::Raw;
+  using Wide = typename U::Wide;
+  constexpr int E = U::kElems;
+  const int D = a.head_dim;
+  const int half = D / 2;
+  const int units_per_half = half / E;                     // 16-byte units in half a head
+  const int pairs_per_row = a.n_kv_heads * units_per_half;  // threads per context row
+  const int64_t row_elems = static_cast<int64_t>(a.n_kv_heads) * D;
+
+  const int64_t w = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  const int64_t pos = a.pos_begin + w / pairs_per_row;
+  if (pos >= a.pos_end) return;
+  const int u = static_cast<int>(w % pairs_per_row);
+
+  const int inst = a.src_inst[pos];
+  const int64_t srow = a.src_row[pos];
+  const int64_t slot = a.dst_slot[pos];
+
+  const T* ksrc;
+  const T* vsrc;
+  if (inst < 0) {
+    if (a.skip_fresh) return;
+    ksrc = static_cast<const T*>(a.fresh_k) + srow * row_elems;
+    vsrc = static_cast<const T*>(a.fresh_v) + srow * row_elems;
+  } else {
+    const T* kt = static_cast<const T*>(tab.k[inst - a.inst_base]);
+    const T* vt = static_cast<const T*>(tab.v[inst - a.inst_base]);
+    if (kt == nullptr) return;  // source still in flight: a later launch links this row
+    ksrc = kt + srow * row_elems;
+    vsrc = vt + srow * row_elems;
+  }
+  T* kdst = static_cast<T*>(a.k_ctx) + slot * row_elems;
+  T* vdst = static_cast<T*>(a.v_ctx) + slot * row_elems;
+
+  // element offsets of this thread's two units inside the row
+  int e0, e1;   // key units
+  int c0;       // first rotary pair index of unit e0 (pair index inside a head)
+  if (kInterleaved) {
+    e0 = u * E;
+    e1 = (u + pairs_per_row) * E;
+    c0 = (e0 % D) / 2;
+  } else {
+    const int head = u / units_per_half;
+    c0 = (u % units_per_half) * E;
+    e0 = head * D + c0;
+    e1 = e0 + half;
+  }
+  const int v0 = u * E, v1 = (u + pairs_per_row) * E;
+
+  const Raw k0 = *reinterpret_cast<const Raw*>(ksrc + e0);
+  const Raw k1 = *reinterpret_cast<const Raw*>(ksrc + e1);
+  const Raw w0 = *reinterpret_cast<const Raw*>(vsrc + v0);
+  const Raw w1 = *reinterpret_cast<const Raw*>(vsrc + v1);
+
+  Raw o0 = k0, o1 = k1;
+  if (inst >= 0) {
+    const float* ct = a.rope_cos + static_cast<int64_t>(inst) * half;
+    const float* st = a.rope_sin + static_cast<int64_t>(inst) * half;
+    const Wide x0 = U::widen(k0), x1 = U::widen(k1);
+    Wide y0, y1;
+    if (kInterleaved) {
+      const int c1 = (e1 % D) / 2;
+#pragma unroll
+      for (int i = 0; i < E / 2; ++i) {
+        const float ca = ct[c0 + i], sa = st[c0 + i];
+        const float cb = ct[c1 + i], sb = st[c1 + i];
+        y0[2 * i] = x0[2 * i] * ca - x0[2 * i + 1] * sa;
+        y0[2 * i + 1] = x0[2 * i] * sa + x0[2 * i + 1] * ca;
+        y1[2 * i] = x1[2 * i] * cb - x1[2 * i + 1] * sb;
+        y1[2 * i + 1] = x1[2 * i] * sb + x1[2 * i + 1] * cb;
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < E; ++i) {
+        const float c = ct[c0 + i], s = st[c0 + i];
+        y0[i] = x0[i] * c - x1[i] * s;
+        y1[i] = x0[i] * s + x1[i] * c;
+      }
+    }
+    o0 = U::narrow(y0);
+    o1 = U::narrow(y1);
+  }
+  *reinterpret_cast<Raw*>(kdst + e0) = o0;
+  *reinterpret_cast<Raw*>(kdst + e1) = o1;
+  *reinterpret_cast<Raw*>(vdst + v0) = w0;
+  *reinterpret_cast<Raw*>(vdst + v1) = w1;
+}
+
+}  // namespace
+
+hipError_t launch_assemble(int dtype, const AssembleArgs& a, const AssembleSrcTable& t,
+                           hipStream_t stream) {
+  const int64_t n_pos = a.pos_end - a.pos_begin;
+  if (n_pos <= 0) return hipSuccess;
+  const int elems = dtype == MPIC_F32 ? 4 : 8;
+  const int64_t pairs_per_row = static_cast<int64_t>(a.n_kv_heads) * (a.head_dim / 2 / elems);
+  const int64_t threads = n_pos * pairs_per_row;
+  const dim3 block(256);
+  const dim3 grid(static_cast<unsigned>((threads + 255) / 256));
+  if (dtype == MPIC_F32) {
+    if (a.interleaved)
+      hipLaunchKernelGGL((assemble_kernel<float, true>), grid, block, 0, stream, a, t);
+    else
+      hipLaunchKernelGGL((assemble_kernel<float, false>), grid, block, 0, stream, a, t);
+  } else {
+    if (a.interleaved)
+      hipLaunchKernelGGL((assemble_kernel<__bf16, true>), grid, block, 0, stream, a, t);
+    else
+      hipLaunchKernelGGL((assemble_kernel<__bf16, false>), grid, block, 0, stream, a, t);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace mpic

@@ -1,0 +1,128 @@
+// Internal declarations shared by the translation units of libmpic.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "mpic.h"
+
+namespace mpic {
+
+// One attention work item, as laid out in MPIC_PLAN_ATTN_TILES (8 int32).
+struct AttnTile {
+  int32_t req;      // request b
+  int32_t kv_head;  // key/value head g
+  int32_t row0;     // first flattened row: (fresh row - q_off[b]) * G + head-in-group
+  int32_t n_rows;   // rows in this tile (0 = padding entry, the workgroup exits)
+  int32_t n_keys;   // keys 0..n_keys-1 are visited (= largest position in the tile + 1)
+  int32_t pad[3];
+};
+static_assert(sizeof(AttnTile) == 32, "tile layout is part of the ABI");
+
+// Device-resident copy of a plan.
+struct PlanDevice {
+  int32_t* src_inst = nullptr;
+  int32_t* src_row = nullptr;
+  int32_t* dst_slot = nullptr;
+  int32_t* q_pos = nullptr;
+  int32_t* q_off = nullptr;
+  int32_t* ctx_off = nullptr;
+  float* rope_cos = nullptr;
+  float* rope_sin = nullptr;
+  AttnTile* tiles = nullptr;
+  void* block = nullptr;  // the single allocation all of the above point into
+  int device = -1;
+};
+
+}  // namespace mpic
+
+struct mpic_ctx {
+  mpic_config cfg{};
+  int group = 1;  // Hq / Hkv
+  std::string last_error;
+  // GPU side, created on first use
+  int device = -1;
+  hipStream_t side_stream = nullptr;
+  hipEvent_t ev_main = nullptr;              // main stream -> side stream ordering
+  std::vector<hipEvent_t> ev_copy;           // one per staging half
+  void* staging = nullptr;                   // device staging for host-sourced chunks
+  size_t staging_bytes = 0;
+};
+
+struct mpic_plan {
+  mpic_ctx* ctx = nullptr;
+  int32_t n_requests = 0;
+  int64_t n_ctx = 0;      // total context positions of the batch
+  int64_t n_q = 0;        // total fresh rows
+  int64_t max_slot = -1;  // largest physical slot used
+  int32_t max_src = -1;   // largest srcs[] index used
+  std::vector<int32_t> ctx_off, q_off, q_pos, q_req, slot_map, src_inst, src_row, dst_slot;
+  std::vector<int32_t> inst_src, inst_delta, inst_len, inst_k, inst_req, runs;
+  std::vector<mpic::AttnTile> tiles;
+  std::vector<float> rope_cos, rope_sin;
+  mpic::PlanDevice dev;
+};
+
+namespace mpic {
+
+int fail(mpic_ctx* ctx, int code, const std::string& msg);
+int fail_hip(mpic_ctx* ctx, hipError_t e, const char* what);
+
+#define MPIC_HIP(ctx, call)                                  \
+  do {                                                       \
+    hipError_t e_ = (call);                                  \
+    if (e_ != hipSuccess) return mpic::fail_hip(ctx, e_, #call); \
+  } while (0)
+
+// Rows of the attention tile handled by one workgroup of the bf16 kernel.
+constexpr int kAttnTileRows = 128;
+
+// ---- kernel launchers (each validates nothing: callers have done so) ----
+
+struct AssembleArgs {
+  const int32_t* src_inst;
+  const int32_t* src_row;
+  const int32_t* dst_slot;
+  const float* rope_cos;
+  const float* rope_sin;
+  const void* fresh_k;
+  const void* fresh_v;
+  void* k_ctx;
+  void* v_ctx;
+  int64_t pos_begin, pos_end;  // batch-flattened context positions handled by this launch
+  int32_t inst_base;           // first chunk instance present in src_k / src_v
+  int32_t n_inst;              // entries in src_k / src_v
+  int32_t n_kv_heads, head_dim, interleaved;
+  int32_t skip_fresh;          // 1: leave rows of the recompute set alone (already written)
+};
+constexpr int kMaxInstPerLaunch = 128;
+struct AssembleSrcTable {
+  const void* k[kMaxInstPerLaunch];
+  const void* v[kMaxInstPerLaunch];
+};
+hipError_t launch_assemble(int dtype, const AssembleArgs& a, const AssembleSrcTable& t,
+                           hipStream_t stream);
+
+struct AttnArgs {
+  const AttnTile* tiles;
+  int32_t n_tiles;
+  const int32_t* q_pos;
+  const int32_t* q_off;
+  const int32_t* ctx_off;
+  const int32_t* dst_slot;
+  const void* q;
+  const void* k_ctx;
+  const void* v_ctx;
+  void* out;
+  float* lse;
+  float scale;
+  int32_t n_q_heads, n_kv_heads, head_dim;
+  int32_t n_requests;
+};
+hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t stream);
+hipError_t launch_attn_f32(const AttnArgs& a, int64_t n_q, hipStream_t stream);
+
+}  // namespace mpic

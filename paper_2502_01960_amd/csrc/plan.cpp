@@ -1,0 +1,336 @@
+// Host-side integer planner of libmpic (no GPU calls in this file).
+//
+// Selection rule, Sec. 4.2: the recompute set is every text token plus the first k
+// tokens of every image chunk.  Linking, Fig. 7 step 2 / Sec. 4.1: rows of the
+// recompute set are replaced by freshly generated K/V (text slots are only
+// placeholders before that), every other row comes from the stored chunk cache.
+// The planner turns a batch of segment lists into range-wise filled index maps,
+// the rotary tables of the chunk shifts and the launch order of attention tiles.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <numeric>
+
+#include "common.h"
+
+namespace mpic {
+
+int fail(mpic_ctx* ctx, int code, const std::string& msg) {
+  if (ctx) ctx->last_error = msg;
+  return code;
+}
+
+int fail_hip(mpic_ctx* ctx, hipError_t e, const char* what) {
+  if (ctx) ctx->last_error = std::string(what) + ": " + hipGetErrorString(e);
+  return MPIC_ERR_HIP;
+}
+
+namespace {
+
+constexpr int kXcds = 8;  // L2 domains of the chip; workgroup i is dispatched to domain i % 8
+
+// Cut the runs of every request into attention tiles and order them for launch.
+//
+// A tile is a range of "flattened rows" of one (request, kv head): all G query heads
+// of a fresh row are adjacent, fresh rows follow each other in position order.  Tiles
+// never straddle two runs, so every row of a tile sees almost the same keys and only
+// the last few key blocks need the causal mask.  Launch order: tiles that read the
+// same K/V (same request and kv head) are dealt to the same L2 domain, and inside a
+// domain the longest tiles come first so the tail of the launch is made of short work.
+void build_tiles(mpic_plan& p, int group, int n_kv_heads) {
+  struct Item {
+    AttnTile t;
+    int64_t cost;
+  };
+  const int B = p.n_requests;
+  const int n_combo = B * n_kv_heads;
+  std::vector<std::vector<Item>> per_combo(n_combo);
+  const size_t n_runs = p.runs.size() / 4;
+  for (size_t i = 0; i < n_runs; ++i) {
+    const int b = p.runs[4 * i + 0];
+    const int64_t r0 = p.runs[4 * i + 1] - p.q_off[b];
+    const int64_t len = p.runs[4 * i + 2];
+    const int64_t lo = r0 * group, hi = (r0 + len) * group;
+    for (int64_t row = lo; row < hi; row += kAttnTileRows) {
+      const int64_t n = std::min<int64_t>(kAttnTileRows, hi - row);
+      const int64_t last_fresh = p.q_off[b] + (row + n - 1) / group;
+      const int32_t n_keys = p.q_pos[last_fresh] + 1;
+      for (int g = 0; g < n_kv_heads; ++g) {
+        Item it{};
+        it.t.req = b;
+        it.t.kv_head = g;
+        it.t.row0 = static_cast<int32_t>(row);
+        it.t.n_rows = static_cast<int32_t>(n);
+        it.t.n_keys = n_keys;
+        it.cost = static_cast<int64_t>(n_keys) + 64;  // per-tile fixed cost keeps ties stable
+        per_combo[b * n_kv_heads + g].push_back(it);
+      }
+    }
+  }
+  auto by_cost = [](const Item& a, const Item& b) { return a.cost > b.cost; };
+  std::vector<std::vector<Item>> queue(kXcds);
+  if (n_combo >= kXcds) {
+    // whole (request, kv head) groups go to the currently lightest domain, heaviest first
+    std::vector<int> order(n_combo);
+    std::iota(order.begin(), order.end(), 0);
+    std::vector<int64_t> total(n_combo, 0);
+    for (int c = 0; c < n_combo; ++c)
+      for (const Item& it : per_combo[c]) total[c] += it.cost;
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return total[a] > total[b]; });
+    std::vector<int64_t> load(kXcds, 0);
+    for (int c : order) {
+      const int x = static_cast<int>(std::min_element(load.begin(), load.end()) - load.begin());
+      load[x] += total[c];
+      queue[x].insert(queue[x].end(), per_combo[c].begin(), per_combo[c].end());
+    }
+  } else {
+    // fewer groups than domains: spread each group over `share` domains, tile by tile
+    const int share = std::max(1, kXcds / std::max(1, n_combo));
+    for (int c = 0; c < n_combo; ++c) {
+      std::stable_sort(per_combo[c].begin(), per_combo[c].end(), by_cost);
+      for (size_t i = 0; i < per_combo[c].size(); ++i)
+        queue[(c * share + static_cast<int>(i % share)) % kXcds].push_back(per_combo[c][i]);
+    }
+  }
+  size_t depth = 0;
+  for (auto& q : queue) {
+    std::stable_sort(q.begin(), q.end(), by_cost);
+    depth = std::max(depth, q.size());
+  }
+  p.tiles.clear();
+  p.tiles.reserve(depth * kXcds);
+  for (size_t i = 0; i < depth; ++i)
+    for (int x = 0; x < kXcds; ++x) {
+      if (i < queue[x].size()) {
+        p.tiles.push_back(queue[x][i].t);
+      } else {
+        p.tiles.push_back(AttnTile{});  // padding keeps the i % 8 dealing intact
+      }
+    }
+  while (!p.tiles.empty() && p.tiles.back().n_rows == 0) p.tiles.pop_back();
+}
+
+}  // namespace
+}  // namespace mpic
+
+using mpic::fail;
+
+extern "C" int mpic_create(mpic_ctx** out, const mpic_config* config) {
+  if (!out || !config) return MPIC_ERR_INVALID;
+  *out = nullptr;
+  const mpic_config& c = *config;
+  if (c.n_q_heads <= 0 || c.n_kv_heads <= 0 || c.head_dim <= 0 || c.n_q_heads % c.n_kv_heads != 0 ||
+      (c.head_dim & 1) || !(c.rope_theta > 0.0) || !std::isfinite(c.rope_theta) || c.page_size < 0 ||
+      (c.rope_interleaved != 0 && c.rope_interleaved != 1))
+    return MPIC_ERR_INVALID;
+  if (c.dtype == MPIC_F32) {
+    if (c.head_dim != 64 && c.head_dim != 128) return MPIC_ERR_UNSUPPORTED;
+  } else if (c.dtype == MPIC_BF16) {
+    if (c.head_dim != 128) return MPIC_ERR_UNSUPPORTED;
+  } else {
+    return MPIC_ERR_INVALID;
+  }
+  mpic_ctx* ctx = new (std::nothrow) mpic_ctx();
+  if (!ctx) return MPIC_ERR_OOM;
+  ctx->cfg = c;
+  ctx->group = c.n_q_heads / c.n_kv_heads;
+  *out = ctx;
+  return MPIC_OK;
+}
+
+extern "C" int mpic_plan_create(mpic_ctx* ctx, int32_t n_requests, const int32_t* seg_off,
+                                const mpic_segment* segs, int32_t default_k,
+                                const int32_t* page_table, const int32_t* page_table_off,
+                                int64_t n_pool_pages, mpic_plan** out) {
+  if (!ctx) return MPIC_ERR_INVALID;
+  if (!out) return fail(ctx, MPIC_ERR_INVALID, "plan_create: out is NULL");
+  *out = nullptr;
+  if (n_requests < 1 || !seg_off || default_k < 0)
+    return fail(ctx, MPIC_ERR_INVALID, "plan_create: need n_requests >= 1, seg_off, default_k >= 0");
+  const int ps = ctx->cfg.page_size;
+  if (ps > 0 && (!page_table || !page_table_off || n_pool_pages <= 0))
+    return fail(ctx, MPIC_ERR_INVALID, "plan_create: paged layout needs page_table, offsets and pool size");
+  if (seg_off[0] != 0) return fail(ctx, MPIC_ERR_INVALID, "plan_create: seg_off[0] must be 0");
+  for (int b = 0; b < n_requests; ++b)
+    if (seg_off[b + 1] < seg_off[b]) return fail(ctx, MPIC_ERR_INVALID, "plan_create: seg_off must not decrease");
+  if (seg_off[n_requests] > 0 && !segs) return fail(ctx, MPIC_ERR_INVALID, "plan_create: segs is NULL");
+
+  // pass 1: validate and size
+  int64_t n_ctx = 0, n_q = 0;
+  for (int32_t s = 0; s < seg_off[n_requests]; ++s) {
+    const mpic_segment& g = segs[s];
+    if (g.len < 0 || (g.kind != 0 && g.kind != 1)) return fail(ctx, MPIC_ERR_INVALID, "plan_create: bad segment kind or negative len");
+    if (g.kind == 1 && g.chunk < 0) return fail(ctx, MPIC_ERR_INVALID, "plan_create: negative chunk index");
+    n_ctx += g.len;
+    if (g.kind == 0) {
+      n_q += g.len;
+    } else {
+      const int64_t k = g.k < 0 ? default_k : g.k;
+      n_q += std::min<int64_t>(k, g.len);
+    }
+  }
+  const int64_t slot_limit = ps > 0 ? n_pool_pages * ps : n_ctx;
+  if (n_ctx >= INT32_MAX || slot_limit >= INT32_MAX || n_q * ctx->group >= INT32_MAX)
+    return fail(ctx, MPIC_ERR_INVALID, "plan_create: batch too large for 32-bit indices");
+
+  mpic_plan* p = new (std::nothrow) mpic_plan();
+  if (!p) return fail(ctx, MPIC_ERR_OOM, "plan_create: out of host memory");
+  try {
+    p->ctx = ctx;
+    p->n_requests = n_requests;
+    p->n_ctx = n_ctx;
+    p->n_q = n_q;
+    p->ctx_off.assign(1, 0);
+    p->q_off.assign(1, 0);
+    p->q_pos.reserve(n_q);
+    p->q_req.reserve(n_q);
+    p->slot_map.reserve(n_q);
+    p->src_inst.resize(n_ctx);
+    p->src_row.resize(n_ctx);
+    p->dst_slot.resize(n_ctx);
+    std::vector<char> page_used;
+    if (ps > 0) page_used.assign(n_pool_pages, 0);
+
+    for (int b = 0; b < n_requests; ++b) {
+      const int32_t ctx0 = p->ctx_off.back();
+      const int32_t q0 = p->q_off.back();
+      int32_t pos = 0;  // position inside the request
+      int32_t row = q0; // next fresh row
+      auto take_fresh = [&](int32_t first, int32_t count) {
+        if (count <= 0) return;
+        const bool extends = !p->runs.empty() && p->runs[p->runs.size() - 4] == b &&
+                             p->runs[p->runs.size() - 1] + p->runs[p->runs.size() - 2] == first;
+        if (extends) {
+          p->runs[p->runs.size() - 2] += count;
+        } else {
+          p->runs.insert(p->runs.end(), {b, row, count, first});
+        }
+        for (int32_t t = 0; t < count; ++t) {
+          p->src_inst[ctx0 + first + t] = -1;
+          p->src_row[ctx0 + first + t] = row;
+          p->q_pos.push_back(first + t);
+          p->q_req.push_back(b);
+          ++row;
+        }
+      };
+      for (int32_t s = seg_off[b]; s < seg_off[b + 1]; ++s) {
+        const mpic_segment& g = segs[s];
+        if (g.kind == 0) {
+          take_fresh(pos, g.len);
+        } else {
+          const int64_t k = g.k < 0 ? default_k : g.k;
+          const int32_t k_eff = static_cast<int32_t>(std::min<int64_t>(k, g.len));
+          const int32_t inst = static_cast<int32_t>(p->inst_src.size());
+          p->inst_src.push_back(g.chunk);
+          p->inst_delta.push_back(pos);
+          p->inst_len.push_back(g.len);
+          p->inst_k.push_back(k_eff);
+          p->inst_req.push_back(b);
+          p->max_src = std::max(p->max_src, g.chunk);
+          take_fresh(pos, k_eff);
+          for (int32_t t = k_eff; t < g.len; ++t) {
+            p->src_inst[ctx0 + pos + t] = inst;
+            p->src_row[ctx0 + pos + t] = t;
+          }
+        }
+        pos += g.len;
+      }
+      // physical slots
+      if (ps > 0) {
+        const int64_t have = static_cast<int64_t>(page_table_off[b + 1]) - page_table_off[b];
+        const int64_t need = (static_cast<int64_t>(pos) + ps - 1) / ps;
+        if (have < need) {
+          delete p;
+          return fail(ctx, MPIC_ERR_INVALID, "plan_create: page table shorter than the request");
+        }
+        const int32_t* tab = page_table + page_table_off[b];
+        for (int64_t pg = 0; pg < need; ++pg) {
+          const int32_t id = tab[pg];
+          if (id < 0 || id >= n_pool_pages || page_used[id]) {
+            delete p;
+            return fail(ctx, MPIC_ERR_INVALID, "plan_create: page id out of range or used twice");
+          }
+          page_used[id] = 1;
+        }
+        for (int32_t t = 0; t < pos; ++t) p->dst_slot[ctx0 + t] = tab[t / ps] * ps + t % ps;
+      } else {
+        for (int32_t t = 0; t < pos; ++t) p->dst_slot[ctx0 + t] = ctx0 + t;
+      }
+      for (int32_t r = q0; r < row; ++r) p->slot_map.push_back(p->dst_slot[ctx0 + p->q_pos[r]]);
+      p->ctx_off.push_back(ctx0 + pos);
+      p->q_off.push_back(row);
+    }
+    for (int32_t s : p->dst_slot) p->max_slot = std::max<int64_t>(p->max_slot, s);
+
+    // rotary tables: one angle vector per chunk instance, evaluated in double
+    const int half = ctx->cfg.head_dim / 2;
+    p->rope_cos.resize(p->inst_src.size() * half);
+    p->rope_sin.resize(p->inst_src.size() * half);
+    for (size_t i = 0; i < p->inst_src.size(); ++i)
+      for (int j = 0; j < half; ++j) {
+        const double inv_freq = std::pow(ctx->cfg.rope_theta, -2.0 * j / ctx->cfg.head_dim);
+        const double phi = static_cast<double>(p->inst_delta[i]) * inv_freq;
+        p->rope_cos[i * half + j] = static_cast<float>(std::cos(phi));
+        p->rope_sin[i * half + j] = static_cast<float>(std::sin(phi));
+      }
+    mpic::build_tiles(*p, ctx->group, ctx->cfg.n_kv_heads);
+  } catch (const std::bad_alloc&) {
+    delete p;
+    return fail(ctx, MPIC_ERR_OOM, "plan_create: out of host memory");
+  }
+  *out = p;
+  return MPIC_OK;
+}
+
+extern "C" int mpic_plan_get(const mpic_plan* plan, int32_t what, const int32_t** host_ptr, size_t* n) {
+  if (!plan || !host_ptr || !n) return MPIC_ERR_INVALID;
+  const std::vector<int32_t>* v = nullptr;
+  switch (what) {
+    case MPIC_PLAN_CTX_OFF: v = &plan->ctx_off; break;
+    case MPIC_PLAN_Q_OFF: v = &plan->q_off; break;
+    case MPIC_PLAN_Q_POS: v = &plan->q_pos; break;
+    case MPIC_PLAN_Q_REQ: v = &plan->q_req; break;
+    case MPIC_PLAN_SLOT_MAP: v = &plan->slot_map; break;
+    case MPIC_PLAN_SRC_INST: v = &plan->src_inst; break;
+    case MPIC_PLAN_SRC_ROW: v = &plan->src_row; break;
+    case MPIC_PLAN_DST_SLOT: v = &plan->dst_slot; break;
+    case MPIC_PLAN_INST_SRC: v = &plan->inst_src; break;
+    case MPIC_PLAN_INST_DELTA: v = &plan->inst_delta; break;
+    case MPIC_PLAN_INST_LEN: v = &plan->inst_len; break;
+    case MPIC_PLAN_INST_K: v = &plan->inst_k; break;
+    case MPIC_PLAN_INST_REQ: v = &plan->inst_req; break;
+    case MPIC_PLAN_RUNS: v = &plan->runs; break;
+    case MPIC_PLAN_ATTN_TILES:
+      *host_ptr = reinterpret_cast<const int32_t*>(plan->tiles.data());
+      *n = plan->tiles.size() * 8;
+      return MPIC_OK;
+    default:
+      return fail(plan->ctx, MPIC_ERR_INVALID, "plan_get: unknown selector");
+  }
+  *host_ptr = v->data();
+  *n = v->size();
+  return MPIC_OK;
+}
+
+extern "C" int mpic_plan_get_rope(const mpic_plan* plan, const float** cos_tab, const float** sin_tab,
+                                  size_t* n) {
+  if (!plan || !cos_tab || !sin_tab || !n) return MPIC_ERR_INVALID;
+  *cos_tab = plan->rope_cos.data();
+  *sin_tab = plan->rope_sin.data();
+  *n = plan->rope_cos.size();
+  return MPIC_OK;
+}
+
+extern "C" const char* mpic_strerror(int status) {
+  switch (status) {
+    case MPIC_OK: return "ok";
+    case MPIC_ERR_INVALID: return "invalid argument";
+    case MPIC_ERR_UNSUPPORTED: return "unsupported configuration";
+    case MPIC_ERR_OOM: return "out of memory";
+    case MPIC_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+extern "C" const char* mpic_last_error(const mpic_ctx* ctx) { return ctx ? ctx->last_error.c_str() : ""; }

@@ -1,0 +1,108 @@
+"""Shared plumbing of the tests: build one layer's inputs from the seeded generator,
+run the HIP library on them, run the float64 oracle on them.  No arithmetic of the
+method lives here."""
+import numpy as np
+import torch
+
+import workloads
+import paper_2502_01960_amd as mpic
+from oracle import attend, build_plan, link_kv
+
+
+class Problem:
+    """Inputs of one layer of one batch, as host tensors in the storage dtype."""
+
+    def __init__(self, cfg_id, *, k=None, layer=0, paged=None, **layout_kw):
+        self.sh = sh = workloads.shape(cfg_id)
+        self.layer = layer
+        self.k = sh.default_k if k is None else k
+        self.requests, self.n_src, self.src_len = workloads.layout(cfg_id, **layout_kw)
+        self.page_size = sh.page_size if paged is None else paged
+        lens = [workloads.request_len(r) for r in self.requests]
+        if self.page_size:
+            self.page_tables, self.n_pool_pages = workloads.gen_page_tables(sh, lens, self.page_size)
+            self.n_slots = self.n_pool_pages * self.page_size
+        else:
+            self.page_tables, self.n_pool_pages = None, 0
+            self.n_slots = sum(lens)
+        self.oplan = build_plan(self.requests, self.k, self.page_size, self.page_tables)
+        used = sorted(set(self.oplan["inst_src"].tolist()))
+        self.chunks = {s: workloads.gen_chunk(sh, layer, s, self.src_len[s]) for s in used}
+        q_off = self.oplan["q_off"]
+        fresh = [workloads.gen_fresh(sh, layer, b, int(q_off[b + 1] - q_off[b]))
+                 for b in range(len(self.requests))]
+        self.q = torch.cat([f[0] for f in fresh])
+        self.fresh_k = torch.cat([f[1] for f in fresh])
+        self.fresh_v = torch.cat([f[2] for f in fresh])
+
+    # ---- oracle side -------------------------------------------------------
+    def oracle_link(self):
+        f64 = lambda t: t.to(torch.float64).numpy()
+        ck = {s: f64(kv[0]) for s, kv in self.chunks.items()}
+        cv = {s: f64(kv[1]) for s, kv in self.chunks.items()}
+        return link_kv(self.oplan, ck, cv, f64(self.fresh_k), f64(self.fresh_v), self.sh.rope_theta)
+
+    def oracle_attend(self, K, V, rows=None):
+        return attend(self.q.to(torch.float64).numpy(), K, V, self.oplan, self.sh.softmax_scale, rows=rows)
+
+    # ---- HIP side ----------------------------------------------------------
+    def gpu_setup(self, host_sourced=None):
+        sh = self.sh
+        dev = torch.device("cuda:0")
+        dt = mpic.MPIC_F32 if sh.dtype == "f32" else mpic.MPIC_BF16
+        self.ctx = mpic.Context(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, dt, sh.rope_theta, 0, self.page_size)
+        self.plan = mpic.Plan(self.ctx, self.requests, self.k, self.page_tables, self.n_pool_pages)
+        host = sh.host_sourced if host_sourced is None else host_sourced
+        self.srcs = []
+        for s in range(self.n_src):
+            if s not in self.chunks:
+                self.srcs.append((None, None))
+            elif host:
+                self.srcs.append(tuple(t.pin_memory() for t in self.chunks[s]))
+            else:
+                self.srcs.append(tuple(t.to(dev) for t in self.chunks[s]))
+        # sources the plan never touches still need a length: give them empty placeholders
+        self.d_q, self.d_fk, self.d_fv = self.q.to(dev), self.fresh_k.to(dev), self.fresh_v.to(dev)
+        shape = (self.n_slots, sh.n_kv_heads, sh.head_dim)
+        self.k_ctx = torch.full(shape, float("nan"), dtype=sh.torch_dtype, device=dev)
+        self.v_ctx = torch.full(shape, float("nan"), dtype=sh.torch_dtype, device=dev)
+        self.out = torch.full(tuple(self.q.shape), float("nan"), dtype=sh.torch_dtype, device=dev)
+        self.lse = torch.full(tuple(self.q.shape[:2]), float("nan"), dtype=torch.float32, device=dev)
+
+    def gpu_assemble(self):
+        mpic.mpic_assemble_kv(self.ctx.handle, self.plan.handle, self.srcs, self.d_fk, self.d_fv,
+                              self.k_ctx, self.v_ctx)
+
+    def gpu_attend(self, lse=True):
+        mpic.mpic_selective_attn(self.ctx.handle, self.plan.handle, self.d_q, self.k_ctx, self.v_ctx,
+                                 self.sh.softmax_scale, self.out, self.lse if lse else None)
+
+    def gpu_logical_kv(self):
+        """Context rows in logical order (request after request), float64 numpy."""
+        slots = torch.from_numpy(self.oplan["dst_slot"].astype(np.int64)).to(self.k_ctx.device)
+        torch.cuda.synchronize()
+        return (self.k_ctx[slots].to(torch.float64).cpu().numpy(),
+                self.v_ctx[slots].to(torch.float64).cpu().numpy())
+
+
+def err_stats(got, ref):
+    e = np.abs(np.asarray(got, dtype=np.float64) - ref)
+    return float(e.max()), float(e.mean())
+
+
+def assert_bf16_close(got, ref, what, max_abs=2e-2, mean_abs=2e-3):
+    """Gate of the bf16 configurations: max-abs <= 2e-2 and mean-abs <= 2e-3."""
+    assert np.isfinite(got).all(), f"{what}: non-finite values"
+    mx, mean = err_stats(got, ref)
+    assert mx <= max_abs and mean <= mean_abs, f"{what}: max-abs {mx:.3e}, mean-abs {mean:.3e}"
+    return mx, mean
+
+
+def assert_f32_close(got, ref, what, rel=1e-5):
+    """Gate of the fp32 configuration: 1e-5 relative, per tensor and per element."""
+    assert np.isfinite(got).all(), f"{what}: non-finite values"
+    e = np.abs(got - ref)
+    scale = np.abs(ref).max()
+    rms = np.sqrt((ref ** 2).mean())
+    assert e.max() <= rel * scale, f"{what}: max err {e.max():.3e} vs {rel * scale:.3e}"
+    assert (e <= rel * np.abs(ref) + rel * rms).all(), f"{what}: element-wise bound violated"

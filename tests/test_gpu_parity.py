@@ -1,0 +1,228 @@
+"""Parity of the HIP library against the float64 oracle (needs an MI355X).
+
+Every test feeds the same seeded inputs to both sides through the C ABI binding and
+compares element by element: integer maps bit-exact, copied rows bit-exact, rotated
+keys and attention outputs within the stated floating-point gates."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+import paper_2502_01960_amd as mpic
+from helpers import Problem, assert_bf16_close, assert_f32_close, err_stats
+
+pytestmark = pytest.mark.gpu
+
+INT_FIELDS = [f for f in mpic.PLAN_FIELDS if f != "attn_tiles"]
+
+
+def _check_plan(p):
+    for f in INT_FIELDS:
+        assert np.array_equal(p.plan.get(f), p.oplan[f]), f
+
+
+def _check_link(p, K_ref, V_ref, bf16):
+    Kg, Vg = p.gpu_logical_kv()
+    fresh = p.oplan["src_inst"] < 0
+    # values and replaced rows are copies: bit-exact
+    assert np.array_equal(Vg, V_ref), "V context must be a bit-exact copy"
+    assert np.array_equal(Kg[fresh], K_ref[fresh]), "fresh K rows must be bit-exact copies"
+    if bf16:
+        assert_bf16_close(Kg, K_ref, "K context")
+    else:
+        assert_f32_close(Kg, K_ref, "K context")
+    # slots that belong to no position stay untouched (NaN canary)
+    used = np.zeros(p.n_slots, dtype=bool)
+    used[p.oplan["dst_slot"]] = True
+    if (~used).any():
+        idle = torch.from_numpy(np.nonzero(~used)[0]).to(p.k_ctx.device)
+        assert torch.isnan(p.k_ctx[idle].float()).all() and torch.isnan(p.v_ctx[idle].float()).all()
+    return Kg, Vg
+
+
+def _run_full(p, host_sourced=None):
+    """assemble + attend on the GPU, oracle on the CPU, compare everything."""
+    bf16 = p.sh.dtype == "bf16"
+    p.gpu_setup(host_sourced)
+    _check_plan(p)
+    p.gpu_assemble()
+    p.gpu_attend()
+    torch.cuda.synchronize()
+    K_ref, V_ref = p.oracle_link()
+    Kg, Vg = _check_link(p, K_ref, V_ref, bf16)
+    O_ref, L_ref = p.oracle_attend(K_ref, V_ref)
+    O = p.out.to(torch.float64).cpu().numpy()
+    L = p.lse.to(torch.float64).cpu().numpy()
+    if len(O_ref) == 0:
+        return
+    if bf16:
+        assert_bf16_close(O, O_ref, "attention output (end to end)")
+        # isolated attention: oracle fed with the GPU-assembled context
+        O_iso, _ = p.oracle_attend(Kg, Vg)
+        assert_bf16_close(O, O_iso, "attention output (isolated)")
+        assert np.abs(L - L_ref).max() < 2e-2
+    else:
+        assert_f32_close(O, O_ref, "attention output")
+        assert np.abs(L - L_ref).max() <= 1e-5 * max(1.0, np.abs(L_ref).max())
+
+
+def test_config1_tiny_fp32():
+    _run_full(Problem(1))
+
+
+def test_config2_llava15_like_full():
+    _run_full(Problem(2))
+
+
+def test_config3_reduced_ragged_device_and_host_sources():
+    # three ragged chunks per request, two requests: several tiles and ragged tails
+    _run_full(Problem(3, n_chunks=3, chunk_len=301, text_len=37, batch=2), host_sourced=False)
+    _run_full(Problem(3, n_chunks=3, chunk_len=301, text_len=37, batch=2), host_sourced=True)
+
+
+def test_config4_reduced_k_sweep():
+    for k in (0, 16, 64, 200):      # 200 >= chunk length: everything recomputed
+        _run_full(Problem(4, k=k, n_chunks=4, chunk_len=160, text_len=70, batch=3))
+
+
+def test_config5_reduced_paged():
+    _run_full(Problem(5, n_chunks=5, chunk_len=203, text_len=21), host_sourced=False)   # N % 16 != 0
+    _run_full(Problem(5, n_chunks=5, chunk_len=203, text_len=21), host_sourced=True)
+
+
+def test_paged_and_contiguous_agree_bitwise():
+    a = Problem(5, n_chunks=4, chunk_len=128, text_len=32, paged=16)
+    b = Problem(5, n_chunks=4, chunk_len=128, text_len=32, paged=0)
+    outs = []
+    for p in (a, b):
+        p.gpu_setup(False); p.gpu_assemble(); p.gpu_attend(); torch.cuda.synchronize()
+        outs.append(p.out.cpu())
+    assert torch.equal(outs[0].view(torch.int16), outs[1].view(torch.int16))
+
+
+def _sampled_rows(p, per_run=6, seed=0):
+    rng = np.random.default_rng(seed)
+    rows = []
+    for (b, r0, ln, p0) in p.oplan["runs"].tolist():
+        pick = {r0, r0 + ln - 1} | set((r0 + rng.integers(0, ln, size=per_run)).tolist())
+        rows += sorted(pick)
+    return np.asarray(rows, dtype=np.int64)
+
+
+def _run_sampled(p, host_sourced, per_run=6):
+    """Full-size configuration: link checked in full, attention on sampled rows (first
+    and last row of every run plus random ones), all heads."""
+    p.gpu_setup(host_sourced)
+    _check_plan(p)
+    p.gpu_assemble()
+    p.gpu_attend()
+    torch.cuda.synchronize()
+    K_ref, V_ref = p.oracle_link()
+    _check_link(p, K_ref, V_ref, True)
+    rows = _sampled_rows(p, per_run)
+    O_ref, L_ref = p.oracle_attend(K_ref, V_ref, rows=rows)
+    O = p.out.to(torch.float64).cpu().numpy()
+    assert np.isfinite(O).all()
+    assert_bf16_close(O[rows], O_ref[rows], "attention output (sampled rows)")
+    assert np.abs(p.lse.cpu().numpy()[rows] - L_ref[rows]).max() < 2e-2
+
+
+def test_config3_full_size_sampled():
+    _run_sampled(Problem(3), host_sourced=False, per_run=3)
+
+
+def test_config3_full_size_host_sourced_link():
+    p = Problem(3, batch=2)
+    p.gpu_setup(True)
+    p.gpu_assemble()
+    K_ref, V_ref = p.oracle_link()
+    _check_link(p, K_ref, V_ref, True)
+    # a second layer reuses plan, context and staging
+    p.gpu_assemble()
+    _check_link(p, K_ref, V_ref, True)
+
+
+def test_config4_full_size_one_layer_sampled():
+    _run_sampled(Problem(4, k=16, batch=2), host_sourced=False, per_run=2)
+
+
+def test_config5_full_size_paged_sampled():
+    _run_sampled(Problem(5), host_sourced=True, per_run=1)
+
+
+# ------------------------------------------------------------------ edge cases
+def _custom(requests, n_src, src_len, k, sh_id=3, paged=0):
+    p = Problem.__new__(Problem)
+    p.sh = workloads.shape(sh_id)
+    p.layer, p.k = 0, k
+    p.requests, p.n_src, p.src_len = requests, n_src, src_len
+    p.page_size = paged
+    lens = [workloads.request_len(r) for r in requests]
+    if paged:
+        p.page_tables, p.n_pool_pages = workloads.gen_page_tables(p.sh, lens, paged)
+        p.n_slots = p.n_pool_pages * paged
+    else:
+        p.page_tables, p.n_pool_pages, p.n_slots = None, 0, max(1, sum(lens))
+    from oracle import build_plan
+    p.oplan = build_plan(requests, k, paged, p.page_tables)
+    p.chunks = {s: workloads.gen_chunk(p.sh, 0, s, src_len[s]) for s in sorted(set(p.oplan["inst_src"].tolist()))}
+    q_off = p.oplan["q_off"]
+    fresh = [workloads.gen_fresh(p.sh, 0, b, int(q_off[b + 1] - q_off[b])) for b in range(len(requests))]
+    p.q = torch.cat([f[0] for f in fresh]); p.fresh_k = torch.cat([f[1] for f in fresh]); p.fresh_v = torch.cat([f[2] for f in fresh])
+    return p
+
+
+def test_edge_layouts():
+    # chunk first (zero shift = bit-exact copy), same chunk twice, single-token and empty
+    # text segments, k = 0 next to k >= L, request with no fresh row at all
+    reqs = [[("chunk", 0, 70, None), ("text", 1), ("chunk", 0, 70, 0), ("text", 0), ("chunk", 1, 33, 99), ("text", 1)],
+            [("chunk", 1, 33, 0)],
+            [("text", 5)]]
+    p = _custom(reqs, 2, [70, 33], 3)
+    _run_full(p, host_sourced=False)
+    Kg, _ = p.gpu_logical_kv()
+    first = p.chunks[0][0].to(torch.float64).numpy()
+    assert np.array_equal(Kg[3:70], first[3:70]), "zero shift must copy keys bit-exactly"
+    _run_full(_custom(reqs, 2, [70, 33], 3, paged=16), host_sourced=True)
+
+
+def test_empty_recompute_set_is_a_noop():
+    p = _custom([[("chunk", 0, 40, None), ("chunk", 1, 24, None)]], 2, [40, 24], 0)
+    _run_full(p, host_sourced=False)
+    assert torch.isnan(p.out.float()).all() or p.out.numel() == 0
+
+
+def test_rejected_gpu_calls_enqueue_nothing():
+    p = Problem(1)
+    p.gpu_setup()
+    small = p.k_ctx[:100]
+    with pytest.raises(mpic.MpicError):
+        mpic.mpic_assemble_kv(p.ctx.handle, p.plan.handle, p.srcs, p.d_fk, p.d_fv, small, small)
+    with pytest.raises(mpic.MpicError):
+        mpic.mpic_assemble_kv(p.ctx.handle, p.plan.handle, p.srcs, p.d_fk[:10], p.d_fv[:10], p.k_ctx, p.v_ctx)
+    with pytest.raises(mpic.MpicError):
+        mpic.mpic_assemble_kv(p.ctx.handle, p.plan.handle, p.srcs[:1], p.d_fk, p.d_fv, p.k_ctx, p.v_ctx)
+    with pytest.raises(mpic.MpicError):
+        mpic.mpic_selective_attn(p.ctx.handle, p.plan.handle, p.d_q, p.k_ctx, p.v_ctx, float("nan"), p.out)
+    torch.cuda.synchronize()
+    assert torch.isnan(p.k_ctx).all() and torch.isnan(p.out).all()
+    other = mpic.Context(4, 4, 64, mpic.MPIC_F32, 1e4)
+    with pytest.raises(mpic.MpicError):
+        mpic.mpic_assemble_kv(other.handle, p.plan.handle, p.srcs, p.d_fk, p.d_fv, p.k_ctx, p.v_ctx)
+
+
+def test_interleaved_rotary_pairs():
+    from oracle import link_kv
+    for cfg in (1, 3):
+        p = Problem(cfg, n_chunks=2, chunk_len=64, text_len=9, batch=1) if cfg == 3 else Problem(1)
+        p.gpu_setup(False)
+        sh = p.sh
+        dt = mpic.MPIC_F32 if sh.dtype == "f32" else mpic.MPIC_BF16
+        p.ctx = mpic.Context(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, dt, sh.rope_theta, 1, 0)
+        p.plan = mpic.Plan(p.ctx, p.requests, p.k)
+        p.gpu_assemble()
+        f64 = lambda t: t.to(torch.float64).numpy()
+        K_ref, V_ref = link_kv(p.oplan, {s: f64(kv[0]) for s, kv in p.chunks.items()},
+                               {s: f64(kv[1]) for s, kv in p.chunks.items()},
+                               f64(p.fresh_k), f64(p.fresh_v), sh.rope_theta, interleaved=True)
+        _check_link(p, K_ref, V_ref, sh.dtype == "bf16")

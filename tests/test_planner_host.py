@@ -1,0 +1,153 @@
+"""Host logic of libmpic without a GPU: the C++ planner against the oracle plan (bit
+exact), the rotary tables against float64, argument checking, exported symbols."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+from hypothesis import given, settings, strategies as st
+
+import workloads
+import paper_2502_01960_amd as mpic
+from oracle import build_plan
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+INT_FIELDS = [f for f in mpic.PLAN_FIELDS if f != "attn_tiles"]
+
+
+def _ctx(hq=4, hkv=2, d=128, dtype=mpic.MPIC_BF16, theta=1e4, page_size=0):
+    return mpic.Context(hq, hkv, d, dtype, theta, 0, page_size)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "mpic.h")).read()
+    names = sorted(set(re.findall(r"\b(mpic_[a-z_]+)\s*\(", header)))
+    assert {"mpic_assemble_kv", "mpic_selective_attn", "mpic_plan_create", "mpic_create"} <= set(names)
+    lib = ctypes.CDLL(mpic.lib_path())
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in mpic.h but not exported"
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_plan_matches_oracle_on_benchmark_layouts(cfg):
+    sh = workloads.shape(cfg)
+    reqs, _, _ = workloads.layout(cfg)
+    tables, pool = (None, 0)
+    if sh.page_size:
+        tables, pool = workloads.gen_page_tables(sh, [workloads.request_len(r) for r in reqs])
+    ks = [0, 16, 64, 1024] if cfg == 4 else [sh.default_k]
+    ctx = _ctx(sh.n_q_heads, sh.n_kv_heads, sh.head_dim,
+               mpic.MPIC_F32 if sh.dtype == "f32" else mpic.MPIC_BF16, sh.rope_theta, sh.page_size)
+    for k in ks:
+        want = build_plan(reqs, k, sh.page_size, tables)
+        got = mpic.Plan(ctx, reqs, k, tables, pool)
+        for f in INT_FIELDS:
+            assert np.array_equal(got.get(f), want[f]), (cfg, k, f)
+        _check_tiles(got, want, sh.n_q_heads // sh.n_kv_heads, sh.n_kv_heads)
+
+
+def _check_tiles(plan, want, group, n_kv):
+    """Tiles cover every (fresh row, query head) exactly once, stay inside one run and
+    carry the key count of their last row."""
+    tiles = plan.get("attn_tiles")
+    nq = len(want["q_pos"])
+    seen = np.zeros((nq, n_kv * group), dtype=np.int32)
+    run_of = np.zeros(nq, dtype=np.int64)
+    for i, (b, r0, ln, p0) in enumerate(want["runs"].tolist()):
+        run_of[r0:r0 + ln] = i
+    for (b, g, row0, n_rows, n_keys, *_rest) in tiles.tolist():
+        if n_rows == 0:
+            continue
+        assert 0 < n_rows <= 128
+        flat = np.arange(row0, row0 + n_rows)
+        fresh = int(want["q_off"][b]) + flat // group
+        assert fresh.max() < want["q_off"][b + 1]
+        assert len(set(run_of[fresh].tolist())) == 1
+        assert n_keys == want["q_pos"][fresh].max() + 1
+        seen[fresh, g * group + flat % group] += 1
+    assert (seen == 1).all()
+
+
+segment = st.one_of(
+    st.tuples(st.just("text"), st.integers(0, 40)),
+    st.tuples(st.just("chunk"), st.integers(0, 5), st.integers(1, 70),
+              st.one_of(st.none(), st.integers(0, 80))),
+)
+
+
+@settings(max_examples=120, deadline=None)
+@given(st.lists(st.lists(segment, min_size=0, max_size=6), min_size=1, max_size=4),
+       st.integers(0, 20), st.sampled_from([(4, 4), (8, 2), (7, 1), (28, 4)]))
+def test_plan_matches_oracle_on_random_layouts(reqs, default_k, heads):
+    ctx = _ctx(heads[0], heads[1])
+    want = build_plan(reqs, default_k)
+    got = mpic.Plan(ctx, reqs, default_k)
+    for f in INT_FIELDS:
+        assert np.array_equal(got.get(f), want[f]), f
+    _check_tiles(got, want, heads[0] // heads[1], heads[1])
+
+
+@settings(max_examples=60, deadline=None)
+@given(st.lists(st.lists(segment, min_size=1, max_size=5), min_size=1, max_size=3),
+       st.integers(0, 9), st.sampled_from([1, 16, 5]), st.randoms(use_true_random=False))
+def test_paged_plan_matches_oracle(reqs, default_k, ps, rnd):
+    need = [(workloads.request_len(r) + ps - 1) // ps for r in reqs]
+    pool = list(range(sum(need) + 2))
+    rnd.shuffle(pool)
+    tables, at = [], 0
+    for n in need:
+        tables.append(np.asarray(pool[at:at + n], dtype=np.int32)); at += n
+    ctx = _ctx(page_size=ps)
+    want = build_plan(reqs, default_k, ps, tables)
+    got = mpic.Plan(ctx, reqs, default_k, tables, len(pool))
+    for f in INT_FIELDS:
+        assert np.array_equal(got.get(f), want[f]), f
+
+
+def test_rope_tables_are_float64_accurate():
+    theta, d = 1e6, 128
+    reqs = [[("text", 64), ("chunk", 0, 2304, None)] * 32 + [("text", 64)]]
+    plan = mpic.Plan(_ctx(64, 8, d, theta=theta), reqs, 32)
+    cos, sin = plan.rope()
+    delta = plan.get("inst_delta").astype(np.float64)
+    assert delta[-1] == 31 * 2368 + 64
+    phi = delta[:, None] * theta ** (-2.0 * np.arange(d // 2) / d)
+    assert cos.shape == (32 * 64,)
+    np.testing.assert_allclose(cos.reshape(32, 64), np.cos(phi), rtol=0, atol=6e-8)
+    np.testing.assert_allclose(sin.reshape(32, 64), np.sin(phi), rtol=0, atol=6e-8)
+
+
+def test_rejected_arguments():
+    with pytest.raises(mpic.MpicError):
+        _ctx(hq=6, hkv=4)                      # heads do not group
+    with pytest.raises(mpic.MpicError):
+        _ctx(d=96)                             # unsupported head_dim
+    with pytest.raises(mpic.MpicError):
+        mpic.Context(4, 4, 128, mpic.MPIC_BF16, -1.0)
+    ctx = _ctx()
+    with pytest.raises(mpic.MpicError):
+        mpic.Plan(ctx, [[("text", -1)]], 4)
+    with pytest.raises(mpic.MpicError):
+        mpic.Plan(ctx, [[("chunk", -2, 4, None)]], 4)
+    with pytest.raises(mpic.MpicError):
+        mpic.Plan(ctx, [[("text", 3)]], -1)
+    paged = _ctx(page_size=16)
+    with pytest.raises(mpic.MpicError):
+        mpic.Plan(paged, [[("text", 40)]], 0, [np.array([0, 1], np.int32)], 8)       # table too short
+    with pytest.raises(mpic.MpicError):
+        mpic.Plan(paged, [[("text", 40)]], 0, [np.array([0, 1, 1], np.int32)], 8)    # page used twice
+    with pytest.raises(mpic.MpicError):
+        mpic.Plan(paged, [[("text", 40)]], 0, [np.array([0, 1, 9], np.int32)], 8)    # id out of range
+    with pytest.raises(mpic.MpicError):
+        mpic.Plan(paged, [[("text", 20)], [("text", 20)]], 0,
+                  [np.array([0, 1], np.int32), np.array([1, 2], np.int32)], 8)        # shared between requests
+    assert "page" in mpic.mpic_last_error(paged.handle)
+    assert mpic.mpic_strerror(-2) == "unsupported configuration"
+
+
+def test_empty_recompute_set_and_empty_request():
+    ctx = _ctx()
+    p = mpic.Plan(ctx, [[("chunk", 0, 5, None)], []], 0)
+    assert len(p.get("q_pos")) == 0 and p.get("attn_tiles").shape == (0, 8)
+    assert p.get("ctx_off").tolist() == [0, 5, 5]
