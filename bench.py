@@ -1,0 +1,240 @@
+#!/usr/bin/env python3
+"""Benchmark of the selective-recompute prefill hot path on one MI355X.
+
+One step = one layer of one batch: mpic_assemble_kv (gather of cached chunks, rotary
+shift of the keys, scatter of the fresh rows) followed by mpic_selective_attn.  The
+integer plan is built once per batch and reused by every step, as the method reuses
+it for every layer; its cost is reported separately (plan_ms, first_layer_ms).
+Inputs are seeded synthetic tensors resident in HBM before the timed region.  The
+steps cycle over several distinct layer input sets so that no step finds its inputs
+in the last-level cache left by the previous one.
+
+Prints ONE JSON line (see the keys below).  `value` is the causal-exact attention
+work of a step divided by the time of the whole step.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=60)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=3, help="workload id (BASELINE.json configs, 1-based)")
+    ap.add_argument("--layers", type=int, default=4, help="distinct layer input sets the steps cycle over")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-host-sourced", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch a plain elementwise copy of 512 MiB (reads and writes 512 MiB per "
+                         "launch): the reference dispatch for scaling hardware traffic counters")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        return 2
+    import torch
+    import workloads
+    import paper_2502_01960_amd as mpic
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 1
+    mpic.load_library()  # fails loudly if the HIP library is not built
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    sh = workloads.shape(args.config)
+    if sh.dtype != "bf16":
+        print("bench.py: the timed workloads are the bf16 configurations (2-5)", file=sys.stderr)
+        return 2
+    requests, n_src, src_len = workloads.layout(args.config)
+    lens = [workloads.request_len(r) for r in requests]
+    tables, pool = (None, 0)
+    if sh.page_size:
+        tables, pool = workloads.gen_page_tables(sh, lens)
+    n_slots = pool * sh.page_size if sh.page_size else sum(lens)
+
+    ctx = mpic.Context(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, mpic.MPIC_BF16, sh.rope_theta, 0, sh.page_size)
+    t0 = time.perf_counter()
+    plan = mpic.Plan(ctx, requests, sh.default_k, tables, pool)
+    plan_ms = (time.perf_counter() - t0) * 1e3
+    q_off = plan.get("q_off")
+    q_pos = plan.get("q_pos").astype(np.int64)
+    n_q, n_ctx = int(q_off[-1]), int(sum(lens))
+    used_src = sorted(set(plan.get("inst_src").tolist()))
+
+    # ---- inputs: `layers` distinct sets, all resident in HBM -----------------
+    L = max(1, args.layers)
+    sets = []
+    host_chunks0 = None
+    for layer in range(L):
+        chunks = {s: workloads.gen_chunk(sh, layer, s, src_len[s]) for s in used_src}
+        if layer == 0:
+            host_chunks0 = chunks
+        srcs = [tuple(t.to(dev) for t in chunks[s]) if s in chunks else (None, None) for s in range(n_src)]
+        fresh = [workloads.gen_fresh(sh, layer, b, int(q_off[b + 1] - q_off[b])) for b in range(len(requests))]
+        q = torch.cat([f[0] for f in fresh]).to(dev)
+        fk = torch.cat([f[1] for f in fresh]).to(dev)
+        fv = torch.cat([f[2] for f in fresh]).to(dev)
+        k_ctx = torch.empty((n_slots, sh.n_kv_heads, sh.head_dim), dtype=torch.bfloat16, device=dev)
+        v_ctx = torch.empty_like(k_ctx)
+        out = torch.empty_like(q)
+        sets.append(dict(srcs=srcs, q=q, fk=fk, fv=fv, k_ctx=k_ctx, v_ctx=v_ctx, out=out))
+    stream = torch.cuda.current_stream()
+
+    def assemble(s, srcs=None):
+        mpic.mpic_assemble_kv(ctx.handle, plan.handle, srcs or s["srcs"], s["fk"], s["fv"], s["k_ctx"], s["v_ctx"], stream)
+
+    def attend(s):
+        mpic.mpic_selective_attn(ctx.handle, plan.handle, s["q"], s["k_ctx"], s["v_ctx"], sh.softmax_scale,
+                                 s["out"], None, stream)
+
+    # first layer end to end (plan + upload of the plan + link + attention)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    assemble(sets[0]); attend(sets[0])
+    torch.cuda.synchronize()
+    first_layer_ms = plan_ms + (time.perf_counter() - t0) * 1e3
+
+    # ---- whole steps -----------------------------------------------------------
+    for i in range(args.warmup):
+        s = sets[i % L]; assemble(s); attend(s)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        s = sets[i % L]; assemble(s); attend(s)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # ---- per-kernel durations with events on the launch stream -----------------
+    def timed(fn, n):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record(stream)
+        for i in range(n):
+            fn(sets[i % L])
+        e1.record(stream)
+        e1.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    attn_ms = timed(attend, args.steps)
+    asm_ms = timed(assemble, args.steps)
+
+    if args.calibrate_copy:
+        x = torch.zeros(256 * 1024 * 1024, dtype=torch.bfloat16, device=dev)
+        y = torch.empty_like(x)
+        for _ in range(5):
+            torch.add(x, 1.0, out=y)
+        torch.cuda.synchronize()
+        del x, y
+
+    # ---- algorithmic work ------------------------------------------------------
+    # attention: 2*D flops for q.k and 2*D for p.v per visible (row, head, key)
+    pairs = int((q_pos + 1).sum())
+    attn_flops = 4.0 * sh.head_dim * sh.n_q_heads * pairs
+    # linking: every context row is read once from its source and written once, K and V
+    row_bytes = sh.n_kv_heads * sh.head_dim * 2
+    asm_bytes = 4.0 * n_ctx * row_bytes
+    attn_tflops = attn_flops / (attn_ms * 1e-3) / 1e12
+    asm_gbs = asm_bytes / (asm_ms * 1e-3) / 1e9
+    value = attn_flops / (ms_per_step * 1e-3) / 1e12
+
+    # ---- host-sourced chunks (PCIe inclusive; never `value`) -------------------
+    host = None
+    if not args.no_host_sourced:
+        pinned = [tuple(t.pin_memory() for t in host_chunks0[s]) if s in host_chunks0 else (None, None)
+                  for s in range(n_src)]
+        n_h = max(3, min(10, args.steps))
+        for _ in range(2):
+            assemble(sets[0], pinned); attend(sets[0])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n_h):
+            assemble(sets[0], pinned); attend(sets[0])
+        torch.cuda.synchronize()
+        h_ms = (time.perf_counter() - t0) * 1e3 / n_h
+        inst_src, inst_len, inst_k = plan.get("inst_src"), plan.get("inst_len"), plan.get("inst_k")
+        copied = sum(2 * src_len[s] * row_bytes for s in set(inst_src[inst_k < inst_len].tolist()))
+        host = dict(ms_per_step=round(h_ms, 4), pcie_bytes=int(copied),
+                    pcie_GBps=round(copied / (h_ms * 1e-3) / 1e9, 2), steps=n_h,
+                    note="cached chunks in pinned host memory, whole chunks staged over the side stream")
+
+    # ---- the oracle on the host cores (reported baseline, bounded sample) ------
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import attend as o_attend, build_plan, link_kv
+        one = [requests[0]]
+        oplan = build_plan(one, sh.default_k)
+        f64 = lambda t: t.to(torch.float64).numpy()
+        ck = {s: f64(host_chunks0[s][0]) for s in set(oplan["inst_src"].tolist())}
+        cv = {s: f64(host_chunks0[s][1]) for s in set(oplan["inst_src"].tolist())}
+        nq0 = int(oplan["q_off"][1])
+        fq, fk, fv = workloads.gen_fresh(sh, 0, 0, nq0)
+        t0 = time.perf_counter()
+        K, V = link_kv(oplan, ck, cv, f64(fk), f64(fv), sh.rope_theta)
+        rows = np.arange(0, nq0)
+        o_attend(f64(fq), K, V, oplan, sh.softmax_scale, rows=rows)
+        dt = time.perf_counter() - t0
+        fl = 4.0 * sh.head_dim * sh.n_q_heads * int((oplan["q_pos"][rows].astype(np.int64) + 1).sum())
+        cpu = dict(value=round(fl / dt / 1e12, 6), unit="TFLOP/s", cores=int(torch.get_num_threads()),
+                   kind="oracle", seconds=round(dt, 2),
+                   sample="request 0 of the batch: float64 link of all rows + attention of every fresh row, all heads")
+
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", "attn_traffic.json")
+    if os.path.exists(tfile):
+        try:
+            traffic = json.load(open(tfile)).get(f"config{args.config}")
+        except Exception:
+            traffic = None
+
+    rec = {
+        "metric": "selective-prefill attention TFLOP/s (link + attention step)",
+        "value": round(value, 3),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"config{args.config}:{sh.name}", "batch": len(requests), "tokens_per_request": lens[0],
+                   "recompute_rows": n_q, "q_heads": sh.n_q_heads, "kv_heads": sh.n_kv_heads, "head_dim": sh.head_dim,
+                   "k": sh.default_k, "page_size": sh.page_size, "layer_sets": L,
+                   "chunks": "HBM-resident", "plan": "built once per batch, reused by every step"},
+        "roofline": {"bound": "mfma", "achieved": round(attn_tflops, 3), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 5), "traffic": traffic,
+                     "kernel": "attn_bf16_kernel", "avg_launch_ms": round(attn_ms, 5)},
+        "cpu_baseline": cpu,
+        "attention": {"ms": round(attn_ms, 5), "TFLOPs": round(attn_tflops, 3),
+                      "pct_mfma_peak": round(100 * attn_tflops / PEAK_BF16_TFLOPS, 3), "flops": attn_flops},
+        "assembly": {"ms": round(asm_ms, 5), "GBps": round(asm_gbs, 2), "pct_hbm_peak": round(100 * asm_gbs / PEAK_HBM_GBS, 3),
+                     "bytes": asm_bytes},
+        "plan_ms": round(plan_ms, 4),
+        "first_layer_ms": round(first_layer_ms, 4),
+        "host_sourced": host,
+    }
+    print(json.dumps(rec))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
