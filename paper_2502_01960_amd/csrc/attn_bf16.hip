@@ -7,7 +7,9 @@
 // Work decomposition.  A workgroup (4 wavefronts) owns one tile of the plan: up to
 // 128 "flattened rows" (fresh row x query head of one kv group) of one request and
 // kv head, all of which read the same K/V.  Each wavefront owns 32 of those rows and
-// walks the keys 0..n_keys-1 in blocks of 64 that the workgroup stages through LDS.
+// walks the keys 0..n_keys-1 in blocks of 64 that the workgroup stages through LDS
+// with direct global->LDS loads (no register round trip), double buffered so that
+// one barrier per block suffices.
 //
 // Matrix-core formulation (v_mfma_f32_32x32x16_bf16, verified lane layout:
 // A[i][k]: lane i + 32*(k/8), element k%8;  B[k][j]: lane j + 32*(k/8), element k%8;
@@ -34,15 +36,23 @@ typedef float f32x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int D = 128;            // head dim
-constexpr int BN = 64;            // keys per LDS stage
-constexpr int LDS_STRIDE = D + 8; // bf16 elements per staged row (272 B: 16-byte reads of
-                                  // consecutive rows fall into different bank groups)
+constexpr int D = 128;   // head dim
+constexpr int BN = 64;   // keys per LDS stage
 constexpr int WAVES = 4;
 constexpr int ROWS_PER_WAVE = 32;
+constexpr int ROW_BYTES = D * 2;             // one staged key or value row
+constexpr int STAGE_ELEMS = BN * D;          // bf16 elements of one staged K or V block
 static_assert(WAVES * ROWS_PER_WAVE == kAttnTileRows, "tile size and kernel shape must agree");
 
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
+#define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
+
+// Staged rows are 256 bytes = 16 columns of 16 bytes, unpadded (the direct
+// global->LDS load writes 64 lanes x 16 bytes contiguously).  Bank conflicts are
+// avoided by storing logical column c of row r at column c ^ swizzle(r); the loader
+// permutes its *global* addresses accordingly.
+__device__ inline int k_swizzle(int row) { return row & 15; }        // 16-byte reads of 8+ consecutive rows
+__device__ inline int v_swizzle(int row) { return (row & 7) << 1; }  // transpose reads: 4 rows x 32 bytes
 
 __device__ inline float wave_min(float x) {
 #pragma unroll
@@ -55,9 +65,10 @@ __device__ inline float wave_max(float x) {
   return x;
 }
 
-__global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
-  __shared__ __attribute__((aligned(16))) __bf16 k_lds[BN * LDS_STRIDE];
-  __shared__ __attribute__((aligned(16))) __bf16 v_lds[BN * LDS_STRIDE];
+__global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
+  // two stages of K and V each: loads of block t+1 fly while block t is consumed
+  __shared__ __attribute__((aligned(1024))) __bf16 k_lds[2 * STAGE_ELEMS];
+  __shared__ __attribute__((aligned(1024))) __bf16 v_lds[2 * STAGE_ELEMS];
 
   const AttnTile tile = a.tiles[blockIdx.x];
   if (tile.n_rows <= 0) return;  // padding entry of the launch order
@@ -70,9 +81,9 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
   const int b = tile.req, g = tile.kv_head;
   const int n_keys = tile.n_keys;
   const int32_t* slot_of = a.dst_slot + a.ctx_off[b];
-  const int64_t row_elems = static_cast<int64_t>(a.n_kv_heads) * D;
-  const __bf16* kbase = static_cast<const __bf16*>(a.k_ctx) + g * D;
-  const __bf16* vbase = static_cast<const __bf16*>(a.v_ctx) + g * D;
+  const int64_t row_bytes = static_cast<int64_t>(a.n_kv_heads) * ROW_BYTES;
+  const char* kbase = static_cast<const char*>(a.k_ctx) + g * ROW_BYTES;
+  const char* vbase = static_cast<const char*>(a.v_ctx) + g * ROW_BYTES;
 
   // ---- this lane's query ----
   const int local = wave * ROWS_PER_WAVE + col;
@@ -87,53 +98,71 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
   for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16 + hi * 8);
 
   const float posf = static_cast<float>(valid ? my_pos : -1);
-  const int wave_hi_pos = static_cast<int>(wave_max(posf));                       // -1: idle wave
+  const int wave_hi_pos = static_cast<int>(wave_max(posf));  // -1: idle wave
   const int wave_lo_pos = static_cast<int>(wave_min(valid ? posf : 3.0e9f));
 
   const float scale_log2 = a.scale * 1.4426950408889634f;
-  float m_run = -INFINITY;  // running maximum, in log2 units of the scaled logits
+  float m_run = -INFINITY;  // running maximum of the raw logits (scale > 0 keeps the order)
   float l_run = 0.f;        // this lane's share of the running sum (other share: lane^32)
   f32x16 acc_o[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) acc_o[i] = f32x16{0};
 
-  // ---- staging: each thread moves 4 + 4 units of 16 bytes per key block ----
-  u32x4 kreg[4], vreg[4];
-  auto prefetch = [&](int j0) {
+  // ---- loader: wave w stages rows 16w..16w+15 of K and of V with four 1 KB direct
+  // loads each; lane i of load p owns LDS column i&15 of row 16w + 4p + (i>>4) ----
+  const int ld_row = wave * 16 + (lane >> 4);  // + 4p
+  const int ld_col = lane & 15;
+  int slots[4];
+  auto fetch_slots = [&](int j0) {
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-      const int idx = p * 256 + tid;
-      int key = j0 + (idx >> 4);
+      int key = j0 + ld_row + 4 * p;
       key = key < n_keys ? key : n_keys - 1;  // clamped rows are never visible to a valid query
-      const int64_t off = static_cast<int64_t>(slot_of[key]) * row_elems + (idx & 15) * 8;
-      kreg[p] = *reinterpret_cast<const u32x4*>(kbase + off);
-      vreg[p] = *reinterpret_cast<const u32x4*>(vbase + off);
+      slots[p] = slot_of[key];
     }
   };
-  auto stage = [&]() {
+  auto issue_loads = [&](int stage) {
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-      const int idx = p * 256 + tid;
-      const int o = (idx >> 4) * LDS_STRIDE + (idx & 15) * 8;
-      *reinterpret_cast<u32x4*>(k_lds + o) = kreg[p];
-      *reinterpret_cast<u32x4*>(v_lds + o) = vreg[p];
+      const int row = ld_row + 4 * p;
+      const int64_t off = static_cast<int64_t>(slots[p]) * row_bytes;
+      const int lds_row = (stage * BN + wave * 16 + 4 * p) * D;  // wave-uniform destination
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(kbase + off + ((ld_col ^ k_swizzle(row)) << 4)),
+                                       LDS_PTR(void, k_lds + lds_row), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(vbase + off + ((ld_col ^ v_swizzle(row)) << 4)),
+                                       LDS_PTR(void, v_lds + lds_row), 16, 0, 0);
     }
   };
 
-  // LDS offsets (elements) of this lane's operand fragments
-  const int k_frag = col * LDS_STRIDE + hi * 8;  // + kb*32*LDS_STRIDE + ks*16
-  // transpose read: 16 lanes fetch a 4-key x 16-d patch; lane i of the patch ends up with
-  // d = patch_d0 + i and the four keys
+  // ---- LDS byte offsets of this lane's operand fragments ----
+  // K (A operand of S^T): row kb*32 + col, logical column 2*ks + hi
+  const int k_row_off = col * ROW_BYTES;
+  const int k_col_x = hi ^ k_swizzle(col);  // ^ (ks << 1) per step
+  // V^T (A operand of O^T) through the transpose read: 16 lanes fetch a 4-key x 16-d
+  // patch, lane i of the patch supplies the address of key i/4, d-offset 4*(i%4) and
+  // receives d = patch_d0 + i for the four keys.
   const int i16 = lane & 15;
-  const int v_frag = (hi * 4 + (i16 >> 2)) * LDS_STRIDE + ((lane >> 4) & 1) * 16 + (i16 & 3) * 4;
+  const int v_row = hi * 4 + (i16 >> 2);                      // + kh*16 (+8)
+  const int v_col_x = ((((lane >> 4) & 1) << 1) | ((i16 & 3) >> 1)) ^ v_swizzle(v_row);  // ^ (db << 2)
+  const int v_off = v_row * ROW_BYTES + (i16 & 1) * 8;
 
-  prefetch(0);
-  for (int j0 = 0; j0 < n_keys; j0 += BN) {
-    __syncthreads();  // previous block fully consumed
-    stage();
-    __syncthreads();
-    if (j0 + BN < n_keys) prefetch(j0 + BN);
+  const int n_iter = (n_keys + BN - 1) / BN;
+  fetch_slots(0);
+  issue_loads(0);
+  if (n_iter > 1) fetch_slots(BN);
+  for (int it = 0; it < n_iter; ++it) {
+    const int j0 = it * BN;
+    const int stage = it & 1;
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of block `it` is in LDS
+    __syncthreads();                     // everyone's share is; the other stage is free again
+    if (it + 1 < n_iter) {
+      issue_loads(stage ^ 1);
+      if (it + 2 < n_iter) fetch_slots(j0 + 2 * BN);
+    }
     if (j0 > wave_hi_pos) continue;  // nothing visible to this wave any more (barriers stay aligned)
+
+    const char* ks_base = reinterpret_cast<const char*>(k_lds + stage * STAGE_ELEMS) + k_row_off;
+    const char* vs_base = reinterpret_cast<const char*>(v_lds + stage * STAGE_ELEMS) + v_off;
 
     // S^T = K . Q^T for 64 keys x 32 queries
     f32x16 acc_s[2];
@@ -142,30 +171,38 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
       acc_s[kb] = f32x16{0};
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(k_lds + k_frag + kb * 32 * LDS_STRIDE + ks * 16);
+        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(ks_base + kb * 32 * ROW_BYTES +
+                                                            ((k_col_x ^ (ks << 1)) << 4));
         acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], acc_s[kb], 0, 0, 0);
       }
     }
 
-    // scaled logits in log2 units, causal mask by position on the diagonal blocks only
-    const bool need_mask = j0 + BN - 1 > wave_lo_pos;
+    // causal mask by position, on the diagonal blocks only
+    if (j0 + BN - 1 > wave_lo_pos) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int key = j0 + kb * 32 + (v >> 2) * 8 + hi * 4 + (v & 3);
+          acc_s[kb][v] = key <= my_pos ? acc_s[kb][v] : -INFINITY;
+        }
+    }
     float m_blk = -INFINITY;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        float x = acc_s[kb][v] * scale_log2;
-        if (need_mask) {
-          const int key = j0 + kb * 32 + (v >> 2) * 8 + hi * 4 + (v & 3);
-          x = key <= my_pos ? x : -INFINITY;
-        }
-        acc_s[kb][v] = x;
-        m_blk = fmaxf(m_blk, x);
-      }
+      for (int v = 0; v < 16; ++v) m_blk = fmaxf(m_blk, acc_s[kb][v]);
     m_blk = fmaxf(m_blk, __shfl_xor(m_blk, 32));
-    const float m_new = fmaxf(m_run, m_blk);
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);  // first block: exp2(-inf) = 0
-    m_run = m_new;
+    // rescale only when some query of the wave has a new maximum (alpha = 1 otherwise)
+    if (__builtin_amdgcn_ballot_w64(m_blk > m_run) != 0) {
+      const float m_new = fmaxf(m_run, m_blk);
+      const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2);  // first block: 0
+      m_run = m_new;
+      l_run *= alpha;
+#pragma unroll
+      for (int db = 0; db < 4; ++db) acc_o[db] *= alpha;
+    }
+    const float m_scaled = m_run * scale_log2;
     float l_blk = 0.f;
     bf16x8 pf[4];
 #pragma unroll
@@ -175,23 +212,21 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
         f32x8 p;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          p[e] = __builtin_amdgcn_exp2f(acc_s[kb][half * 8 + e] - m_new);
+          p[e] = __builtin_amdgcn_exp2f(fmaf(acc_s[kb][half * 8 + e], scale_log2, -m_scaled));
           l_blk += p[e];
         }
         pf[kb * 2 + half] = __builtin_convertvector(p, bf16x8);
       }
-    l_run = l_run * alpha + l_blk;
-#pragma unroll
-    for (int db = 0; db < 4; ++db) acc_o[db] *= alpha;
+    l_run += l_blk;
 
     // O^T += V^T . P^T
 #pragma unroll
     for (int kh = 0; kh < 4; ++kh) {  // 16 keys each: kb = kh/2, half = kh%2
 #pragma unroll
       for (int db = 0; db < 4; ++db) {
-        const __bf16* vp = v_lds + v_frag + kh * 16 * LDS_STRIDE + db * 32;
+        const char* vp = vs_base + kh * 16 * ROW_BYTES + ((v_col_x ^ (db << 2)) << 4);
         const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, vp));
-        const s16x4 up = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, vp + 8 * LDS_STRIDE));
+        const s16x4 up = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, vp + 8 * ROW_BYTES));
         const s16x8 both = __builtin_shufflevector(lo, up, 0, 1, 2, 3, 4, 5, 6, 7);
         acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf[kh],
                                                             acc_o[db], 0, 0, 0);
@@ -214,7 +249,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
       *reinterpret_cast<bf16x4*>(op + db * 32 + q4 * 8 + hi * 4) = __builtin_convertvector(o, bf16x4);
     }
   if (a.lse && hi == 0)
-    a.lse[fresh_row * a.n_q_heads + head] = (m_run + log2f(l_tot)) * 0.6931471805599453f;
+    a.lse[fresh_row * a.n_q_heads + head] = m_run * a.scale + logf(l_tot);
 }
 
 }  // namespace
