@@ -42,6 +42,7 @@ constexpr int WAVES = 4;
 constexpr int ROWS_PER_WAVE = 32;
 constexpr int ROW_BYTES = D * 2;             // one staged key or value row
 constexpr int STAGE_ELEMS = BN * D;          // bf16 elements of one staged K or V block
+constexpr float kSlack = 8.0f;               // lazy-rescale threshold, log2 units
 static_assert(WAVES * ROWS_PER_WAVE == kAttnTileRows, "tile size and kernel shape must agree");
 
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
@@ -67,13 +68,17 @@ __device__ inline float wave_max(float x) {
 
 __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   // two stages of K and V each: loads of block t+1 fly while block t is consumed
-  __shared__ __attribute__((aligned(1024))) __bf16 k_lds[2 * STAGE_ELEMS];
-  __shared__ __attribute__((aligned(1024))) __bf16 v_lds[2 * STAGE_ELEMS];
+  // (separate arrays per stage: the compiler can then tell that reads of one stage do
+  // not have to wait for the direct loads in flight into the other)
+  __shared__ __attribute__((aligned(1024))) __bf16 k_lds0[STAGE_ELEMS];
+  __shared__ __attribute__((aligned(1024))) __bf16 k_lds1[STAGE_ELEMS];
+  __shared__ __attribute__((aligned(1024))) __bf16 v_lds0[STAGE_ELEMS];
+  __shared__ __attribute__((aligned(1024))) __bf16 v_lds1[STAGE_ELEMS];
 
   const AttnTile tile = a.tiles[blockIdx.x];
   if (tile.n_rows <= 0) return;  // padding entry of the launch order
   const int tid = threadIdx.x;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63;
   const int col = lane & 31;  // query column owned by this lane
   const int hi = lane >> 5;   // which half of the contraction index this lane feeds
@@ -121,16 +126,16 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
       slots[p] = slot_of[key];
     }
   };
-  auto issue_loads = [&](int stage) {
+  auto issue_loads = [&](__bf16* k_dst, __bf16* v_dst) {
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
       const int row = ld_row + 4 * p;
       const int64_t off = static_cast<int64_t>(slots[p]) * row_bytes;
-      const int lds_row = (stage * BN + wave * 16 + 4 * p) * D;  // wave-uniform destination
+      const int lds_row = (wave * 16 + 4 * p) * D;  // wave-uniform destination
       __builtin_amdgcn_global_load_lds(GLOBAL_PTR(kbase + off + ((ld_col ^ k_swizzle(row)) << 4)),
-                                       LDS_PTR(void, k_lds + lds_row), 16, 0, 0);
+                                       LDS_PTR(void, k_dst + lds_row), 16, 0, 0);
       __builtin_amdgcn_global_load_lds(GLOBAL_PTR(vbase + off + ((ld_col ^ v_swizzle(row)) << 4)),
-                                       LDS_PTR(void, v_lds + lds_row), 16, 0, 0);
+                                       LDS_PTR(void, v_dst + lds_row), 16, 0, 0);
     }
   };
 
@@ -147,22 +152,19 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   const int v_off = v_row * ROW_BYTES + (i16 & 1) * 8;
 
   const int n_iter = (n_keys + BN - 1) / BN;
-  fetch_slots(0);
-  issue_loads(0);
-  if (n_iter > 1) fetch_slots(BN);
-  for (int it = 0; it < n_iter; ++it) {
+  // one key block: wait for it, start the next one into the other stage, consume it
+  auto block = [&](int it, const __bf16* k_cur, const __bf16* v_cur, __bf16* k_nxt, __bf16* v_nxt) {
     const int j0 = it * BN;
-    const int stage = it & 1;
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of block `it` is in LDS
     __syncthreads();                     // everyone's share is; the other stage is free again
     if (it + 1 < n_iter) {
-      issue_loads(stage ^ 1);
+      issue_loads(k_nxt, v_nxt);
       if (it + 2 < n_iter) fetch_slots(j0 + 2 * BN);
     }
-    if (j0 > wave_hi_pos) continue;  // nothing visible to this wave any more (barriers stay aligned)
+    if (j0 > wave_hi_pos) return;  // nothing visible to this wave any more (barriers stay aligned)
 
-    const char* ks_base = reinterpret_cast<const char*>(k_lds + stage * STAGE_ELEMS) + k_row_off;
-    const char* vs_base = reinterpret_cast<const char*>(v_lds + stage * STAGE_ELEMS) + v_off;
+    const char* ks_base = reinterpret_cast<const char*>(k_cur) + k_row_off;
+    const char* vs_base = reinterpret_cast<const char*>(v_cur) + v_off;
 
     // S^T = K . Q^T for 64 keys x 32 queries
     f32x16 acc_s[2];
@@ -193,8 +195,11 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) m_blk = fmaxf(m_blk, acc_s[kb][v]);
     m_blk = fmaxf(m_blk, __shfl_xor(m_blk, 32));
-    // rescale only when some query of the wave has a new maximum (alpha = 1 otherwise)
-    if (__builtin_amdgcn_ballot_w64(m_blk > m_run) != 0) {
+    // Lazy rescale: the reference point m_run only moves when some query's block maximum
+    // exceeds it by more than kSlack (in log2 units), so probabilities are at most
+    // 2^kSlack before normalisation -- exact in the end because numerator and
+    // denominator share the reference point.
+    if (__builtin_amdgcn_ballot_w64((m_blk - m_run) * scale_log2 > kSlack) != 0) {
       const float m_new = fmaxf(m_run, m_blk);
       const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2);  // first block: 0
       m_run = m_new;
@@ -232,6 +237,14 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
                                                             acc_o[db], 0, 0, 0);
       }
     }
+  };
+
+  fetch_slots(0);
+  issue_loads(k_lds0, v_lds0);
+  if (n_iter > 1) fetch_slots(BN);
+  for (int it = 0; it < n_iter; it += 2) {
+    block(it, k_lds0, v_lds0, k_lds1, v_lds1);
+    if (it + 1 < n_iter) block(it + 1, k_lds1, v_lds1, k_lds0, v_lds0);
   }
 
   // ---- epilogue: normalise and store this lane's query column ----
