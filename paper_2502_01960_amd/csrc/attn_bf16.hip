@@ -53,7 +53,7 @@ static_assert(WAVES * ROWS_PER_WAVE == kAttnTileRows, "tile size and kernel shap
 // avoided by storing logical column c of row r at column c ^ swizzle(r); the loader
 // permutes its *global* addresses accordingly.
 __device__ inline int k_swizzle(int row) { return row & 15; }        // 16-byte reads of 8+ consecutive rows
-__device__ inline int v_swizzle(int row) { return (row & 7) << 1; }  // transpose reads: 4 rows x 32 bytes
+__device__ inline int v_swizzle(int row) { return (row & 3) << 2; }  // transpose reads: 32 lanes = 4 rows x 64 bytes
 
 __device__ inline float wave_min(float x) {
 #pragma unroll
