@@ -166,18 +166,46 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     const char* ks_base = reinterpret_cast<const char*>(k_cur) + k_row_off;
     const char* vs_base = reinterpret_cast<const char*>(v_cur) + v_off;
 
-    // S^T = K . Q^T for 64 keys x 32 queries
-    f32x16 acc_s[2];
+    auto k_frag = [&](int kb, int ks) {
+      return *reinterpret_cast<const bf16x8*>(ks_base + kb * 32 * ROW_BYTES + ((k_col_x ^ (ks << 1)) << 4));
+    };
+    auto v_frag = [&](int kh, int db) {
+      const char* vp = vs_base + kh * 16 * ROW_BYTES + ((v_col_x ^ (db << 2)) << 4);
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, vp));
+      const s16x4 up = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, vp + 8 * ROW_BYTES));
+      return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, up, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+
+    // S^T = K . Q^T for 64 keys x 32 queries.  The LDS reads run kPre steps ahead of the
+    // MFMAs that consume them and the two key sub-blocks alternate, so neither the LDS
+    // latency nor the accumulator dependency is exposed; the scheduling barriers pin
+    // that order.
+    constexpr int kPre = 3;
+    f32x16 acc_s[2] = {f32x16{0}, f32x16{0}};
+    bf16x8 kf[2][8];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-      acc_s[kb] = f32x16{0};
-#pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(ks_base + kb * 32 * ROW_BYTES +
-                                                            ((k_col_x ^ (ks << 1)) << 4));
-        acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], acc_s[kb], 0, 0, 0);
-      }
+    for (int ks = 0; ks < kPre; ++ks) {
+      kf[0][ks] = k_frag(0, ks);
+      kf[1][ks] = k_frag(1, ks);
     }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      if (ks + kPre < 8) {
+        kf[0][ks + kPre] = k_frag(0, ks + kPre);
+        kf[1][ks + kPre] = k_frag(1, ks + kPre);
+      }
+      acc_s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0][ks], qf[ks], acc_s[0], 0, 0, 0);
+      acc_s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[1][ks], qf[ks], acc_s[1], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // the first value fragments are fetched now and land while the softmax runs
+    bf16x8 vf[2][4];
+#pragma unroll
+    for (int db = 0; db < 4; ++db) vf[0][db] = v_frag(0, db);
+#pragma unroll
+    for (int db = 0; db < 4; ++db) vf[1][db] = v_frag(1, db);
+    __builtin_amdgcn_sched_barrier(0);
 
     // causal mask by position, on the diagonal blocks only
     if (j0 + BN - 1 > wave_lo_pos) {
@@ -224,18 +252,18 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
       }
     l_run += l_blk;
 
-    // O^T += V^T . P^T
+    // O^T += V^T . P^T, 16 keys per step, fragments of step kh+2 fetched behind step kh
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int kh = 0; kh < 4; ++kh) {  // 16 keys each: kb = kh/2, half = kh%2
+    for (int kh = 0; kh < 4; ++kh) {  // kb = kh/2, half = kh%2
 #pragma unroll
-      for (int db = 0; db < 4; ++db) {
-        const char* vp = vs_base + kh * 16 * ROW_BYTES + ((v_col_x ^ (db << 2)) << 4);
-        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, vp));
-        const s16x4 up = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, vp + 8 * ROW_BYTES));
-        const s16x8 both = __builtin_shufflevector(lo, up, 0, 1, 2, 3, 4, 5, 6, 7);
-        acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf[kh],
-                                                            acc_o[db], 0, 0, 0);
+      for (int db = 0; db < 4; ++db)
+        acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[kh & 1][db], pf[kh], acc_o[db], 0, 0, 0);
+      if (kh + 2 < 4) {
+#pragma unroll
+        for (int db = 0; db < 4; ++db) vf[kh & 1][db] = v_frag(kh + 2, db);
       }
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
 
