@@ -23,6 +23,8 @@ int bind_device(mpic_ctx* ctx) {
   return MPIC_OK;
 }
 
+constexpr size_t kTablePad = 128;
+
 template <typename T>
 size_t padded(size_t n) {
   return (n * sizeof(T) + 255) / 256 * 256;
@@ -35,7 +37,7 @@ int upload_plan(mpic_ctx* ctx, mpic_plan* p) {
     return MPIC_OK;
   }
   const size_t n = p->n_ctx, nq = p->n_q, B = p->n_requests;
-  size_t total = 3 * padded<int32_t>(n) + padded<int32_t>(nq) + 2 * padded<int32_t>(B + 1) +
+  size_t total = 3 * padded<int32_t>(n) + padded<int32_t>(n + kTablePad) + padded<int32_t>(nq) + 2 * padded<int32_t>(B + 1) +
                  2 * padded<float>(p->rope_cos.size()) + padded<AttnTile>(p->tiles.size()) + 256;
   char* base = nullptr;
   hipError_t e = hipMalloc(reinterpret_cast<void**>(&base), total);
@@ -55,6 +57,21 @@ int upload_plan(mpic_ctx* ctx, mpic_plan* p) {
   d.src_inst = static_cast<int32_t*>(put(p->src_inst.data(), n * 4, padded<int32_t>(n)));
   if (e == hipSuccess) d.src_row = static_cast<int32_t*>(put(p->src_row.data(), n * 4, padded<int32_t>(n)));
   if (e == hipSuccess) d.dst_slot = static_cast<int32_t*>(put(p->dst_slot.data(), n * 4, padded<int32_t>(n)));
+  {
+    // byte offset of every context row in 16-byte units (saves the attention kernel a
+    // 64-bit multiply per staged row); fits 32 bits for context buffers below 64 GiB
+    const uint64_t units = static_cast<uint64_t>(ctx->cfg.n_kv_heads) * ctx->cfg.head_dim *
+                           (ctx->cfg.dtype == MPIC_F32 ? 4 : 2) / 16;
+    if (static_cast<uint64_t>(p->max_slot + 1) * units > 0xffffffffull) {
+      (void)hipFree(base);
+      return fail(ctx, MPIC_ERR_UNSUPPORTED, "context buffers of 64 GiB or more are not supported");
+    }
+    // kTablePad zero entries follow the table: the attention kernel fetches offsets eight
+    // at a time and may run up to one key block past the last key of a tile
+    std::vector<uint32_t> off(n + kTablePad, 0u);
+    for (size_t i = 0; i < n; ++i) off[i] = static_cast<uint32_t>(static_cast<uint64_t>(p->dst_slot[i]) * units);
+    if (e == hipSuccess) d.kv_off16 = static_cast<uint32_t*>(put(off.data(), off.size() * 4, padded<int32_t>(off.size())));
+  }
   if (e == hipSuccess) d.q_pos = static_cast<int32_t*>(put(p->q_pos.data(), nq * 4, padded<int32_t>(nq)));
   if (e == hipSuccess) d.q_off = static_cast<int32_t*>(put(p->q_off.data(), (B + 1) * 4, padded<int32_t>(B + 1)));
   if (e == hipSuccess) d.ctx_off = static_cast<int32_t*>(put(p->ctx_off.data(), (B + 1) * 4, padded<int32_t>(B + 1)));
@@ -290,6 +307,7 @@ extern "C" int mpic_selective_attn(mpic_ctx* ctx, mpic_plan* plan, const void* f
   a.q_off = plan->dev.q_off;
   a.ctx_off = plan->dev.ctx_off;
   a.dst_slot = plan->dev.dst_slot;
+  a.kv_off16 = plan->dev.kv_off16;
   a.q = fresh_q;
   a.k_ctx = k_ctx;
   a.v_ctx = v_ctx;

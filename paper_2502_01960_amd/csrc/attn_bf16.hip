@@ -4,12 +4,14 @@
 // whole linked K cache, softmax-normalised over the positions it may see
 // (j <= its own position) and multiplied with the linked V cache.
 //
-// Work decomposition.  A workgroup (4 wavefronts) owns one tile of the plan: up to
-// 128 "flattened rows" (fresh row x query head of one kv group) of one request and
+// Work decomposition.  A workgroup (8 wavefronts) owns one tile of the plan: up to
+// 256 "flattened rows" (fresh row x query head of one kv group) of one request and
 // kv head, all of which read the same K/V.  Each wavefront owns 32 of those rows and
-// walks the keys 0..n_keys-1 in blocks of 64 that the workgroup stages through LDS
-// with direct global->LDS loads (no register round trip), double buffered so that
-// one barrier per block suffices.
+// walks the keys 0..n_keys-1 in blocks of 64 that the workgroup stages through a
+// four-deep LDS ring with direct global->LDS loads (no register round trip): three
+// blocks are in flight while one is consumed, and one barrier per block suffices.
+// The kernel is bound by the L2->LDS stream of K/V blocks as much as by the matrix
+// cores, which is why a tile is as tall as the register file allows.
 //
 // Matrix-core formulation (v_mfma_f32_32x32x16_bf16, verified lane layout:
 // A[i][k]: lane i + 32*(k/8), element k%8;  B[k][j]: lane j + 32*(k/8), element k%8;
@@ -35,25 +37,53 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x8_a4 __attribute__((ext_vector_type(8), aligned(4)));  // eight table entries, dword aligned
 
 constexpr int D = 128;   // head dim
 constexpr int BN = 64;   // keys per LDS stage
-constexpr int WAVES = 4;
+constexpr int WAVES = 8;
 constexpr int ROWS_PER_WAVE = 32;
-constexpr int ROW_BYTES = D * 2;             // one staged key or value row
-constexpr int STAGE_ELEMS = BN * D;          // bf16 elements of one staged K or V block
-constexpr float kSlack = 8.0f;               // lazy-rescale threshold, log2 units
+constexpr int THREADS = WAVES * 64;
+constexpr int ROW_BYTES = D * 2;                 // one staged key or value row
+constexpr int TILE_BYTES = BN * ROW_BYTES;       // one staged K (or V) block: 16 KB
+constexpr int STAGE_BYTES = 2 * TILE_BYTES;      // K block followed by V block
+constexpr int STAGES = 4;                        // ring depth: loads run 3 blocks ahead
+constexpr int LDS_BYTES = STAGES * STAGE_BYTES;  // 128 KB of the CU's 160 KB
+constexpr int LOADS_PER_STAGE = 4;               // direct loads each wave issues per block
+constexpr float kSlack = 8.0f;                   // lazy-rescale threshold, log2 units
 static_assert(WAVES * ROWS_PER_WAVE == kAttnTileRows, "tile size and kernel shape must agree");
 
-#define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
-#define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
+// Phase timing (development builds only, -DMPIC_PHASE_TIMING): per-wave sums of shader
+// clock ticks between marks, written to the lse buffer as [tile][wave][8] floats.
+#ifdef MPIC_PHASE_TIMING
+#define PHASE_DECL unsigned long long ph_t = __builtin_amdgcn_s_memtime(); float ph_sum[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#define PHASE_MARK(i) { const unsigned long long n_ = __builtin_amdgcn_s_memtime(); ph_sum[i] += static_cast<float>(n_ - ph_t); ph_t = n_; }
+#else
+#define PHASE_DECL
+#define PHASE_MARK(i)
+#endif
 
-// Staged rows are 256 bytes = 16 columns of 16 bytes, unpadded (the direct
-// global->LDS load writes 64 lanes x 16 bytes contiguously).  Bank conflicts are
-// avoided by storing logical column c of row r at column c ^ swizzle(r); the loader
-// permutes its *global* addresses accordingly.
-__device__ inline int k_swizzle(int row) { return row & 15; }        // 16-byte reads of 8+ consecutive rows
-__device__ inline int v_swizzle(int row) { return (row & 3) << 2; }  // transpose reads: 32 lanes = 4 rows x 64 bytes
+#define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
+
+// Staged rows are 256 bytes = 16 columns of 16 bytes, unpadded (a direct global->LDS
+// load writes 64 lanes x 16 bytes contiguously).  Bank conflicts are avoided by
+// storing logical column c of row r at column c ^ swizzle(r); the loader permutes its
+// *global* addresses accordingly.
+//   K, read 16 bytes per lane by 16+ consecutive rows:      swizzle = row & 15
+//   V, transpose-read as 4 rows x 64 bytes per 32 lanes:    swizzle = (row & 3) << 2
+
+// Direct global->LDS load of 16 bytes per lane: LDS[m0 + 16*lane] = *gptr.  Written as
+// inline assembly so that the outstanding-load counter is managed by hand below: the
+// compiler would otherwise wait for *all* direct loads before any LDS read, which
+// defeats a ring that keeps three blocks in flight.
+__device__ inline void load_to_lds_16B(const void* gptr, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :
+               : "v"(gptr), "s"(lds_addr)
+               : "memory", "m0");
+}
+// s_waitcnt vmcnt(n) only (expcnt / lgkmcnt fields left at "no wait")
+#define WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
 
 __device__ inline float wave_min(float x) {
 #pragma unroll
@@ -66,14 +96,8 @@ __device__ inline float wave_max(float x) {
   return x;
 }
 
-__global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
-  // two stages of K and V each: loads of block t+1 fly while block t is consumed
-  // (separate arrays per stage: the compiler can then tell that reads of one stage do
-  // not have to wait for the direct loads in flight into the other)
-  __shared__ __attribute__((aligned(1024))) __bf16 k_lds0[STAGE_ELEMS];
-  __shared__ __attribute__((aligned(1024))) __bf16 k_lds1[STAGE_ELEMS];
-  __shared__ __attribute__((aligned(1024))) __bf16 v_lds0[STAGE_ELEMS];
-  __shared__ __attribute__((aligned(1024))) __bf16 v_lds1[STAGE_ELEMS];
+__global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a) {
+  extern __shared__ __attribute__((aligned(1024))) char lds[];  // LDS_BYTES: ring of K|V blocks
 
   const AttnTile tile = a.tiles[blockIdx.x];
   if (tile.n_rows <= 0) return;  // padding entry of the launch order
@@ -85,10 +109,13 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   const int group = a.n_q_heads / a.n_kv_heads;
   const int b = tile.req, g = tile.kv_head;
   const int n_keys = tile.n_keys;
-  const int32_t* slot_of = a.dst_slot + a.ctx_off[b];
-  const int64_t row_bytes = static_cast<int64_t>(a.n_kv_heads) * ROW_BYTES;
+  // context row offsets in 16-byte units; read with scalar loads (the table is padded so
+  // that reading up to 64 entries past the last key of the tile stays in bounds)
+  const __attribute__((address_space(4))) uint32_t* off_of =
+      (const __attribute__((address_space(4))) uint32_t*)(a.kv_off16 + a.ctx_off[b]);
   const char* kbase = static_cast<const char*>(a.k_ctx) + g * ROW_BYTES;
   const char* vbase = static_cast<const char*>(a.v_ctx) + g * ROW_BYTES;
+  const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(LDS_PTR(char, lds)));
 
   // ---- this lane's query ----
   const int local = wave * ROWS_PER_WAVE + col;
@@ -107,65 +134,75 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   const int wave_lo_pos = static_cast<int>(wave_min(valid ? posf : 3.0e9f));
 
   const float scale_log2 = a.scale * 1.4426950408889634f;
-  float m_run = -INFINITY;  // running maximum of the raw logits (scale > 0 keeps the order)
+  float m_run = -INFINITY;  // running reference maximum of the raw logits (scale > 0 keeps the order)
   float l_run = 0.f;        // this lane's share of the running sum (other share: lane^32)
   f32x16 acc_o[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) acc_o[i] = f32x16{0};
 
-  // ---- loader: wave w stages rows 16w..16w+15 of K and of V with four 1 KB direct
-  // loads each; lane i of load p owns LDS column i&15 of row 16w + 4p + (i>>4) ----
-  const int ld_row = wave * 16 + (lane >> 4);  // + 4p
-  const int ld_col = lane & 15;
-  int slots[4];
-  auto fetch_slots = [&](int j0) {
+  // ---- loader: wave w stages rows 8w..8w+7 of K and of V with two 1 KB direct loads
+  // each; lane i of load p owns LDS column i&15 of row 8w + 4p + (i>>4) ----
+  const int ld_sub = lane >> 4;
+  const uint32_t ld_col = lane & 15;
+  const uint32_t ld_k16 = ld_col ^ ld_sub ^ ((wave & 1) << 3);  // ^ (4p): K swizzle = row & 15
+  const uint32_t ld_v16 = ld_col ^ (ld_sub << 2);               //          V swizzle = (row & 3) << 2
+  auto issue_loads = [&](int blk) {
+    // row offsets of this wave's eight rows: one scalar load
+    const int first = blk * BN + wave * 8;
+    const u32x8_a4 ro = *reinterpret_cast<const __attribute__((address_space(4))) u32x8_a4*>(off_of + first);
+    const uint32_t dst = lds_base + (blk % STAGES) * STAGE_BYTES + wave * 8 * ROW_BYTES;
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      int key = j0 + ld_row + 4 * p;
-      key = key < n_keys ? key : n_keys - 1;  // clamped rows are never visible to a valid query
-      slots[p] = slot_of[key];
-    }
-  };
-  auto issue_loads = [&](__bf16* k_dst, __bf16* v_dst) {
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      const int row = ld_row + 4 * p;
-      const int64_t off = static_cast<int64_t>(slots[p]) * row_bytes;
-      const int lds_row = (wave * 16 + 4 * p) * D;  // wave-uniform destination
-      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(kbase + off + ((ld_col ^ k_swizzle(row)) << 4)),
-                                       LDS_PTR(void, k_dst + lds_row), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(vbase + off + ((ld_col ^ v_swizzle(row)) << 4)),
-                                       LDS_PTR(void, v_dst + lds_row), 16, 0, 0);
+    for (int p = 0; p < 2; ++p) {
+      const uint32_t r16 = ld_sub == 0 ? ro[4 * p] : ld_sub == 1 ? ro[4 * p + 1] : ld_sub == 2 ? ro[4 * p + 2] : ro[4 * p + 3];
+      load_to_lds_16B(kbase + (static_cast<uint64_t>(r16 + (ld_k16 ^ (4 * p))) << 4), dst + p * 4 * ROW_BYTES);
+      load_to_lds_16B(vbase + (static_cast<uint64_t>(r16 + ld_v16) << 4), dst + TILE_BYTES + p * 4 * ROW_BYTES);
     }
   };
 
   // ---- LDS byte offsets of this lane's operand fragments ----
   // K (A operand of S^T): row kb*32 + col, logical column 2*ks + hi
   const int k_row_off = col * ROW_BYTES;
-  const int k_col_x = hi ^ k_swizzle(col);  // ^ (ks << 1) per step
+  const int k_col_x = hi ^ (col & 15);  // ^ (ks << 1) per step
   // V^T (A operand of O^T) through the transpose read: 16 lanes fetch a 4-key x 16-d
   // patch, lane i of the patch supplies the address of key i/4, d-offset 4*(i%4) and
   // receives d = patch_d0 + i for the four keys.
   const int i16 = lane & 15;
-  const int v_row = hi * 4 + (i16 >> 2);                      // + kh*16 (+8)
-  const int v_col_x = ((((lane >> 4) & 1) << 1) | ((i16 & 3) >> 1)) ^ v_swizzle(v_row);  // ^ (db << 2)
-  const int v_off = v_row * ROW_BYTES + (i16 & 1) * 8;
+  const int v_row = hi * 4 + (i16 >> 2);                                                   // + kh*16 (+8)
+  const int v_col_x = ((((lane >> 4) & 1) << 1) | ((i16 & 3) >> 1)) ^ ((v_row & 3) << 2);  // ^ (db << 2)
+  const int v_off = TILE_BYTES + v_row * ROW_BYTES + (i16 & 1) * 8;
 
   const int n_iter = (n_keys + BN - 1) / BN;
-  // one key block: wait for it, start the next one into the other stage, consume it
-  auto block = [&](int it, const __bf16* k_cur, const __bf16* v_cur, __bf16* k_nxt, __bf16* v_nxt) {
+  PHASE_DECL
+  // every ordinary load (query fragments, positions) is complete before the first direct
+  // load is issued: from here on the outstanding-load counter only counts ring traffic
+  WAIT_VMCNT(0);
+  __builtin_amdgcn_sched_barrier(0);
+  issue_loads(0);
+  if (n_iter > 1) issue_loads(1);
+  if (n_iter > 2) issue_loads(2);
+
+  for (int it = 0; it < n_iter; ++it) {
     const int j0 = it * BN;
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of block `it` is in LDS
-    __syncthreads();                     // everyone's share is; the other stage is free again
-    if (it + 1 < n_iter) {
-      issue_loads(k_nxt, v_nxt);
-      if (it + 2 < n_iter) fetch_slots(j0 + 2 * BN);
+    PHASE_MARK(0)
+    // this wave's share of block `it` has landed when at most the loads of the younger
+    // blocks are still outstanding
+    if (it + 2 < n_iter) {
+      WAIT_VMCNT(2 * LOADS_PER_STAGE);
+    } else if (it + 1 < n_iter) {
+      WAIT_VMCNT(LOADS_PER_STAGE);
+    } else {
+      WAIT_VMCNT(0);
     }
-    if (j0 > wave_hi_pos) return;  // nothing visible to this wave any more (barriers stay aligned)
+    PHASE_MARK(1)
+    __syncthreads();  // everyone's share has; the stage consumed in the previous round is free
+    PHASE_MARK(2)
+    if (it + STAGES - 1 < n_iter) issue_loads(it + STAGES - 1);
+    PHASE_MARK(3)
+    if (j0 > wave_hi_pos) continue;  // nothing visible to this wave any more (barriers stay aligned)
 
-    const char* ks_base = reinterpret_cast<const char*>(k_cur) + k_row_off;
-    const char* vs_base = reinterpret_cast<const char*>(v_cur) + v_off;
-
+    const char* stage = lds + (it % STAGES) * STAGE_BYTES;
+    const char* ks_base = stage + k_row_off;
+    const char* vs_base = stage + v_off;
     auto k_frag = [&](int kb, int ks) {
       return *reinterpret_cast<const bf16x8*>(ks_base + kb * 32 * ROW_BYTES + ((k_col_x ^ (ks << 1)) << 4));
     };
@@ -199,6 +236,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
       acc_s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[1][ks], qf[ks], acc_s[1], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
+    PHASE_MARK(4)
     // the first value fragments are fetched now and land while the softmax runs
     bf16x8 vf[2][4];
 #pragma unroll
@@ -252,6 +290,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
       }
     l_run += l_blk;
 
+    PHASE_MARK(5)
     // O^T += V^T . P^T, 16 keys per step, fragments of step kh+2 fetched behind step kh
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -265,16 +304,15 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
       }
       __builtin_amdgcn_sched_barrier(0);
     }
-  };
-
-  fetch_slots(0);
-  issue_loads(k_lds0, v_lds0);
-  if (n_iter > 1) fetch_slots(BN);
-  for (int it = 0; it < n_iter; it += 2) {
-    block(it, k_lds0, v_lds0, k_lds1, v_lds1);
-    if (it + 1 < n_iter) block(it + 1, k_lds1, v_lds1, k_lds0, v_lds0);
+    PHASE_MARK(6)
   }
 
+#ifdef MPIC_PHASE_TIMING
+  if (lane == 0 && a.lse) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) a.lse[(static_cast<int64_t>(blockIdx.x) * WAVES + wave) * 8 + i] = ph_sum[i];
+  }
+#endif
   // ---- epilogue: normalise and store this lane's query column ----
   if (!valid) return;
   const float l_tot = l_run + __shfl_xor(l_run, 32);
@@ -289,15 +327,28 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
       for (int e = 0; e < 4; ++e) o[e] = acc_o[db][q4 * 4 + e] * inv;
       *reinterpret_cast<bf16x4*>(op + db * 32 + q4 * 8 + hi * 4) = __builtin_convertvector(o, bf16x4);
     }
+#ifndef MPIC_PHASE_TIMING
   if (a.lse && hi == 0)
     a.lse[fresh_row * a.n_q_heads + head] = m_run * a.scale + logf(l_tot);
+#endif
 }
 
 }  // namespace
 
 hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t stream) {
   if (a.n_tiles <= 0) return hipSuccess;
-  hipLaunchKernelGGL(attn_bf16_kernel, dim3(a.n_tiles), dim3(256), 0, stream, a);
+  // 128 KB of dynamic LDS needs an explicit opt-in, once per device
+  static bool opted_in[64] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev >= 0 && dev < 64 && !opted_in[dev]) {
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bf16_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+    if (e != hipSuccess) return e;
+    opted_in[dev] = true;
+  }
+  hipLaunchKernelGGL(attn_bf16_kernel, dim3(a.n_tiles), dim3(THREADS), LDS_BYTES, stream, a);
   return hipGetLastError();
 }
 

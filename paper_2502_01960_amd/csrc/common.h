@@ -27,6 +27,7 @@ struct PlanDevice {
   int32_t* src_inst = nullptr;
   int32_t* src_row = nullptr;
   int32_t* dst_slot = nullptr;
+  uint32_t* kv_off16 = nullptr;  // dst_slot * (bytes of a context row / 16): row offset in 16-byte units
   int32_t* q_pos = nullptr;
   int32_t* q_off = nullptr;
   int32_t* ctx_off = nullptr;
@@ -78,7 +79,7 @@ int fail_hip(mpic_ctx* ctx, hipError_t e, const char* what);
   } while (0)
 
 // Rows of the attention tile handled by one workgroup of the bf16 kernel.
-constexpr int kAttnTileRows = 128;
+constexpr int kAttnTileRows = 256;
 
 // ---- kernel launchers (each validates nothing: callers have done so) ----
 
@@ -113,6 +114,7 @@ struct AttnArgs {
   const int32_t* q_off;
   const int32_t* ctx_off;
   const int32_t* dst_slot;
+  const uint32_t* kv_off16;
   const void* q;
   const void* k_ctx;
   const void* v_ctx;

@@ -30,14 +30,16 @@ namespace {
 
 constexpr int kXcds = 8;  // L2 domains of the chip; workgroup i is dispatched to domain i % 8
 
-// Cut the runs of every request into attention tiles and order them for launch.
+// Cut the recompute set of every request into attention tiles and order them for launch.
 //
 // A tile is a range of "flattened rows" of one (request, kv head): all G query heads
 // of a fresh row are adjacent, fresh rows follow each other in position order.  Tiles
-// never straddle two runs, so every row of a tile sees almost the same keys and only
-// the last few key blocks need the causal mask.  Launch order: tiles that read the
-// same K/V (same request and kv head) are dealt to the same L2 domain, and inside a
-// domain the longest tiles come first so the tail of the launch is made of short work.
+// are cut every kAttnTileRows rows regardless of run boundaries: the kernel masks per
+// row and every wavefront stops at the last key its own rows can see, so a tile that
+// straddles two runs costs no more than its parts while full tiles keep the K/V
+// stream per flop low.  Launch order: tiles that read the same K/V (same request and
+// kv head) are dealt to the same L2 domain, and inside a domain the longest tiles come
+// first so the tail of the launch is made of short work.
 void build_tiles(mpic_plan& p, int group, int n_kv_heads) {
   struct Item {
     AttnTile t;
@@ -46,24 +48,26 @@ void build_tiles(mpic_plan& p, int group, int n_kv_heads) {
   const int B = p.n_requests;
   const int n_combo = B * n_kv_heads;
   std::vector<std::vector<Item>> per_combo(n_combo);
-  const size_t n_runs = p.runs.size() / 4;
-  for (size_t i = 0; i < n_runs; ++i) {
-    const int b = p.runs[4 * i + 0];
-    const int64_t r0 = p.runs[4 * i + 1] - p.q_off[b];
-    const int64_t len = p.runs[4 * i + 2];
-    const int64_t lo = r0 * group, hi = (r0 + len) * group;
-    for (int64_t row = lo; row < hi; row += kAttnTileRows) {
-      const int64_t n = std::min<int64_t>(kAttnTileRows, hi - row);
+  for (int b = 0; b < B; ++b) {
+    const int64_t rows = static_cast<int64_t>(p.q_off[b + 1] - p.q_off[b]) * group;
+    for (int64_t row = 0; row < rows; row += kAttnTileRows) {
+      const int64_t n = std::min<int64_t>(kAttnTileRows, rows - row);
+      // keys visited by the tile = position of its last row + 1; cost = keys summed over
+      // its wavefronts of 32 rows (each stops at its own last row)
+      int64_t cost = 64;
+      for (int64_t w = row; w < row + n; w += 32) {
+        const int64_t last = p.q_off[b] + (std::min(w + 32, row + n) - 1) / group;
+        cost += p.q_pos[last] + 1;
+      }
       const int64_t last_fresh = p.q_off[b] + (row + n - 1) / group;
-      const int32_t n_keys = p.q_pos[last_fresh] + 1;
       for (int g = 0; g < n_kv_heads; ++g) {
         Item it{};
         it.t.req = b;
         it.t.kv_head = g;
         it.t.row0 = static_cast<int32_t>(row);
         it.t.n_rows = static_cast<int32_t>(n);
-        it.t.n_keys = n_keys;
-        it.cost = static_cast<int64_t>(n_keys) + 64;  // per-tile fixed cost keeps ties stable
+        it.t.n_keys = p.q_pos[last_fresh] + 1;
+        it.cost = cost;
         per_combo[b * n_kv_heads + g].push_back(it);
       }
     }
