@@ -146,14 +146,21 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a) {
   const uint32_t ld_col = lane & 15;
   const uint32_t ld_k16 = ld_col ^ ld_sub ^ ((wave & 1) << 3);  // ^ (4p): K swizzle = row & 15
   const uint32_t ld_v16 = ld_col ^ (ld_sub << 2);               //          V swizzle = (row & 3) << 2
+  // row offsets of this wave's eight rows of a block: one scalar load, issued one block
+  // ahead of its use so that its latency is never waited for
+  const int n_iter = (n_keys + BN - 1) / BN;
+  auto fetch_rows = [&](int blk) {
+    blk = blk < n_iter ? blk : n_iter - 1;
+    return *reinterpret_cast<const __attribute__((address_space(4))) u32x8_a4*>(off_of + blk * BN + wave * 8);
+  };
+  u32x8_a4 ro = fetch_rows(0);
   auto issue_loads = [&](int blk) {
-    // row offsets of this wave's eight rows: one scalar load
-    const int first = blk * BN + wave * 8;
-    const u32x8_a4 ro = *reinterpret_cast<const __attribute__((address_space(4))) u32x8_a4*>(off_of + first);
+    const u32x8_a4 cur = ro;
+    ro = fetch_rows(blk + 1);
     const uint32_t dst = lds_base + (blk % STAGES) * STAGE_BYTES + wave * 8 * ROW_BYTES;
 #pragma unroll
     for (int p = 0; p < 2; ++p) {
-      const uint32_t r16 = ld_sub == 0 ? ro[4 * p] : ld_sub == 1 ? ro[4 * p + 1] : ld_sub == 2 ? ro[4 * p + 2] : ro[4 * p + 3];
+      const uint32_t r16 = ld_sub == 0 ? cur[4 * p] : ld_sub == 1 ? cur[4 * p + 1] : ld_sub == 2 ? cur[4 * p + 2] : cur[4 * p + 3];
       load_to_lds_16B(kbase + (static_cast<uint64_t>(r16 + (ld_k16 ^ (4 * p))) << 4), dst + p * 4 * ROW_BYTES);
       load_to_lds_16B(vbase + (static_cast<uint64_t>(r16 + ld_v16) << 4), dst + TILE_BYTES + p * 4 * ROW_BYTES);
     }
@@ -171,7 +178,6 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a) {
   const int v_col_x = ((((lane >> 4) & 1) << 1) | ((i16 & 3) >> 1)) ^ ((v_row & 3) << 2);  // ^ (db << 2)
   const int v_off = TILE_BYTES + v_row * ROW_BYTES + (i16 & 1) * 8;
 
-  const int n_iter = (n_keys + BN - 1) / BN;
   PHASE_DECL
   // every ordinary load (query fragments, positions) is complete before the first direct
   // load is issued: from here on the outstanding-load counter only counts ring traffic
@@ -179,72 +185,78 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a) {
   __builtin_amdgcn_sched_barrier(0);
   issue_loads(0);
   if (n_iter > 1) issue_loads(1);
-  if (n_iter > 2) issue_loads(2);
 
-  for (int it = 0; it < n_iter; ++it) {
-    const int j0 = it * BN;
-    PHASE_MARK(0)
-    // this wave's share of block `it` has landed when at most the loads of the younger
-    // blocks are still outstanding
-    if (it + 2 < n_iter) {
-      WAIT_VMCNT(2 * LOADS_PER_STAGE);
-    } else if (it + 1 < n_iter) {
-      WAIT_VMCNT(LOADS_PER_STAGE);
-    } else {
-      WAIT_VMCNT(0);
+  // Ping-pong schedule.  The two wavefronts that share a SIMD (w and w+4) belong to
+  // different groups and run half a block apart: while one group keeps the matrix
+  // core busy with O^T += V^T P^T of block t-1 and S^T = K Q^T of block t, the other
+  // does the softmax of its block on the vector ALU; a workgroup barrier at every
+  // half step keeps them in anti-phase.  Group gp runs its matrix part of block t in
+  // half step 2t + gp and its softmax of block t in half step 2t + gp + 1.
+  //   stage t (K and V of block t) is first read in half step 2t and last in 2t + 3,
+  //   so its ring slot is refilled with block t+4... the loads of block t+2 are issued
+  //   at half step 2t, into the slot block t-2 left free after half step 2t - 1.
+  const int gp = wave >> 2;
+  f32x16 acc_s[2] = {f32x16{0}, f32x16{0}};
+  bf16x8 pf[4] = {};
+
+  auto k_frag = [&](const char* stage, int kb, int ks) {
+    return *reinterpret_cast<const bf16x8*>(stage + k_row_off + kb * 32 * ROW_BYTES + ((k_col_x ^ (ks << 1)) << 4));
+  };
+  auto v_frag = [&](const char* stage, int kh, int db) {
+    const char* vp = stage + v_off + kh * 16 * ROW_BYTES + ((v_col_x ^ (db << 2)) << 4);
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, vp));
+    const s16x4 up = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, vp + 8 * ROW_BYTES));
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, up, 0, 1, 2, 3, 4, 5, 6, 7));
+  };
+
+  // O^T += V^T . P^T of block t: 16 keys per step, each fragment register refilled for the
+  // next step right behind the MFMA that read it; the scheduling barriers pin that order
+  auto pv_block = [&](int t) {
+    const char* stage = lds + (t % STAGES) * STAGE_BYTES;
+    bf16x8 vf[4];
+#pragma unroll
+    for (int db = 0; db < 4; ++db) vf[db] = v_frag(stage, 0, db);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int kh = 0; kh < 4; ++kh) {  // kb = kh/2, half = kh%2
+#pragma unroll
+      for (int db = 0; db < 4; ++db) {
+        acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[db], pf[kh], acc_o[db], 0, 0, 0);
+        if (kh + 1 < 4) vf[db] = v_frag(stage, kh + 1, db);  // refill behind the MFMA that consumed it
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
-    PHASE_MARK(1)
-    __syncthreads();  // everyone's share has; the stage consumed in the previous round is free
-    PHASE_MARK(2)
-    if (it + STAGES - 1 < n_iter) issue_loads(it + STAGES - 1);
-    PHASE_MARK(3)
-    if (j0 > wave_hi_pos) continue;  // nothing visible to this wave any more (barriers stay aligned)
+  };
 
-    const char* stage = lds + (it % STAGES) * STAGE_BYTES;
-    const char* ks_base = stage + k_row_off;
-    const char* vs_base = stage + v_off;
-    auto k_frag = [&](int kb, int ks) {
-      return *reinterpret_cast<const bf16x8*>(ks_base + kb * 32 * ROW_BYTES + ((k_col_x ^ (ks << 1)) << 4));
-    };
-    auto v_frag = [&](int kh, int db) {
-      const char* vp = vs_base + kh * 16 * ROW_BYTES + ((v_col_x ^ (db << 2)) << 4);
-      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, vp));
-      const s16x4 up = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, vp + 8 * ROW_BYTES));
-      return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, up, 0, 1, 2, 3, 4, 5, 6, 7));
-    };
-
-    // S^T = K . Q^T for 64 keys x 32 queries.  The LDS reads run kPre steps ahead of the
-    // MFMAs that consume them and the two key sub-blocks alternate, so neither the LDS
-    // latency nor the accumulator dependency is exposed; the scheduling barriers pin
-    // that order.
-    constexpr int kPre = 3;
-    f32x16 acc_s[2] = {f32x16{0}, f32x16{0}};
+  // S^T = K . Q^T of block t for 64 keys x 32 queries; LDS reads run kPre steps ahead of
+  // the MFMAs and the two key sub-blocks alternate
+  auto qk_block = [&](int t) {
+    const char* stage = lds + (t % STAGES) * STAGE_BYTES;
+    constexpr int kPre = 2;
+    acc_s[0] = f32x16{0};
+    acc_s[1] = f32x16{0};
     bf16x8 kf[2][8];
 #pragma unroll
     for (int ks = 0; ks < kPre; ++ks) {
-      kf[0][ks] = k_frag(0, ks);
-      kf[1][ks] = k_frag(1, ks);
+      kf[0][ks] = k_frag(stage, 0, ks);
+      kf[1][ks] = k_frag(stage, 1, ks);
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
       if (ks + kPre < 8) {
-        kf[0][ks + kPre] = k_frag(0, ks + kPre);
-        kf[1][ks + kPre] = k_frag(1, ks + kPre);
+        kf[0][ks + kPre] = k_frag(stage, 0, ks + kPre);
+        kf[1][ks + kPre] = k_frag(stage, 1, ks + kPre);
       }
       acc_s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0][ks], qf[ks], acc_s[0], 0, 0, 0);
       acc_s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[1][ks], qf[ks], acc_s[1], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
-    PHASE_MARK(4)
-    // the first value fragments are fetched now and land while the softmax runs
-    bf16x8 vf[2][4];
-#pragma unroll
-    for (int db = 0; db < 4; ++db) vf[0][db] = v_frag(0, db);
-#pragma unroll
-    for (int db = 0; db < 4; ++db) vf[1][db] = v_frag(1, db);
-    __builtin_amdgcn_sched_barrier(0);
+  };
 
+  // softmax of block t: S^T (acc_s) -> P^T (pf), running sum and reference maximum
+  auto softmax_block = [&](int t) {
+    const int j0 = t * BN;
     // causal mask by position, on the diagonal blocks only
     if (j0 + BN - 1 > wave_lo_pos) {
 #pragma unroll
@@ -264,7 +276,8 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a) {
     // Lazy rescale: the reference point m_run only moves when some query's block maximum
     // exceeds it by more than kSlack (in log2 units), so probabilities are at most
     // 2^kSlack before normalisation -- exact in the end because numerator and
-    // denominator share the reference point.
+    // denominator share the reference point.  (All earlier blocks are already in acc_o:
+    // the matrix part of block t-1 ran in the previous half step.)
     if (__builtin_amdgcn_ballot_w64((m_blk - m_run) * scale_log2 > kSlack) != 0) {
       const float m_new = fmaxf(m_run, m_blk);
       const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2);  // first block: 0
@@ -275,7 +288,6 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a) {
     }
     const float m_scaled = m_run * scale_log2;
     float l_blk = 0.f;
-    bf16x8 pf[4];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -289,22 +301,55 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a) {
         pf[kb * 2 + half] = __builtin_convertvector(p, bf16x8);
       }
     l_run += l_blk;
+  };
 
-    PHASE_MARK(5)
-    // O^T += V^T . P^T, 16 keys per step, fragments of step kh+2 fetched behind step kh
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int kh = 0; kh < 4; ++kh) {  // kb = kh/2, half = kh%2
-#pragma unroll
-      for (int db = 0; db < 4; ++db)
-        acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[kh & 1][db], pf[kh], acc_o[db], 0, 0, 0);
-      if (kh + 2 < 4) {
-#pragma unroll
-        for (int db = 0; db < 4; ++db) vf[kh & 1][db] = v_frag(kh + 2, db);
+  // even half step 2t: block t must be complete in LDS, then the loads of block t+2 go out
+  auto even_sync = [&](int t) {
+    PHASE_MARK(0)
+    if (t < n_iter) {
+      // this wave's share of block t has landed when at most the loads of block t+1 are
+      // still outstanding
+      if (t + 1 < n_iter) {
+        WAIT_VMCNT(LOADS_PER_STAGE);
+      } else {
+        WAIT_VMCNT(0);
       }
-      __builtin_amdgcn_sched_barrier(0);
     }
-    PHASE_MARK(6)
+    PHASE_MARK(1)
+    __syncthreads();
+    PHASE_MARK(2)
+    if (t + 2 < n_iter) issue_loads(t + 2);
+    PHASE_MARK(3)
+  };
+  // matrix half step of block t: finish block t-1, start block t (blocks past the last key
+  // this wave can see are skipped; the barriers stay aligned)
+  auto matrix_part = [&](int t) {
+    const bool do_pv = t >= 1 && (t - 1) * BN <= wave_hi_pos;
+    if (t < n_iter && t * BN <= wave_hi_pos) {
+      if (do_pv) pv_block(t - 1);
+      PHASE_MARK(4)
+      qk_block(t);
+      PHASE_MARK(5)
+    } else if (do_pv) {
+      pv_block(t - 1);
+    }
+  };
+  if (gp == 0) {
+    for (int t = 0; t <= n_iter; ++t) {
+      even_sync(t);
+      matrix_part(t);
+      __syncthreads();  // odd half step 2t+1
+      if (t < n_iter && t * BN <= wave_hi_pos) softmax_block(t);
+      PHASE_MARK(6)
+    }
+  } else {
+    for (int t = 0; t <= n_iter; ++t) {
+      even_sync(t);
+      if (t >= 1 && (t - 1) * BN <= wave_hi_pos) softmax_block(t - 1);
+      PHASE_MARK(6)
+      __syncthreads();  // odd half step 2t+1
+      matrix_part(t);
+    }
   }
 
 #ifdef MPIC_PHASE_TIMING
