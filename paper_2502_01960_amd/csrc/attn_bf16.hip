@@ -325,6 +325,7 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a) {
   // this wave can see are skipped; the barriers stay aligned)
   auto matrix_part = [&](int t) {
     const bool do_pv = t >= 1 && (t - 1) * BN <= wave_hi_pos;
+    __builtin_amdgcn_s_setprio(1);  // the wave that feeds the matrix core is issued first
     if (t < n_iter && t * BN <= wave_hi_pos) {
       if (do_pv) pv_block(t - 1);
       PHASE_MARK(4)
@@ -333,6 +334,7 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a) {
     } else if (do_pv) {
       pv_block(t - 1);
     }
+    __builtin_amdgcn_s_setprio(0);
   };
   if (gp == 0) {
     for (int t = 0; t <= n_iter; ++t) {
