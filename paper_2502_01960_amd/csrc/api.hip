@@ -16,7 +16,8 @@ int bind_device(mpic_ctx* ctx) {
   if (ctx->device < 0) {
     ctx->device = dev;
     MPIC_HIP(ctx, hipStreamCreateWithFlags(&ctx->side_stream, hipStreamNonBlocking));
-    MPIC_HIP(ctx, hipEventCreateWithFlags(&ctx->ev_main, hipEventDisableTiming));
+    MPIC_HIP(ctx, hipEventCreateWithFlags(&ctx->ev_done[0], hipEventDisableTiming));
+    MPIC_HIP(ctx, hipEventCreateWithFlags(&ctx->ev_done[1], hipEventDisableTiming));
   } else if (ctx->device != dev) {
     return fail(ctx, MPIC_ERR_INVALID, "context is bound to another GPU than the current one");
   }
@@ -108,9 +109,11 @@ extern "C" void mpic_destroy(mpic_ctx* ctx) {
       (void)hipStreamSynchronize(ctx->side_stream);
       (void)hipStreamDestroy(ctx->side_stream);
     }
-    if (ctx->ev_main) (void)hipEventDestroy(ctx->ev_main);
+    for (hipEvent_t ev : ctx->ev_done)
+      if (ev) (void)hipEventDestroy(ev);
     for (hipEvent_t ev : ctx->ev_copy) (void)hipEventDestroy(ev);
-    if (ctx->staging) (void)hipFree(ctx->staging);
+    for (void* buf : ctx->staging)
+      if (buf) (void)hipFree(buf);
     if (cur >= 0) (void)hipSetDevice(cur);
   }
   delete ctx;
@@ -163,48 +166,65 @@ extern "C" int mpic_assemble_kv(mpic_ctx* ctx, mpic_plan* plan, const mpic_chunk
   const size_t row_bytes = static_cast<size_t>(c.n_kv_heads) * c.head_dim * elem;
 
   // ---- host-resident sources: where each lands in device staging ----
+  // Only rows that some instance actually reuses cross the bus: rows below the smallest
+  // effective k of the source's instances are replaced by fresh rows anyway.
   constexpr int kGroup = 4;  // sources per transfer group (one event each)
   std::vector<int32_t> host_srcs;              // distinct host sources in order of first use
   std::vector<size_t> stage_off(n_srcs > 0 ? n_srcs : 0, SIZE_MAX);
+  std::vector<int32_t> first_row(n_srcs > 0 ? n_srcs : 0, INT32_MAX);
   size_t need = 0;
+  char* staging = nullptr;
+  int buf = 0;
   if (any_host) {
     for (size_t i = 0; i < n_inst; ++i) {
       const int32_t s = plan->inst_src[i];
+      if (srcs[s].on_host && plan->inst_k[i] < plan->inst_len[i])
+        first_row[s] = std::min(first_row[s], plan->inst_k[i]);
+    }
+    for (size_t i = 0; i < n_inst; ++i) {
+      const int32_t s = plan->inst_src[i];
       if (srcs[s].on_host && plan->inst_k[i] < plan->inst_len[i] && stage_off[s] == SIZE_MAX) {
-        stage_off[s] = need;
+        stage_off[s] = need;  // room for the whole chunk keeps row addressing trivial
         need += 2 * static_cast<size_t>(srcs[s].len) * row_bytes;
         host_srcs.push_back(s);
       }
     }
-    if (need > ctx->staging_bytes) {
-      // growing the staging area is rare (first call / larger batch): drain and reallocate
+    buf = ctx->next_staging;
+    ctx->next_staging ^= 1;
+    if (need > ctx->staging_bytes[buf]) {
+      // growing a staging area is rare (first calls / larger batch): drain and reallocate
       MPIC_HIP(ctx, hipStreamSynchronize(ctx->side_stream));
       MPIC_HIP(ctx, hipStreamSynchronize(stream));
-      if (ctx->staging) MPIC_HIP(ctx, hipFree(ctx->staging));
-      ctx->staging = nullptr;
-      ctx->staging_bytes = 0;
-      hipError_t e = hipMalloc(&ctx->staging, need);
+      if (ctx->ev_done_valid[buf]) MPIC_HIP(ctx, hipEventSynchronize(ctx->ev_done[buf]));
+      if (ctx->staging[buf]) MPIC_HIP(ctx, hipFree(ctx->staging[buf]));
+      ctx->staging[buf] = nullptr;
+      ctx->staging_bytes[buf] = 0;
+      hipError_t e = hipMalloc(&ctx->staging[buf], need);
       if (e != hipSuccess) {
         (void)hipGetLastError();
         return fail(ctx, MPIC_ERR_OOM, "assemble_kv: device staging allocation failed");
       }
-      ctx->staging_bytes = need;
+      ctx->staging_bytes[buf] = need;
     }
+    staging = static_cast<char*>(ctx->staging[buf]);
     const size_t n_groups = (host_srcs.size() + kGroup - 1) / kGroup;
     while (ctx->ev_copy.size() < n_groups) {
       hipEvent_t ev;
       MPIC_HIP(ctx, hipEventCreateWithFlags(&ev, hipEventDisableTiming));
       ctx->ev_copy.push_back(ev);
     }
-    // staging may still be read by linking work enqueued earlier on `stream`
-    MPIC_HIP(ctx, hipEventRecord(ctx->ev_main, stream));
-    MPIC_HIP(ctx, hipStreamWaitEvent(ctx->side_stream, ctx->ev_main, 0));
+    // this staging buffer may still be read by the linking kernels of the call before last
+    if (ctx->ev_done_valid[buf]) MPIC_HIP(ctx, hipStreamWaitEvent(ctx->side_stream, ctx->ev_done[buf], 0));
     for (size_t i = 0; i < host_srcs.size(); ++i) {
-      const mpic_chunk_src& s = srcs[host_srcs[i]];
+      const int32_t si = host_srcs[i];
+      const mpic_chunk_src& s = srcs[si];
+      const size_t skip = static_cast<size_t>(first_row[si]) * row_bytes;
       const size_t bytes = static_cast<size_t>(s.len) * row_bytes;
-      char* dst = static_cast<char*>(ctx->staging) + stage_off[host_srcs[i]];
-      MPIC_HIP(ctx, hipMemcpyAsync(dst, s.k, bytes, hipMemcpyHostToDevice, ctx->side_stream));
-      MPIC_HIP(ctx, hipMemcpyAsync(dst + bytes, s.v, bytes, hipMemcpyHostToDevice, ctx->side_stream));
+      char* dst = staging + stage_off[si];
+      MPIC_HIP(ctx, hipMemcpyAsync(dst + skip, static_cast<const char*>(s.k) + skip, bytes - skip,
+                                   hipMemcpyHostToDevice, ctx->side_stream));
+      MPIC_HIP(ctx, hipMemcpyAsync(dst + bytes + skip, static_cast<const char*>(s.v) + skip, bytes - skip,
+                                   hipMemcpyHostToDevice, ctx->side_stream));
       if ((i + 1) % kGroup == 0 || i + 1 == host_srcs.size())
         MPIC_HIP(ctx, hipEventRecord(ctx->ev_copy[i / kGroup], ctx->side_stream));
     }
@@ -269,8 +289,8 @@ extern "C" int mpic_assemble_kv(mpic_ctx* ctx, mpic_plan* plan, const mpic_chunk
       }
       mpic::AssembleSrcTable tab{};
       const size_t bytes = static_cast<size_t>(srcs[s].len) * row_bytes;
-      tab.k[0] = static_cast<char*>(ctx->staging) + stage_off[s];
-      tab.v[0] = static_cast<char*>(ctx->staging) + stage_off[s] + bytes;
+      tab.k[0] = staging + stage_off[s];
+      tab.v[0] = staging + stage_off[s] + bytes;
       a.pos_begin = inst_first_pos(i) + plan->inst_k[i];
       a.pos_end = inst_first_pos(i) + plan->inst_len[i];
       a.inst_base = static_cast<int32_t>(i);
@@ -278,6 +298,8 @@ extern "C" int mpic_assemble_kv(mpic_ctx* ctx, mpic_plan* plan, const mpic_chunk
       a.skip_fresh = 1;
       MPIC_HIP(ctx, mpic::launch_assemble(c.dtype, a, tab, stream));
     }
+    MPIC_HIP(ctx, hipEventRecord(ctx->ev_done[buf], stream));
+    ctx->ev_done_valid[buf] = true;
   }
   return MPIC_OK;
 }

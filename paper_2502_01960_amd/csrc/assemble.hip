@@ -93,10 +93,12 @@ __global__ __launch_bounds__(256) void assemble_kernel(AssembleArgs a, AssembleS
   }
   const int v0 = u * E, v1 = (u + pairs_per_row) * E;
 
-  const Raw k0 = *reinterpret_cast<const Raw*>(ksrc + e0);
-  const Raw k1 = *reinterpret_cast<const Raw*>(ksrc + e1);
-  const Raw w0 = *reinterpret_cast<const Raw*>(vsrc + v0);
-  const Raw w1 = *reinterpret_cast<const Raw*>(vsrc + v1);
+  // sources are read exactly once: streaming (non-temporal) loads keep them out of the way
+  // of the context rows, which the attention kernel reads next
+  const Raw k0 = __builtin_nontemporal_load(reinterpret_cast<const Raw*>(ksrc + e0));
+  const Raw k1 = __builtin_nontemporal_load(reinterpret_cast<const Raw*>(ksrc + e1));
+  const Raw w0 = __builtin_nontemporal_load(reinterpret_cast<const Raw*>(vsrc + v0));
+  const Raw w1 = __builtin_nontemporal_load(reinterpret_cast<const Raw*>(vsrc + v1));
 
   Raw o0 = k0, o1 = k1;
   if (inst >= 0) {

@@ -47,10 +47,15 @@ struct mpic_ctx {
   // GPU side, created on first use
   int device = -1;
   hipStream_t side_stream = nullptr;
-  hipEvent_t ev_main = nullptr;              // main stream -> side stream ordering
-  std::vector<hipEvent_t> ev_copy;           // one per staging half
-  void* staging = nullptr;                   // device staging for host-sourced chunks
-  size_t staging_bytes = 0;
+  // Device staging for host-resident chunks, double buffered: the copies of one call may
+  // run while the kernels of the previous call (linking and whatever the caller enqueued
+  // after it) still read the other buffer.
+  void* staging[2] = {nullptr, nullptr};
+  size_t staging_bytes[2] = {0, 0};
+  hipEvent_t ev_done[2] = {nullptr, nullptr};  // recorded after the last kernel that reads staging[i]
+  bool ev_done_valid[2] = {false, false};
+  int next_staging = 0;
+  std::vector<hipEvent_t> ev_copy;             // one per transfer group
 };
 
 struct mpic_plan {
