@@ -226,3 +226,36 @@ def test_interleaved_rotary_pairs():
                                {s: f64(kv[1]) for s, kv in p.chunks.items()},
                                f64(p.fresh_k), f64(p.fresh_v), sh.rope_theta, interleaved=True)
         _check_link(p, K_ref, V_ref, sh.dtype == "bf16")
+
+
+def test_random_layouts_and_head_groupings():
+    """Seeded random layouts (ragged chunks, empty text, k from 0 to beyond the chunk) with
+    several head groupings, including a group size of 7 and tiles that straddle runs and
+    end in a partial wavefront."""
+    import dataclasses
+    rng = np.random.default_rng(20250201)
+    groupings = [(4, 4), (8, 2), (28, 4), (7, 1), (64, 8)]
+    for case in range(10):
+        hq, hkv = groupings[case % len(groupings)]
+        n_src = int(rng.integers(1, 4))
+        src_len = [int(rng.integers(1, 200)) for _ in range(n_src)]
+        reqs = []
+        for _ in range(int(rng.integers(1, 4))):
+            segs = []
+            for _ in range(int(rng.integers(1, 6))):
+                if rng.random() < 0.45:
+                    segs.append(("text", int(rng.integers(0, 50))))
+                else:
+                    s = int(rng.integers(0, n_src))
+                    k = [None, 0, 1, 17, 500][int(rng.integers(0, 5))]
+                    segs.append(("chunk", s, src_len[s], k))
+            reqs.append(segs)
+        paged = 16 if case % 3 == 2 else 0
+        p = _custom(reqs, n_src, src_len, int(rng.integers(0, 40)), paged=paged)
+        p.sh = dataclasses.replace(p.sh, n_q_heads=hq, n_kv_heads=hkv)
+        # regenerate the tensors for the new head counts
+        p.chunks = {s: workloads.gen_chunk(p.sh, case, s, src_len[s]) for s in p.chunks}
+        q_off = p.oplan["q_off"]
+        fresh = [workloads.gen_fresh(p.sh, case, b, int(q_off[b + 1] - q_off[b])) for b in range(len(reqs))]
+        p.q = torch.cat([f[0] for f in fresh]); p.fresh_k = torch.cat([f[1] for f in fresh]); p.fresh_v = torch.cat([f[2] for f in fresh])
+        _run_full(p, host_sourced=bool(case % 2))
