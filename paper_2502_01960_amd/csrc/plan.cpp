@@ -29,6 +29,7 @@ int fail_hip(mpic_ctx* ctx, hipError_t e, const char* what) {
 namespace {
 
 constexpr int kXcds = 8;  // L2 domains of the chip; workgroup i is dispatched to domain i % 8
+constexpr int kComputeUnits = 256;
 
 // Cut the recompute set of every request into attention tiles and order them for launch.
 //
@@ -48,10 +49,22 @@ void build_tiles(mpic_plan& p, int group, int n_kv_heads) {
   const int B = p.n_requests;
   const int n_combo = B * n_kv_heads;
   std::vector<std::vector<Item>> per_combo(n_combo);
+  // Small problems: full tiles would leave most of the chip idle, so the tile height is
+  // halved (down to two wavefronts' worth of rows) until there is a tile per compute unit.
+  int64_t tile_rows = kAttnTileRows;
+  auto count_tiles = [&](int64_t h) {
+    int64_t n = 0;
+    for (int b = 0; b < B; ++b) {
+      const int64_t rows = static_cast<int64_t>(p.q_off[b + 1] - p.q_off[b]) * group;
+      n += (rows + h - 1) / h * n_kv_heads;
+    }
+    return n;
+  };
+  while (tile_rows > 64 && count_tiles(tile_rows) < kComputeUnits) tile_rows /= 2;
   for (int b = 0; b < B; ++b) {
     const int64_t rows = static_cast<int64_t>(p.q_off[b + 1] - p.q_off[b]) * group;
-    for (int64_t row = 0; row < rows; row += kAttnTileRows) {
-      const int64_t n = std::min<int64_t>(kAttnTileRows, rows - row);
+    for (int64_t row = 0; row < rows; row += tile_rows) {
+      const int64_t n = std::min<int64_t>(tile_rows, rows - row);
       // keys visited by the tile = position of its last row + 1; cost = keys summed over
       // its wavefronts of 32 rows (each stops at its own last row)
       int64_t cost = 64;
