@@ -120,7 +120,8 @@ void mpic_destroy(mpic_ctx* ctx);
  *   seg_off  [B+1]    host; request b owns segs[seg_off[b] .. seg_off[b+1])
  *   segs              host; see mpic_segment
  *   default_k         >= 0
- *   page_table        host, or NULL when config.page_size == 0.  Physical page ids
+ *   page_table        host; may be NULL when config.page_size == 0 or no request holds
+ *                     a token.  Physical page ids
  *                     (0 <= id < n_pool_pages), all requests concatenated.
  *   page_table_off [B+1]  host; request b owns page_table[off[b] .. off[b+1]), which
  *                     must cover ceil(N_b / page_size) pages.  No page id may be used

@@ -166,8 +166,8 @@ extern "C" int mpic_plan_create(mpic_ctx* ctx, int32_t n_requests, const int32_t
   if (n_requests < 1 || !seg_off || default_k < 0)
     return fail(ctx, MPIC_ERR_INVALID, "plan_create: need n_requests >= 1, seg_off, default_k >= 0");
   const int ps = ctx->cfg.page_size;
-  if (ps > 0 && (!page_table || !page_table_off || n_pool_pages <= 0))
-    return fail(ctx, MPIC_ERR_INVALID, "plan_create: paged layout needs page_table, offsets and pool size");
+  if (ps > 0 && (!page_table_off || n_pool_pages <= 0))
+    return fail(ctx, MPIC_ERR_INVALID, "plan_create: paged layout needs page table offsets and a pool size");
   if (seg_off[0] != 0) return fail(ctx, MPIC_ERR_INVALID, "plan_create: seg_off[0] must be 0");
   for (int b = 0; b < n_requests; ++b)
     if (seg_off[b + 1] < seg_off[b]) return fail(ctx, MPIC_ERR_INVALID, "plan_create: seg_off must not decrease");
@@ -257,9 +257,9 @@ extern "C" int mpic_plan_create(mpic_ctx* ctx, int32_t n_requests, const int32_t
       if (ps > 0) {
         const int64_t have = static_cast<int64_t>(page_table_off[b + 1]) - page_table_off[b];
         const int64_t need = (static_cast<int64_t>(pos) + ps - 1) / ps;
-        if (have < need) {
+        if (have < need || (need > 0 && !page_table)) {
           delete p;
-          return fail(ctx, MPIC_ERR_INVALID, "plan_create: page table shorter than the request");
+          return fail(ctx, MPIC_ERR_INVALID, "plan_create: page table missing or shorter than the request");
         }
         const int32_t* tab = page_table + page_table_off[b];
         for (int64_t pg = 0; pg < need; ++pg) {
