@@ -182,6 +182,23 @@ int mpic_assemble_kv(mpic_ctx* ctx, mpic_plan* plan, const mpic_chunk_src* srcs,
                      void* v_ctx, int64_t n_ctx_slots, void* stream);
 
 /*
+ * The same linking in two parts, for callers that overlap it with other work (Sec. 3.2:
+ * preparing the stored caches proceeds concurrently with computation).  MPIC_PART_CACHED
+ * links every row that comes from a stored chunk -- it needs only the plan and the chunk
+ * sources, so it can run ahead, e.g. on another stream while the previous layer computes;
+ * MPIC_PART_FRESH writes the rows of the recompute set once the model has produced them.
+ * The two parts write disjoint rows and may run in either order or concurrently; with
+ * both bits the call equals mpic_assemble_kv.  With MPIC_PART_CACHED alone fresh_k, fresh_v
+ * and n_fresh_rows are ignored; with MPIC_PART_FRESH alone srcs and n_srcs are ignored.
+ * Errors: as mpic_assemble_kv; MPIC_ERR_INVALID for an empty or unknown `parts`.
+ */
+enum { MPIC_PART_CACHED = 1, MPIC_PART_FRESH = 2 };
+int mpic_assemble_kv_parts(mpic_ctx* ctx, mpic_plan* plan, const mpic_chunk_src* srcs,
+                           int32_t n_srcs, const void* fresh_k, const void* fresh_v,
+                           int64_t n_fresh_rows, void* k_ctx, void* v_ctx, int64_t n_ctx_slots,
+                           uint32_t parts, void* stream);
+
+/*
  * Selective attention (Fig. 7 step 3; App. A): for every fresh row r at position p
  * of its request and every query head h (kv head h / (Hq/Hkv)):
  *   s_j = softmax_scale * <fresh_q[r][h], K_ctx[slot(j)][kv]>   for positions j = 0..p

@@ -69,6 +69,8 @@ def load_library():
     lib.mpic_plan_destroy.restype = None
     lib.mpic_assemble_kv.argtypes = [vp, vp, C.POINTER(_ChunkSrc), i32, vp, vp, i64, vp, vp, i64, vp]
     lib.mpic_assemble_kv.restype = C.c_int
+    lib.mpic_assemble_kv_parts.argtypes = [vp, vp, C.POINTER(_ChunkSrc), i32, vp, vp, i64, vp, vp, i64, C.c_uint32, vp]
+    lib.mpic_assemble_kv_parts.restype = C.c_int
     lib.mpic_selective_attn.argtypes = [vp, vp, vp, i64, vp, vp, i64, C.c_double, vp, vp, vp]
     lib.mpic_selective_attn.restype = C.c_int
     lib.mpic_strerror.argtypes = [C.c_int]
@@ -175,9 +177,18 @@ def _stream(stream):
     return C.c_void_p(getattr(stream, "cuda_stream", stream))
 
 
+MPIC_PART_CACHED, MPIC_PART_FRESH = 1, 2
+
+
 def mpic_assemble_kv(ctx, plan, srcs, fresh_k, fresh_v, k_ctx, v_ctx, stream=None):
     """srcs: list of (k_tensor, v_tensor) per source id; a pinned CPU tensor is staged
     by the library, a device tensor is read in place.  Tensors are torch tensors."""
+    mpic_assemble_kv_parts(ctx, plan, srcs, fresh_k, fresh_v, k_ctx, v_ctx,
+                           MPIC_PART_CACHED | MPIC_PART_FRESH, stream)
+
+
+def mpic_assemble_kv_parts(ctx, plan, srcs, fresh_k, fresh_v, k_ctx, v_ctx, parts, stream=None):
+    srcs = srcs or []
     arr = (_ChunkSrc * max(1, len(srcs)))()
     for i, (k, v) in enumerate(srcs):
         if k is None:
@@ -188,8 +199,9 @@ def mpic_assemble_kv(ctx, plan, srcs, fresh_k, fresh_v, k_ctx, v_ctx, stream=Non
             raise ValueError("host chunk sources must be pinned")
         arr[i] = _ChunkSrc(k.data_ptr(), v.data_ptr(), k.shape[0], on_host)
     n_fresh = 0 if fresh_k is None else fresh_k.shape[0]
-    rc = load_library().mpic_assemble_kv(ctx, plan, arr, len(srcs), _ptr(fresh_k), _ptr(fresh_v), n_fresh,
-                                         _ptr(k_ctx), _ptr(v_ctx), k_ctx.shape[0], _stream(stream))
+    rc = load_library().mpic_assemble_kv_parts(ctx, plan, arr, len(srcs), _ptr(fresh_k), _ptr(fresh_v), n_fresh,
+                                               _ptr(k_ctx), _ptr(v_ctx), k_ctx.shape[0], int(parts),
+                                               _stream(stream))
     _check(rc, ctx)
 
 

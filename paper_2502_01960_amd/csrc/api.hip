@@ -38,7 +38,7 @@ int upload_plan(mpic_ctx* ctx, mpic_plan* p) {
     return MPIC_OK;
   }
   const size_t n = p->n_ctx, nq = p->n_q, B = p->n_requests;
-  size_t total = 3 * padded<int32_t>(n) + padded<int32_t>(n + kTablePad) + padded<int32_t>(nq) + 2 * padded<int32_t>(B + 1) +
+  size_t total = 3 * padded<int32_t>(n) + padded<int32_t>(n + kTablePad) + padded<int32_t>(nq) + padded<int32_t>(nq) + 2 * padded<int32_t>(B + 1) +
                  2 * padded<float>(p->rope_cos.size()) + padded<AttnTile>(p->tiles.size()) + 256;
   char* base = nullptr;
   hipError_t e = hipMalloc(reinterpret_cast<void**>(&base), total);
@@ -72,6 +72,11 @@ int upload_plan(mpic_ctx* ctx, mpic_plan* p) {
     std::vector<uint32_t> off(n + kTablePad, 0u);
     for (size_t i = 0; i < n; ++i) off[i] = static_cast<uint32_t>(static_cast<uint64_t>(p->dst_slot[i]) * units);
     if (e == hipSuccess) d.kv_off16 = static_cast<uint32_t*>(put(off.data(), off.size() * 4, padded<int32_t>(off.size())));
+  }
+  {
+    std::vector<int32_t> fp(nq);
+    for (size_t r = 0; r < nq; ++r) fp[r] = p->ctx_off[p->q_req[r]] + p->q_pos[r];
+    if (e == hipSuccess) d.fresh_pos = static_cast<int32_t*>(put(fp.data(), nq * 4, padded<int32_t>(nq)));
   }
   if (e == hipSuccess) d.q_pos = static_cast<int32_t*>(put(p->q_pos.data(), nq * 4, padded<int32_t>(nq)));
   if (e == hipSuccess) d.q_off = static_cast<int32_t*>(put(p->q_off.data(), (B + 1) * 4, padded<int32_t>(B + 1)));
@@ -135,16 +140,27 @@ extern "C" int mpic_assemble_kv(mpic_ctx* ctx, mpic_plan* plan, const mpic_chunk
                                 int32_t n_srcs, const void* fresh_k, const void* fresh_v,
                                 int64_t n_fresh_rows, void* k_ctx, void* v_ctx, int64_t n_ctx_slots,
                                 void* stream_) {
+  return mpic_assemble_kv_parts(ctx, plan, srcs, n_srcs, fresh_k, fresh_v, n_fresh_rows, k_ctx, v_ctx,
+                                n_ctx_slots, MPIC_PART_CACHED | MPIC_PART_FRESH, stream_);
+}
+
+extern "C" int mpic_assemble_kv_parts(mpic_ctx* ctx, mpic_plan* plan, const mpic_chunk_src* srcs,
+                                      int32_t n_srcs, const void* fresh_k, const void* fresh_v,
+                                      int64_t n_fresh_rows, void* k_ctx, void* v_ctx,
+                                      int64_t n_ctx_slots, uint32_t parts, void* stream_) {
   if (!ctx) return MPIC_ERR_INVALID;
+  if (parts == 0 || (parts & ~static_cast<uint32_t>(MPIC_PART_CACHED | MPIC_PART_FRESH)))
+    return fail(ctx, MPIC_ERR_INVALID, "assemble_kv: parts must be MPIC_PART_CACHED, MPIC_PART_FRESH or both");
+  const bool do_cached = parts & MPIC_PART_CACHED, do_fresh = parts & MPIC_PART_FRESH;
   if (!plan || plan->ctx != ctx) return fail(ctx, MPIC_ERR_INVALID, "assemble_kv: plan does not belong to this context");
-  if (n_fresh_rows != plan->n_q) return fail(ctx, MPIC_ERR_INVALID, "assemble_kv: n_fresh_rows differs from the plan's recompute set");
-  if (plan->n_q > 0 && (!fresh_k || !fresh_v)) return fail(ctx, MPIC_ERR_INVALID, "assemble_kv: fresh_k / fresh_v missing");
+  if (do_fresh && n_fresh_rows != plan->n_q) return fail(ctx, MPIC_ERR_INVALID, "assemble_kv: n_fresh_rows differs from the plan's recompute set");
+  if (do_fresh && plan->n_q > 0 && (!fresh_k || !fresh_v)) return fail(ctx, MPIC_ERR_INVALID, "assemble_kv: fresh_k / fresh_v missing");
   if (plan->n_ctx == 0) return MPIC_OK;
   if (!k_ctx || !v_ctx) return fail(ctx, MPIC_ERR_INVALID, "assemble_kv: k_ctx / v_ctx missing");
   if (n_ctx_slots <= plan->max_slot) return fail(ctx, MPIC_ERR_INVALID, "assemble_kv: context buffers smaller than the plan's largest slot");
-  if (!mpic::aligned16(fresh_k) || !mpic::aligned16(fresh_v) || !mpic::aligned16(k_ctx) || !mpic::aligned16(v_ctx))
+  if ((do_fresh && (!mpic::aligned16(fresh_k) || !mpic::aligned16(fresh_v))) || !mpic::aligned16(k_ctx) || !mpic::aligned16(v_ctx))
     return fail(ctx, MPIC_ERR_INVALID, "assemble_kv: buffers must be 16-byte aligned");
-  const size_t n_inst = plan->inst_src.size();
+  const size_t n_inst = do_cached ? plan->inst_src.size() : 0;  // chunk sources are only looked at for the cached part
   if (n_inst > 0 && (!srcs || n_srcs <= plan->max_src)) return fail(ctx, MPIC_ERR_INVALID, "assemble_kv: srcs does not cover every chunk index of the plan");
   bool any_host = false;
   for (size_t i = 0; i < n_inst; ++i) {
@@ -244,6 +260,18 @@ extern "C" int mpic_assemble_kv(mpic_ctx* ctx, mpic_plan* plan, const mpic_chunk
   a.head_dim = c.head_dim;
   a.interleaved = c.rope_interleaved;
 
+  if (!do_cached) {
+    // fresh rows only: one launch over the list of their positions
+    mpic::AssembleSrcTable none{};
+    a.pos_list = plan->dev.fresh_pos;
+    a.pos_begin = 0;
+    a.pos_end = plan->n_q;
+    a.inst_base = 0;
+    a.n_inst = 0;
+    a.skip_fresh = 0;
+    MPIC_HIP(ctx, mpic::launch_assemble(c.dtype, a, none, stream));
+    return MPIC_OK;
+  }
   auto inst_first_pos = [&](size_t i) -> int64_t {
     return static_cast<int64_t>(plan->ctx_off[plan->inst_req[i]]) + plan->inst_delta[i];
   };
@@ -263,7 +291,7 @@ extern "C" int mpic_assemble_kv(mpic_ctx* ctx, mpic_plan* plan, const mpic_chunk
     a.pos_end = i1 < n_inst ? inst_first_pos(i1) : plan->n_ctx;
     a.inst_base = static_cast<int32_t>(i0);
     a.n_inst = static_cast<int32_t>(i1 - i0);
-    a.skip_fresh = 0;
+    a.skip_fresh = do_fresh ? 0 : 1;
     MPIC_HIP(ctx, mpic::launch_assemble(c.dtype, a, tab, stream));
   }
   // Pass 2: one launch per chunk instance fed from staging, as soon as its transfer group

@@ -54,8 +54,9 @@ __global__ __launch_bounds__(256) void assemble_kernel(AssembleArgs a, AssembleS
   const int64_t row_elems = static_cast<int64_t>(a.n_kv_heads) * D;
 
   const int64_t w = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
-  const int64_t pos = a.pos_begin + w / pairs_per_row;
-  if (pos >= a.pos_end) return;
+  const int64_t item = a.pos_begin + w / pairs_per_row;
+  if (item >= a.pos_end) return;
+  const int64_t pos = a.pos_list ? a.pos_list[item] : item;
   const int u = static_cast<int>(w % pairs_per_row);
 
   const int inst = a.src_inst[pos];

@@ -27,6 +27,7 @@ struct PlanDevice {
   int32_t* src_inst = nullptr;
   int32_t* src_row = nullptr;
   int32_t* dst_slot = nullptr;
+  int32_t* fresh_pos = nullptr;  // batch-flattened context position of every fresh row
   uint32_t* kv_off16 = nullptr;  // dst_slot * (bytes of a context row / 16): row offset in 16-byte units
   int32_t* q_pos = nullptr;
   int32_t* q_off = nullptr;
@@ -102,7 +103,8 @@ struct AssembleArgs {
   int32_t inst_base;           // first chunk instance present in src_k / src_v
   int32_t n_inst;              // entries in src_k / src_v
   int32_t n_kv_heads, head_dim, interleaved;
-  int32_t skip_fresh;          // 1: leave rows of the recompute set alone (already written)
+  int32_t skip_fresh;          // 1: leave rows of the recompute set alone
+  const int32_t* pos_list;     // non-null: the launch visits pos_list[pos_begin .. pos_end) instead of a range
 };
 constexpr int kMaxInstPerLaunch = 128;
 struct AssembleSrcTable {

@@ -259,3 +259,29 @@ def test_random_layouts_and_head_groupings():
         fresh = [workloads.gen_fresh(p.sh, case, b, int(q_off[b + 1] - q_off[b])) for b in range(len(reqs))]
         p.q = torch.cat([f[0] for f in fresh]); p.fresh_k = torch.cat([f[1] for f in fresh]); p.fresh_v = torch.cat([f[2] for f in fresh])
         _run_full(p, host_sourced=bool(case % 2))
+
+
+def test_linking_in_two_parts_equals_one_call():
+    """Cached rows first (they need no model output), fresh rows later, on two streams:
+    bit-identical to the single call; either part alone leaves the other rows untouched."""
+    for host in (False, True):
+        p = Problem(3, n_chunks=3, chunk_len=301, text_len=37, batch=2)
+        p.gpu_setup(host)
+        p.gpu_assemble()
+        torch.cuda.synchronize()
+        k_ref, v_ref = p.k_ctx.clone(), p.v_ctx.clone()
+        fresh = torch.from_numpy(p.oplan["dst_slot"][p.oplan["src_inst"] < 0].astype(np.int64)).to(p.k_ctx.device)
+        p.k_ctx.fill_(float("nan")); p.v_ctx.fill_(float("nan"))
+        side = torch.cuda.Stream()
+        torch.cuda.synchronize()
+        mpic.mpic_assemble_kv_parts(p.ctx.handle, p.plan.handle, p.srcs, None, None, p.k_ctx, p.v_ctx,
+                                    mpic.MPIC_PART_CACHED, side)
+        side.synchronize()
+        assert torch.isnan(p.k_ctx[fresh].float()).all(), "the cached part must not touch fresh rows"
+        mpic.mpic_assemble_kv_parts(p.ctx.handle, p.plan.handle, None, p.d_fk, p.d_fv, p.k_ctx, p.v_ctx,
+                                    mpic.MPIC_PART_FRESH)
+        torch.cuda.synchronize()
+        assert torch.equal(p.k_ctx.view(torch.int16), k_ref.view(torch.int16))
+        assert torch.equal(p.v_ctx.view(torch.int16), v_ref.view(torch.int16))
+    with pytest.raises(mpic.MpicError):
+        mpic.mpic_assemble_kv_parts(p.ctx.handle, p.plan.handle, p.srcs, p.d_fk, p.d_fv, p.k_ctx, p.v_ctx, 0)
