@@ -14,6 +14,9 @@ Pin status of every function (see tests/test_oracle_*.py):
                          counts, brute-force set construction on random layouts
   rope.rotate            pinned: complex-multiplication form of RoPE, group laws
   link.link_kv           pinned: consistent-cache case reproduces full prefill
+  link.position_fresh    pinned: row-by-row complex form of RoPE at per-request position
+                         ids, full prefill reproduced from unpositioned fresh rows,
+                         logits depend on the signed distance only
   attend.attend          pinned: loop transcription of App. A, library SDPA in the
                          recompute-all case, closed forms (zero queries, one-hot V)
 The paper prints no worked numeric example of this path, so beyond those pins the
@@ -21,5 +24,5 @@ values are unpinned by the paper itself.
 """
 from .plan import build_plan            # noqa: F401
 from .rope import rotate                # noqa: F401
-from .link import link_kv, to_slots     # noqa: F401
+from .link import link_kv, position_fresh, to_slots     # noqa: F401
 from .attend import attend, attend_loops  # noqa: F401

@@ -4,17 +4,33 @@ Fig. 7 step 2 and Sec. 4.1: the K (and V) rows of the selected tokens are replac
 by the freshly generated ones; every other row comes from the stored cache of its
 image.  Stored keys are moved from chunk-local to global positions with
 rope.rotate; values carry no position and are copied.
+
+Fresh rows may be handed over straight from the projections, before any positional
+embedding (the step Fig. 7 leaves out): position_fresh then turns every fresh row by
+the position id of its token inside the request, the same rotation full prefill would
+apply.  Queries and keys take it; values never do.
 """
 import numpy as np
 from .rope import rotate
 
 
-def link_kv(plan, chunk_k, chunk_v, fresh_k, fresh_v, theta, interleaved=False):
+def position_fresh(x, plan, theta, interleaved=False):
+    """x [Nq][H][D], one row per token of the recompute set, not yet rotated.  Returns the
+    rows rotated to their position ids plan["q_pos"] (float64)."""
+    x = np.asarray(x, dtype=np.float64)
+    pos = np.asarray(plan["q_pos"], dtype=np.float64)
+    return rotate(x, pos[:, None], theta, interleaved)
+
+
+def link_kv(plan, chunk_k, chunk_v, fresh_k, fresh_v, theta, interleaved=False, fresh_pre_rope=False):
     """chunk_k / chunk_v: mapping source id -> float64 array [L][Hkv][D];
     fresh_k / fresh_v: float64 [Nq][Hkv][D].  Returns (K, V) in logical order
-    [N][Hkv][D] (requests one after the other), float64."""
+    [N][Hkv][D] (requests one after the other), float64.  With fresh_pre_rope the
+    fresh keys are rotated to their positions first (see position_fresh)."""
     n = int(plan["ctx_off"][-1])
     fresh_k = np.asarray(fresh_k, dtype=np.float64)
+    if fresh_pre_rope:
+        fresh_k = position_fresh(fresh_k, plan, theta, interleaved)
     fresh_v = np.asarray(fresh_v, dtype=np.float64)
     K = np.empty((n,) + fresh_k.shape[1:], dtype=np.float64)
     V = np.empty_like(K)

@@ -10,7 +10,7 @@ import pytest
 import torch
 
 import workloads
-from oracle import attend, attend_loops, build_plan, link_kv, rotate, to_slots
+from oracle import attend, attend_loops, build_plan, link_kv, position_fresh, rotate, to_slots
 
 RNG = np.random.default_rng(1234)
 
@@ -212,6 +212,70 @@ def test_consistent_cache_reproduces_full_prefill(k, interleaved):
     o, _ = attend(q_full[sel], K, V, plan, 0.25)
     full = _sdpa(q_full, k_full, v0, 0.25, hq // hkv)
     np.testing.assert_allclose(o, full[sel], rtol=1e-10, atol=1e-11)
+
+
+@pytest.mark.parametrize("interleaved", [False, True])
+def test_pre_rope_fresh_rows_take_their_position_inside_the_request(interleaved):
+    """Fresh rows handed over before positional embedding: linking must give every context
+    row the rotation of its own position id, counted from the start of *its* request, which
+    is what full prefill applies -- checked against the complex-number form of RoPE, row by
+    row, on a batch of two requests (so a batch-flattened index or a fresh-row index used as
+    the position would show)."""
+    theta, hq, hkv, d = 1e4, 4, 2, 16
+    reqs = [[("text", 4), ("chunk", 0, 8, None), ("text", 3), ("chunk", 1, 6, None), ("text", 2)],
+            [("chunk", 1, 6, None), ("text", 5), ("chunk", 0, 8, 3)]]
+    plan = build_plan(reqs, 2)
+    n = int(plan["ctx_off"][-1])
+    rng = np.random.default_rng(17)
+    k0, v0, q0 = rng.standard_normal((n, hkv, d)), rng.standard_normal((n, hkv, d)), rng.standard_normal((n, hq, d))
+    # the two requests share their stored chunks, so the position-free base rows of a chunk
+    # must agree wherever it appears
+    first = {}
+    for inst in range(len(plan["inst_src"])):
+        src, L = int(plan["inst_src"][inst]), int(plan["inst_len"][inst])
+        g0 = int(plan["ctx_off"][plan["inst_req"][inst]]) + int(plan["inst_delta"][inst])
+        if src in first:
+            k0[g0:g0 + L], v0[g0:g0 + L] = k0[first[src]:first[src] + L], v0[first[src]:first[src] + L]
+        else:
+            first[src] = g0
+    pos = np.concatenate([np.arange(plan["ctx_off"][b + 1] - plan["ctx_off"][b]) for b in range(2)])
+    k_full = np.stack([_rope_complex(k0[g], float(pos[g]), theta, interleaved) for g in range(n)])
+    q_full = np.stack([_rope_complex(q0[g], float(pos[g]), theta, interleaved) for g in range(n)])
+    chunk_k, chunk_v = {}, {}
+    for src, g0 in first.items():
+        L = 8 if src == 0 else 6
+        chunk_k[src] = np.stack([_rope_complex(k0[g0 + t], float(t), theta, interleaved) for t in range(L)])
+        chunk_v[src] = v0[g0:g0 + L]
+    sel = plan["ctx_off"][plan["q_req"]] + plan["q_pos"]          # batch-flattened rows of the recompute set
+    K, V = link_kv(plan, chunk_k, chunk_v, k0[sel], v0[sel], theta, interleaved, fresh_pre_rope=True)
+    np.testing.assert_allclose(K, k_full, atol=1e-12)
+    assert np.array_equal(V, v0)
+    q_rot = position_fresh(q0[sel], plan, theta, interleaved)
+    np.testing.assert_allclose(q_rot, q_full[sel], atol=1e-12)
+    o, _ = attend(q_rot, K, V, plan, 0.25)
+    for b in range(2):
+        lo, hi = int(plan["ctx_off"][b]), int(plan["ctx_off"][b + 1])
+        full = _sdpa(q_full[lo:hi], k_full[lo:hi], v0[lo:hi], 0.25, hq // hkv)
+        rows = np.flatnonzero(plan["q_req"] == b)
+        np.testing.assert_allclose(o[rows], full[plan["q_pos"][rows]], rtol=1e-10, atol=1e-11)
+
+
+def test_pre_rope_logits_depend_on_relative_position_only():
+    """<Rot(p) q, Rot(j) k> = <q, Rot(j - p) k>: the logit of a positioned fresh query against a
+    positioned fresh key equals the unpositioned query against the key turned by the signed
+    distance (a rotation of the query in the wrong direction would fail this)."""
+    theta, d = 1e6, 32
+    reqs = [[("text", 3), ("chunk", 0, 40, None), ("text", 2)]]
+    plan = build_plan(reqs, 4)
+    rng = np.random.default_rng(18)
+    nq = len(plan["q_pos"])
+    q0, k0 = rng.standard_normal((nq, 1, d)), rng.standard_normal((nq, 1, d))
+    q, k = position_fresh(q0, plan, theta), position_fresh(k0, plan, theta)
+    for r in range(nq):
+        for j in range(nq):
+            dist = float(plan["q_pos"][j] - plan["q_pos"][r])
+            want = q0[r, 0] @ _rope_complex(k0[j, 0], dist, theta, False)
+            assert abs(q[r, 0] @ k[j, 0] - want) < 1e-10
 
 
 def test_link_replaces_rows_and_shifts_by_chunk_offset():
