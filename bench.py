@@ -34,6 +34,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=3, help="workload id (BASELINE.json configs, 1-based)")
     ap.add_argument("--layers", type=int, default=4, help="distinct layer input sets the steps cycle over")
+    ap.add_argument("--fresh-pre-rope", action="store_true",
+                    help="hand fresh Q/K over before positional embedding (the library rotates them)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-host-sourced", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -69,7 +71,8 @@ def main():
         tables, pool = workloads.gen_page_tables(sh, lens)
     n_slots = pool * sh.page_size if sh.page_size else sum(lens)
 
-    ctx = mpic.Context(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, mpic.MPIC_BF16, sh.rope_theta, 0, sh.page_size)
+    ctx = mpic.Context(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, mpic.MPIC_BF16, sh.rope_theta, 0, sh.page_size,
+                       int(args.fresh_pre_rope))
     t0 = time.perf_counter()
     plan = mpic.Plan(ctx, requests, sh.default_k, tables, pool)
     plan_ms = (time.perf_counter() - t0) * 1e3
@@ -222,7 +225,7 @@ def main():
     # ---- the oracle on the host cores (reported baseline, bounded sample) ------
     cpu = None
     if not args.no_cpu_baseline:
-        from oracle import attend as o_attend, build_plan, link_kv
+        from oracle import attend as o_attend, build_plan, link_kv, position_fresh
         n_req = min(2, len(requests))
         sub = requests[:n_req]
         oplan = build_plan(sub, sh.default_k)
@@ -234,7 +237,9 @@ def main():
         fk = np.concatenate([f64(f[1]) for f in fresh])
         fv = np.concatenate([f64(f[2]) for f in fresh])
         t0 = time.perf_counter()
-        K, V = link_kv(oplan, ck, cv, fk, fv, sh.rope_theta)
+        K, V = link_kv(oplan, ck, cv, fk, fv, sh.rope_theta, False, args.fresh_pre_rope)
+        if args.fresh_pre_rope:
+            fq = position_fresh(fq, oplan, sh.rope_theta)
         o_attend(fq, K, V, oplan, sh.softmax_scale)
         dt = time.perf_counter() - t0
         fl = 4.0 * sh.head_dim * sh.n_q_heads * int((oplan["q_pos"].astype(np.int64) + 1).sum())
@@ -266,6 +271,7 @@ def main():
         "config": {"workload": f"config{args.config}:{sh.name}", "batch": len(requests), "tokens_per_request": lens[0],
                    "recompute_rows": n_q, "q_heads": sh.n_q_heads, "kv_heads": sh.n_kv_heads, "head_dim": sh.head_dim,
                    "k": sh.default_k, "page_size": sh.page_size, "layer_sets": L,
+                   "fresh_rows": "rotated by the library" if args.fresh_pre_rope else "handed over rotated",
                    "chunks": "HBM-resident", "plan": "built once per batch, reused by every step",
                    "overlap": "cached rows of step i+1 linked on a second stream while step i attends"},
         "roofline": {"bound": "mfma", "achieved": round(attn_tflops, 3), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",

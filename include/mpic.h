@@ -58,6 +58,11 @@ typedef struct mpic_config {
   double rope_theta;        /* rotary base; pair i turns by shift * theta^(-2i/D)    */
   int32_t rope_interleaved; /* 0: pairs (i, i+D/2) "rotate-half"; 1: pairs (2i,2i+1) */
   int32_t page_size;        /* 0: contiguous context; >0: tokens per physical page   */
+  int32_t fresh_pre_rope;   /* 0: fresh Q and K already carry their positions;       */
+                            /* 1: they come straight from the projections and the    */
+                            /*    library rotates them (K while linking, Q while     */
+                            /*    attending) by the position id of their token, the  */
+                            /*    positional step that Fig. 7 leaves out             */
 } mpic_config;
 
 /* One segment of a request, in prompt order. */
@@ -104,7 +109,8 @@ enum {
  * mpic_assemble_kv / mpic_selective_attn, which binds the context to the GPU that
  * is current at that moment.
  * Errors: MPIC_ERR_INVALID (null pointer, non-positive sizes, Hq % Hkv != 0, odd
- * head_dim, theta <= 0, page_size < 0), MPIC_ERR_UNSUPPORTED (dtype / head_dim).
+ * head_dim, theta <= 0, page_size < 0, flags other than 0 / 1), MPIC_ERR_UNSUPPORTED
+ * (dtype / head_dim).
  */
 int mpic_create(mpic_ctx** out, const mpic_config* config);
 
@@ -149,6 +155,15 @@ int mpic_plan_get(const mpic_plan* plan, int32_t what, const int32_t** host_ptr,
 int mpic_plan_get_rope(const mpic_plan* plan, const float** cos_tab, const float** sin_tab,
                        size_t* n);
 
+/*
+ * Borrow the rotary tables of the fresh rows (contexts created with fresh_pre_rope = 1;
+ * otherwise *n_rows = 0): table_row [Nq] gives, for every fresh row, its row in cos_tab /
+ * sin_tab, which hold cos and sin of position * theta^(-2i/D) as [n_rows][D/2] floats, one
+ * row per distinct position id of the batch.
+ */
+int mpic_plan_get_fresh_rope(const mpic_plan* plan, const int32_t** table_row, const float** cos_tab,
+                             const float** sin_tab, size_t* n_rows);
+
 /* Destroy a plan (device copies included).  The caller must have synchronised every
  * stream that still uses it.  NULL is allowed. */
 void mpic_plan_destroy(mpic_plan* plan);
@@ -170,7 +185,10 @@ void mpic_plan_destroy(mpic_plan* plan);
  *                     on_host != 0 (copied on the library's side stream into library
  *                     staging, overlapped with the linking of other rows).
  *   fresh_k, fresh_v  device [n_fresh_rows][Hkv][D]; may be NULL only if the plan
- *                     has no fresh row.  Keys already carry their global position.
+ *                     has no fresh row.  Keys already carry their global position,
+ *                     unless the context was created with fresh_pre_rope = 1: then each
+ *                     fresh key is rotated by its position id on its way into K_ctx
+ *                     (fp32 arithmetic, one rounding), like a stored key by its shift.
  *   n_fresh_rows      must equal the plan's total recompute-set size
  *   k_ctx, v_ctx      device [n_ctx_slots][Hkv][D], written
  *   n_ctx_slots       slots in k_ctx / v_ctx; must cover every slot of the plan
@@ -208,7 +226,10 @@ int mpic_assemble_kv_parts(mpic_ctx* ctx, mpic_plan* plan, const mpic_chunk_src*
  * probabilities rounded to bf16 before the second product, one final rounding of
  * out.  F32: fp32 throughout.
  *
- *   fresh_q           device [n_fresh_rows][Hq][D], already rotated for its position
+ *   fresh_q           device [n_fresh_rows][Hq][D], already rotated for its position;
+ *                     with fresh_pre_rope = 1 not yet rotated: the kernel rotates each
+ *                     row by its position id as it loads it (fp32 arithmetic, rounded
+ *                     once to the storage type before the first product)
  *   k_ctx, v_ctx      device [n_ctx_slots][Hkv][D] as written by mpic_assemble_kv
  *   softmax_scale     finite, > 0 (1/sqrt(D) for the definition of App. A)
  *   out               device [n_fresh_rows][Hq][D], written

@@ -25,7 +25,7 @@ class MpicError(RuntimeError):
 class _Config(C.Structure):
     _fields_ = [("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("dtype", C.c_int32), ("rope_theta", C.c_double), ("rope_interleaved", C.c_int32),
-                ("page_size", C.c_int32)]
+                ("page_size", C.c_int32), ("fresh_pre_rope", C.c_int32)]
 
 
 class _Segment(C.Structure):
@@ -65,6 +65,9 @@ def load_library():
     lib.mpic_plan_get_rope.argtypes = [vp, C.POINTER(C.POINTER(C.c_float)),
                                        C.POINTER(C.POINTER(C.c_float)), C.POINTER(C.c_size_t)]
     lib.mpic_plan_get_rope.restype = C.c_int
+    lib.mpic_plan_get_fresh_rope.argtypes = [vp, C.POINTER(C.POINTER(i32)), C.POINTER(C.POINTER(C.c_float)),
+                                             C.POINTER(C.POINTER(C.c_float)), C.POINTER(C.c_size_t)]
+    lib.mpic_plan_get_fresh_rope.restype = C.c_int
     lib.mpic_plan_destroy.argtypes = [vp]
     lib.mpic_plan_destroy.restype = None
     lib.mpic_assemble_kv.argtypes = [vp, vp, C.POINTER(_ChunkSrc), i32, vp, vp, i64, vp, vp, i64, vp]
@@ -95,8 +98,10 @@ def _check(rc, ctx=None):
         raise MpicError(rc, mpic_last_error(ctx) if ctx else "")
 
 
-def mpic_create(n_q_heads, n_kv_heads, head_dim, dtype, rope_theta, rope_interleaved=0, page_size=0):
-    cfg = _Config(n_q_heads, n_kv_heads, head_dim, dtype, rope_theta, rope_interleaved, page_size)
+def mpic_create(n_q_heads, n_kv_heads, head_dim, dtype, rope_theta, rope_interleaved=0, page_size=0,
+                fresh_pre_rope=0):
+    cfg = _Config(n_q_heads, n_kv_heads, head_dim, dtype, rope_theta, rope_interleaved, page_size,
+                  fresh_pre_rope)
     h = C.c_void_p()
     _check(load_library().mpic_create(C.byref(h), C.byref(cfg)))
     return h
@@ -162,6 +167,17 @@ def mpic_plan_get_rope(plan):
             np.ctypeslib.as_array(s, shape=(n.value,)).copy())
 
 
+def mpic_plan_get_fresh_rope(plan, n_fresh_rows, half_dim):
+    """(table_row [Nq], cos [n_rows][D/2], sin [n_rows][D/2]) of a fresh_pre_rope context."""
+    idx, c, s, n = C.POINTER(C.c_int32)(), C.POINTER(C.c_float)(), C.POINTER(C.c_float)(), C.c_size_t()
+    _check(load_library().mpic_plan_get_fresh_rope(plan, C.byref(idx), C.byref(c), C.byref(s), C.byref(n)))
+    if not n.value:
+        return np.zeros(0, np.int32), np.zeros((0, half_dim), np.float32), np.zeros((0, half_dim), np.float32)
+    return (np.ctypeslib.as_array(idx, shape=(n_fresh_rows,)).copy(),
+            np.ctypeslib.as_array(c, shape=(n.value, half_dim)).copy(),
+            np.ctypeslib.as_array(s, shape=(n.value, half_dim)).copy())
+
+
 def mpic_plan_destroy(plan):
     load_library().mpic_plan_destroy(plan)
 
@@ -215,8 +231,10 @@ def mpic_selective_attn(ctx, plan, fresh_q, k_ctx, v_ctx, softmax_scale, out, ls
 
 # ---------------------------------------------------------------- handle owners
 class Context:
-    def __init__(self, n_q_heads, n_kv_heads, head_dim, dtype, rope_theta, rope_interleaved=0, page_size=0):
-        self.handle = mpic_create(n_q_heads, n_kv_heads, head_dim, dtype, rope_theta, rope_interleaved, page_size)
+    def __init__(self, n_q_heads, n_kv_heads, head_dim, dtype, rope_theta, rope_interleaved=0, page_size=0,
+                 fresh_pre_rope=0):
+        self.handle = mpic_create(n_q_heads, n_kv_heads, head_dim, dtype, rope_theta, rope_interleaved, page_size,
+                                  fresh_pre_rope)
         self.n_q_heads, self.n_kv_heads, self.head_dim = n_q_heads, n_kv_heads, head_dim
         self.dtype, self.page_size = dtype, page_size
 
@@ -242,6 +260,9 @@ class Plan:
 
     def rope(self):
         return mpic_plan_get_rope(self.handle)
+
+    def fresh_rope(self):
+        return mpic_plan_get_fresh_rope(self.handle, len(self.get("q_pos")), self.ctx.head_dim // 2)
 
     def as_dict(self):
         return {k: self.get(k) for k in PLAN_FIELDS}

@@ -39,7 +39,8 @@ int upload_plan(mpic_ctx* ctx, mpic_plan* p) {
   }
   const size_t n = p->n_ctx, nq = p->n_q, B = p->n_requests;
   size_t total = 3 * padded<int32_t>(n) + padded<int32_t>(n + kTablePad) + padded<int32_t>(nq) + padded<int32_t>(nq) + 2 * padded<int32_t>(B + 1) +
-                 2 * padded<float>(p->rope_cos.size()) + padded<AttnTile>(p->tiles.size()) + 256;
+                 2 * padded<float>(p->rope_cos.size()) + padded<AttnTile>(p->tiles.size()) + 256 +
+                 padded<int32_t>(p->fresh_rot.size()) + 2 * padded<float>(p->fresh_cos.size());
   char* base = nullptr;
   hipError_t e = hipMalloc(reinterpret_cast<void**>(&base), total);
   if (e != hipSuccess) {
@@ -84,6 +85,12 @@ int upload_plan(mpic_ctx* ctx, mpic_plan* p) {
   const size_t nr = p->rope_cos.size();
   if (e == hipSuccess) d.rope_cos = static_cast<float*>(put(p->rope_cos.data(), nr * 4, padded<float>(nr)));
   if (e == hipSuccess) d.rope_sin = static_cast<float*>(put(p->rope_sin.data(), nr * 4, padded<float>(nr)));
+  if (!p->fresh_rot.empty()) {
+    const size_t nf = p->fresh_cos.size();
+    if (e == hipSuccess) d.fresh_rot = static_cast<int32_t*>(put(p->fresh_rot.data(), nq * 4, padded<int32_t>(nq)));
+    if (e == hipSuccess) d.fresh_cos = static_cast<float*>(put(p->fresh_cos.data(), nf * 4, padded<float>(nf)));
+    if (e == hipSuccess) d.fresh_sin = static_cast<float*>(put(p->fresh_sin.data(), nf * 4, padded<float>(nf)));
+  }
   if (e == hipSuccess)
     d.tiles = static_cast<AttnTile*>(put(p->tiles.data(), p->tiles.size() * sizeof(AttnTile),
                                          padded<AttnTile>(p->tiles.size())));
@@ -252,6 +259,9 @@ extern "C" int mpic_assemble_kv_parts(mpic_ctx* ctx, mpic_plan* plan, const mpic
   a.dst_slot = plan->dev.dst_slot;
   a.rope_cos = plan->dev.rope_cos;
   a.rope_sin = plan->dev.rope_sin;
+  a.fresh_rot = plan->dev.fresh_rot;
+  a.fresh_cos = plan->dev.fresh_cos;
+  a.fresh_sin = plan->dev.fresh_sin;
   a.fresh_k = fresh_k;
   a.fresh_v = fresh_v;
   a.k_ctx = k_ctx;
@@ -368,6 +378,10 @@ extern "C" int mpic_selective_attn(mpic_ctx* ctx, mpic_plan* plan, const void* f
   a.n_kv_heads = c.n_kv_heads;
   a.head_dim = c.head_dim;
   a.n_requests = plan->n_requests;
+  a.q_rot = plan->dev.fresh_rot;
+  a.q_cos = plan->dev.fresh_cos;
+  a.q_sin = plan->dev.fresh_sin;
+  a.interleaved = c.rope_interleaved;
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   if (c.dtype == MPIC_F32) {
     MPIC_HIP(ctx, mpic::launch_attn_f32(a, plan->n_q, stream));

@@ -65,16 +65,25 @@ __global__ __launch_bounds__(256) void assemble_kernel(AssembleArgs a, AssembleS
 
   const T* ksrc;
   const T* vsrc;
+  const float* ct = nullptr;  // rotary table row of this context row (null: the key is copied)
+  const float* st = nullptr;
   if (inst < 0) {
     if (a.skip_fresh) return;
     ksrc = static_cast<const T*>(a.fresh_k) + srow * row_elems;
     vsrc = static_cast<const T*>(a.fresh_v) + srow * row_elems;
+    if (a.fresh_rot) {  // fresh keys arrive without positions: turn them by their position id
+      const int64_t u = a.fresh_rot[srow];
+      ct = a.fresh_cos + u * half;
+      st = a.fresh_sin + u * half;
+    }
   } else {
     const T* kt = static_cast<const T*>(tab.k[inst - a.inst_base]);
     const T* vt = static_cast<const T*>(tab.v[inst - a.inst_base]);
     if (kt == nullptr) return;  // source still in flight: a later launch links this row
     ksrc = kt + srow * row_elems;
     vsrc = vt + srow * row_elems;
+    ct = a.rope_cos + static_cast<int64_t>(inst) * half;
+    st = a.rope_sin + static_cast<int64_t>(inst) * half;
   }
   T* kdst = static_cast<T*>(a.k_ctx) + slot * row_elems;
   T* vdst = static_cast<T*>(a.v_ctx) + slot * row_elems;
@@ -102,9 +111,7 @@ __global__ __launch_bounds__(256) void assemble_kernel(AssembleArgs a, AssembleS
   const Raw w1 = __builtin_nontemporal_load(reinterpret_cast<const Raw*>(vsrc + v1));
 
   Raw o0 = k0, o1 = k1;
-  if (inst >= 0) {
-    const float* ct = a.rope_cos + static_cast<int64_t>(inst) * half;
-    const float* st = a.rope_sin + static_cast<int64_t>(inst) * half;
+  if (ct) {
     const Wide x0 = U::widen(k0), x1 = U::widen(k1);
     Wide y0, y1;
     if (kInterleaved) {

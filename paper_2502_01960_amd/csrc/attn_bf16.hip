@@ -128,6 +128,40 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a) {
   bf16x8 qf[8];
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16 + hi * 8);
+  if (a.q_rot) {
+    // Queries that arrive without positions are turned by their position id here, in fp32,
+    // and rounded once.  This lane holds coordinates d = 16*ks + 8*hi + e: a rotate-half
+    // pair (d, d + 64) is (qf[ks], qf[ks + 4]) element by element, an interleaved pair
+    // (2i, 2i + 1) is two neighbouring elements of one fragment.
+    const int64_t u = a.q_rot[fresh_row];
+    const float* ct = a.q_cos + u * (D / 2);
+    const float* st = a.q_sin + u * (D / 2);
+    if (a.interleaved) {
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        const f32x4 c = *reinterpret_cast<const f32x4*>(ct + ks * 8 + hi * 4);
+        const f32x4 s = *reinterpret_cast<const f32x4*>(st + ks * 8 + hi * 4);
+        const f32x8 x = __builtin_convertvector(qf[ks], f32x8);
+        f32x8 y;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          y[2 * i] = x[2 * i] * c[i] - x[2 * i + 1] * s[i];
+          y[2 * i + 1] = x[2 * i] * s[i] + x[2 * i + 1] * c[i];
+        }
+        qf[ks] = __builtin_convertvector(y, bf16x8);
+      }
+    } else {
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        const f32x8 c = *reinterpret_cast<const f32x8*>(ct + ks * 16 + hi * 8);
+        const f32x8 s = *reinterpret_cast<const f32x8*>(st + ks * 16 + hi * 8);
+        const f32x8 x0 = __builtin_convertvector(qf[ks], f32x8);
+        const f32x8 x1 = __builtin_convertvector(qf[ks + 4], f32x8);
+        qf[ks] = __builtin_convertvector(x0 * c - x1 * s, bf16x8);
+        qf[ks + 4] = __builtin_convertvector(x0 * s + x1 * c, bf16x8);
+      }
+    }
+  }
 
   const float posf = static_cast<float>(valid ? my_pos : -1);
   const int wave_hi_pos = static_cast<int>(wave_max(posf));  // -1: idle wave

@@ -36,6 +36,27 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(AttnArgs a, int64_t n_q) 
     q[d] = t.x; q[d + 1] = t.y; q[d + 2] = t.z; q[d + 3] = t.w;
   }
 
+  if (a.q_rot) {
+    // a query that arrives without its position is turned by its position id first
+    const float* ct = a.q_cos + static_cast<int64_t>(a.q_rot[r]) * (D / 2);
+    const float* st = a.q_sin + static_cast<int64_t>(a.q_rot[r]) * (D / 2);
+    if (a.interleaved) {
+#pragma unroll
+      for (int i = 0; i < D / 2; ++i) {
+        const float x = q[2 * i], y = q[2 * i + 1], c = ct[i], s = st[i];
+        q[2 * i] = x * c - y * s;
+        q[2 * i + 1] = x * s + y * c;
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < D / 2; ++i) {
+        const float x = q[i], y = q[i + D / 2], c = ct[i], s = st[i];
+        q[i] = x * c - y * s;
+        q[i + D / 2] = x * s + y * c;
+      }
+    }
+  }
+
   auto logit = [&](int j) {
     const float* kp = K + static_cast<int64_t>(slot_of[j]) * row_elems;
     float acc = 0.f;

@@ -34,6 +34,9 @@ struct PlanDevice {
   int32_t* ctx_off = nullptr;
   float* rope_cos = nullptr;
   float* rope_sin = nullptr;
+  int32_t* fresh_rot = nullptr;  // row of fresh_cos / fresh_sin for every fresh row (null: rows arrive rotated)
+  float* fresh_cos = nullptr;
+  float* fresh_sin = nullptr;
   AttnTile* tiles = nullptr;
   void* block = nullptr;  // the single allocation all of the above point into
   int device = -1;
@@ -70,6 +73,8 @@ struct mpic_plan {
   std::vector<int32_t> inst_src, inst_delta, inst_len, inst_k, inst_req, runs;
   std::vector<mpic::AttnTile> tiles;
   std::vector<float> rope_cos, rope_sin;
+  std::vector<int32_t> fresh_rot;            // contexts with fresh_pre_rope only
+  std::vector<float> fresh_cos, fresh_sin;   // one row per distinct position id
   mpic::PlanDevice dev;
 };
 
@@ -95,6 +100,9 @@ struct AssembleArgs {
   const int32_t* dst_slot;
   const float* rope_cos;
   const float* rope_sin;
+  const int32_t* fresh_rot;  // non-null: fresh keys are rotated with row fresh_rot[r] of fresh_cos / fresh_sin
+  const float* fresh_cos;
+  const float* fresh_sin;
   const void* fresh_k;
   const void* fresh_v;
   void* k_ctx;
@@ -130,6 +138,10 @@ struct AttnArgs {
   float scale;
   int32_t n_q_heads, n_kv_heads, head_dim;
   int32_t n_requests;
+  const int32_t* q_rot;  // non-null: queries are rotated with row q_rot[r] of q_cos / q_sin on load
+  const float* q_cos;
+  const float* q_sin;
+  int32_t interleaved;
 };
 hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t stream);
 hipError_t launch_attn_f32(const AttnArgs& a, int64_t n_q, hipStream_t stream);

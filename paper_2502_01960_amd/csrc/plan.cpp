@@ -128,6 +128,58 @@ void build_tiles(mpic_plan& p, int group, int n_kv_heads) {
   while (!p.tiles.empty() && p.tiles.back().n_rows == 0) p.tiles.pop_back();
 }
 
+// Rotary tables of the fresh rows, for contexts whose fresh Q/K arrive without positions:
+// one table row per distinct position id of the batch (requests with the same layout share
+// all of them) and an index per fresh row.  cos/sin of p * w_i are evaluated in double
+// from p = 256 * hi + lo by the angle-addition formulas, which needs (max_p / 256 + 256)
+// evaluations per frequency instead of one per position, and are rounded once to float.
+void build_fresh_rope(mpic_plan& p, const mpic_config& c) {
+  const int half = c.head_dim / 2;
+  const size_t nq = p.q_pos.size();
+  p.fresh_rot.resize(nq);
+  if (nq == 0) return;
+  const int32_t max_pos = *std::max_element(p.q_pos.begin(), p.q_pos.end());
+  std::vector<int32_t> row_of(static_cast<size_t>(max_pos) + 1, -1);
+  std::vector<int32_t> uniq;
+  for (size_t r = 0; r < nq; ++r) {
+    int32_t& u = row_of[p.q_pos[r]];
+    if (u < 0) {
+      u = static_cast<int32_t>(uniq.size());
+      uniq.push_back(p.q_pos[r]);
+    }
+    p.fresh_rot[r] = u;
+  }
+  constexpr int kLo = 256;
+  const int n_hi = max_pos / kLo + 1;
+  std::vector<double> hi_c(static_cast<size_t>(n_hi) * half), hi_s(hi_c.size());
+  std::vector<double> lo_c(static_cast<size_t>(kLo) * half), lo_s(lo_c.size());
+  for (int j = 0; j < half; ++j) {
+    const double w = std::pow(c.rope_theta, -2.0 * j / c.head_dim);
+    for (int h = 0; h < n_hi; ++h) {
+      const double phi = static_cast<double>(h) * kLo * w;
+      hi_c[static_cast<size_t>(h) * half + j] = std::cos(phi);
+      hi_s[static_cast<size_t>(h) * half + j] = std::sin(phi);
+    }
+    for (int l = 0; l < kLo; ++l) {
+      const double phi = static_cast<double>(l) * w;
+      lo_c[static_cast<size_t>(l) * half + j] = std::cos(phi);
+      lo_s[static_cast<size_t>(l) * half + j] = std::sin(phi);
+    }
+  }
+  p.fresh_cos.resize(uniq.size() * half);
+  p.fresh_sin.resize(uniq.size() * half);
+  for (size_t u = 0; u < uniq.size(); ++u) {
+    const double* hc = &hi_c[static_cast<size_t>(uniq[u] / kLo) * half];
+    const double* hs = &hi_s[static_cast<size_t>(uniq[u] / kLo) * half];
+    const double* lc = &lo_c[static_cast<size_t>(uniq[u] % kLo) * half];
+    const double* ls = &lo_s[static_cast<size_t>(uniq[u] % kLo) * half];
+    for (int j = 0; j < half; ++j) {
+      p.fresh_cos[u * half + j] = static_cast<float>(hc[j] * lc[j] - hs[j] * ls[j]);
+      p.fresh_sin[u * half + j] = static_cast<float>(hs[j] * lc[j] + hc[j] * ls[j]);
+    }
+  }
+}
+
 }  // namespace
 }  // namespace mpic
 
@@ -139,7 +191,7 @@ extern "C" int mpic_create(mpic_ctx** out, const mpic_config* config) {
   const mpic_config& c = *config;
   if (c.n_q_heads <= 0 || c.n_kv_heads <= 0 || c.head_dim <= 0 || c.n_q_heads % c.n_kv_heads != 0 ||
       (c.head_dim & 1) || !(c.rope_theta > 0.0) || !std::isfinite(c.rope_theta) || c.page_size < 0 ||
-      (c.rope_interleaved != 0 && c.rope_interleaved != 1))
+      (c.rope_interleaved != 0 && c.rope_interleaved != 1) || (c.fresh_pre_rope != 0 && c.fresh_pre_rope != 1))
     return MPIC_ERR_INVALID;
   if (c.dtype == MPIC_F32) {
     if (c.head_dim != 64 && c.head_dim != 128) return MPIC_ERR_UNSUPPORTED;
@@ -291,6 +343,7 @@ extern "C" int mpic_plan_create(mpic_ctx* ctx, int32_t n_requests, const int32_t
         p->rope_cos[i * half + j] = static_cast<float>(std::cos(phi));
         p->rope_sin[i * half + j] = static_cast<float>(std::sin(phi));
       }
+    if (ctx->cfg.fresh_pre_rope) mpic::build_fresh_rope(*p, ctx->cfg);
     mpic::build_tiles(*p, ctx->group, ctx->cfg.n_kv_heads);
   } catch (const std::bad_alloc&) {
     delete p;
@@ -336,6 +389,16 @@ extern "C" int mpic_plan_get_rope(const mpic_plan* plan, const float** cos_tab, 
   *cos_tab = plan->rope_cos.data();
   *sin_tab = plan->rope_sin.data();
   *n = plan->rope_cos.size();
+  return MPIC_OK;
+}
+
+extern "C" int mpic_plan_get_fresh_rope(const mpic_plan* plan, const int32_t** table_row,
+                                        const float** cos_tab, const float** sin_tab, size_t* n_rows) {
+  if (!plan || !table_row || !cos_tab || !sin_tab || !n_rows) return MPIC_ERR_INVALID;
+  *table_row = plan->fresh_rot.data();
+  *cos_tab = plan->fresh_cos.data();
+  *sin_tab = plan->fresh_sin.data();
+  *n_rows = plan->fresh_cos.size() / (plan->ctx->cfg.head_dim / 2);
   return MPIC_OK;
 }
 

@@ -6,14 +6,18 @@ import torch
 
 import workloads
 import paper_2502_01960_amd as mpic
-from oracle import attend, build_plan, link_kv
+from oracle import attend, build_plan, link_kv, position_fresh
 
 
 class Problem:
     """Inputs of one layer of one batch, as host tensors in the storage dtype."""
+    interleaved = False
+    pre_rope = False
 
-    def __init__(self, cfg_id, *, k=None, layer=0, paged=None, **layout_kw):
+    def __init__(self, cfg_id, *, k=None, layer=0, paged=None, interleaved=False, pre_rope=False, **layout_kw):
         self.sh = sh = workloads.shape(cfg_id)
+        self.interleaved = interleaved   # rotary pairing (2i, 2i+1) instead of (i, i+D/2)
+        self.pre_rope = pre_rope         # fresh Q/K are handed over before positional embedding
         self.layer = layer
         self.k = sh.default_k if k is None else k
         self.requests, self.n_src, self.src_len = workloads.layout(cfg_id, **layout_kw)
@@ -40,17 +44,22 @@ class Problem:
         f64 = lambda t: t.to(torch.float64).numpy()
         ck = {s: f64(kv[0]) for s, kv in self.chunks.items()}
         cv = {s: f64(kv[1]) for s, kv in self.chunks.items()}
-        return link_kv(self.oplan, ck, cv, f64(self.fresh_k), f64(self.fresh_v), self.sh.rope_theta)
+        return link_kv(self.oplan, ck, cv, f64(self.fresh_k), f64(self.fresh_v), self.sh.rope_theta,
+                       self.interleaved, self.pre_rope)
 
     def oracle_attend(self, K, V, rows=None):
-        return attend(self.q.to(torch.float64).numpy(), K, V, self.oplan, self.sh.softmax_scale, rows=rows)
+        q = self.q.to(torch.float64).numpy()
+        if self.pre_rope:
+            q = position_fresh(q, self.oplan, self.sh.rope_theta, self.interleaved)
+        return attend(q, K, V, self.oplan, self.sh.softmax_scale, rows=rows)
 
     # ---- HIP side ----------------------------------------------------------
     def gpu_setup(self, host_sourced=None):
         sh = self.sh
         dev = torch.device("cuda:0")
         dt = mpic.MPIC_F32 if sh.dtype == "f32" else mpic.MPIC_BF16
-        self.ctx = mpic.Context(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, dt, sh.rope_theta, 0, self.page_size)
+        self.ctx = mpic.Context(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, dt, sh.rope_theta,
+                                int(self.interleaved), self.page_size, int(self.pre_rope))
         self.plan = mpic.Plan(self.ctx, self.requests, self.k, self.page_tables, self.n_pool_pages)
         host = sh.host_sourced if host_sourced is None else host_sourced
         self.srcs = []

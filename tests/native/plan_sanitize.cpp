@@ -29,6 +29,7 @@ int main() {
     cfg.dtype = MPIC_BF16;
     cfg.rope_theta = 1e4 + iter;
     cfg.page_size = (iter % 3 == 0) ? 16 : 0;
+    cfg.fresh_pre_rope = iter % 2;
     mpic_ctx* ctx = nullptr;
     CHECK(mpic_create(&ctx, &cfg) == MPIC_OK);
     const int B = rnd(1, 4);
@@ -86,6 +87,15 @@ int main() {
     const float *c = nullptr, *s = nullptr;
     CHECK(mpic_plan_get_rope(plan, &c, &s, &n) == MPIC_OK);
     for (size_t i = 0; i < n; ++i) sum += static_cast<long long>(c[i] * 4 + s[i] * 4);
+    const int32_t* fr = nullptr;
+    CHECK(mpic_plan_get_fresh_rope(plan, &fr, &c, &s, &n) == MPIC_OK);
+    CHECK(cfg.fresh_pre_rope ? (n_q == 0 || n > 0) : n == 0);
+    if (n > 0) {
+      for (size_t r = 0; r < n_q; ++r) {
+        CHECK(fr[r] >= 0 && static_cast<size_t>(fr[r]) < n);
+        sum += static_cast<long long>(c[fr[r] * 64 + 63] * 4 + s[fr[r] * 64] * 4);
+      }
+    }
     // argument checks that fail before any GPU call
     CHECK(mpic_assemble_kv(ctx, plan, nullptr, 0, nullptr, nullptr, static_cast<int64_t>(n_q) + 1, nullptr, nullptr, 0, nullptr) == MPIC_ERR_INVALID);
     CHECK(mpic_selective_attn(ctx, plan, nullptr, static_cast<int64_t>(n_q) + 1, nullptr, nullptr, 0, 1.0, nullptr, nullptr, nullptr) == MPIC_ERR_INVALID);

@@ -26,7 +26,8 @@ def _check_link(p, K_ref, V_ref, bf16):
     fresh = p.oplan["src_inst"] < 0
     # values and replaced rows are copies: bit-exact
     assert np.array_equal(Vg, V_ref), "V context must be a bit-exact copy"
-    assert np.array_equal(Kg[fresh], K_ref[fresh]), "fresh K rows must be bit-exact copies"
+    if not p.pre_rope:
+        assert np.array_equal(Kg[fresh], K_ref[fresh]), "fresh K rows must be bit-exact copies"
     if bf16:
         assert_bf16_close(Kg, K_ref, "K context")
     else:
@@ -228,6 +229,29 @@ def test_interleaved_rotary_pairs():
         _check_link(p, K_ref, V_ref, sh.dtype == "bf16")
 
 
+def test_fresh_rows_before_positional_embedding():
+    """Contexts created with fresh_pre_rope: the library rotates fresh keys while linking and
+    fresh queries while attending, by their position ids; fp32 and bf16, both pairings,
+    contiguous and paged, several requests (position ids restart per request)."""
+    _run_full(Problem(1, pre_rope=True))
+    _run_full(Problem(1, pre_rope=True, interleaved=True))
+    _run_full(Problem(3, n_chunks=3, chunk_len=301, text_len=37, batch=2, pre_rope=True), host_sourced=False)
+    _run_full(Problem(3, n_chunks=3, chunk_len=301, text_len=37, batch=2, pre_rope=True, interleaved=True),
+              host_sourced=True)
+    _run_full(Problem(5, n_chunks=5, chunk_len=203, text_len=21, pre_rope=True), host_sourced=False)
+    _run_full(Problem(4, k=200, n_chunks=4, chunk_len=160, text_len=70, batch=3, pre_rope=True))
+    # the fresh part alone takes the same route
+    p = Problem(3, n_chunks=2, chunk_len=130, text_len=11, batch=2, pre_rope=True)
+    p.gpu_setup(False)
+    p.gpu_assemble(); torch.cuda.synchronize()
+    k_ref = p.k_ctx.clone()
+    p.k_ctx.fill_(float("nan")); p.v_ctx.fill_(float("nan"))
+    mpic.mpic_assemble_kv_parts(p.ctx.handle, p.plan.handle, p.srcs, None, None, p.k_ctx, p.v_ctx, mpic.MPIC_PART_CACHED)
+    mpic.mpic_assemble_kv_parts(p.ctx.handle, p.plan.handle, None, p.d_fk, p.d_fv, p.k_ctx, p.v_ctx, mpic.MPIC_PART_FRESH)
+    torch.cuda.synchronize()
+    assert torch.equal(p.k_ctx.view(torch.int16), k_ref.view(torch.int16))
+
+
 def test_random_layouts_and_head_groupings():
     """Seeded random layouts (ragged chunks, empty text, k from 0 to beyond the chunk) with
     several head groupings, including a group size of 7 and tiles that straddle runs and
@@ -253,6 +277,7 @@ def test_random_layouts_and_head_groupings():
         paged = 16 if case % 3 == 2 else 0
         p = _custom(reqs, n_src, src_len, int(rng.integers(0, 40)), paged=paged)
         p.sh = dataclasses.replace(p.sh, n_q_heads=hq, n_kv_heads=hkv)
+        p.pre_rope, p.interleaved = case % 3 == 1, case % 4 == 3
         # regenerate the tensors for the new head counts
         p.chunks = {s: workloads.gen_chunk(p.sh, case, s, src_len[s]) for s in p.chunks}
         q_off = p.oplan["q_off"]

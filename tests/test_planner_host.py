@@ -114,6 +114,31 @@ def test_rope_tables_are_float64_accurate():
     np.testing.assert_allclose(sin.reshape(32, 64), np.sin(phi), rtol=0, atol=6e-8)
 
 
+def test_fresh_row_rotary_tables_are_float64_accurate():
+    """fresh_pre_rope contexts: one table row per distinct position id of the batch, every
+    fresh row pointing at the row of its own position id; values against float64 cos / sin."""
+    theta, d = 1e6, 128
+    reqs = [[("text", 64), ("chunk", 0, 2304, None)] * 32 + [("text", 64)],
+            [("chunk", 0, 2304, 7), ("text", 300)]]
+    ctx = mpic.Context(64, 8, d, mpic.MPIC_BF16, theta, 0, 0, 1)
+    plan = mpic.Plan(ctx, reqs, 32)
+    row, cos, sin = plan.fresh_rope()
+    q_pos = plan.get("q_pos")
+    assert len(row) == len(q_pos) and cos.shape == sin.shape == (len(np.unique(q_pos)), d // 2)
+    assert row.min() == 0 and row.max() == len(cos) - 1
+    phi = q_pos.astype(np.float64)[:, None] * theta ** (-2.0 * np.arange(d // 2) / d)
+    assert q_pos.max() == 75839
+    np.testing.assert_allclose(cos[row], np.cos(phi), rtol=0, atol=6e-8)
+    np.testing.assert_allclose(sin[row], np.sin(phi), rtol=0, atol=6e-8)
+    # almost always the correctly rounded float (the two evaluations differ by ~1e-11)
+    assert (cos[row] != np.cos(phi).astype(np.float32)).mean() < 1e-3
+    # a context without the flag carries no such table
+    r0, c0, s0 = mpic.Plan(_ctx(64, 8, d, theta=theta), reqs, 32).fresh_rope()
+    assert len(r0) == 0 and len(c0) == 0
+    with pytest.raises(mpic.MpicError):
+        mpic.Context(4, 4, 64, mpic.MPIC_F32, 1e4, 0, 0, 2)
+
+
 def test_rejected_arguments():
     with pytest.raises(mpic.MpicError):
         _ctx(hq=6, hkv=4)                      # heads do not group
