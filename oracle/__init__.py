@@ -19,6 +19,9 @@ Pin status of every function (see tests/test_oracle_*.py):
                          logits depend on the signed distance only
   attend.attend          pinned: loop transcription of App. A, library SDPA in the
                          recompute-all case, closed forms (zero queries, one-hot V)
+  decode.decode_attend   pinned: the last row of causal prefill over context + new token
+                         (library SDPA), the last row of attend when the request ends
+                         in a text token, closed forms
 The paper prints no worked numeric example of this path, so beyond those pins the
 values are unpinned by the paper itself.
 """
@@ -26,3 +29,4 @@ from .plan import build_plan            # noqa: F401
 from .rope import rotate                # noqa: F401
 from .link import link_kv, position_fresh, to_slots     # noqa: F401
 from .attend import attend, attend_loops  # noqa: F401
+from .decode import decode_attend       # noqa: F401

@@ -10,7 +10,7 @@ import pytest
 import torch
 
 import workloads
-from oracle import attend, attend_loops, build_plan, link_kv, position_fresh, rotate, to_slots
+from oracle import attend, attend_loops, build_plan, decode_attend, link_kv, position_fresh, rotate, to_slots
 
 RNG = np.random.default_rng(1234)
 
@@ -296,3 +296,59 @@ def test_to_slots_places_rows():
     x = np.arange(12, dtype=np.float64).reshape(6, 2)
     out = to_slots(x, [4, 5, 0, 1, 8, 9], 12)
     assert np.array_equal(out[[4, 5, 0, 1, 8, 9]], x) and np.isnan(out[[2, 3, 6, 7, 10, 11]]).all()
+
+
+# ----------------------------------------------------------------- decode step
+def test_decode_step_is_the_last_row_of_causal_prefill():
+    """Context of N tokens plus the new token = causal prefill of N + 1 tokens, last row
+    (library SDPA, float64), for two requests of different length, GQA 3:1."""
+    reqs = [[("text", 3), ("chunk", 0, 6, None), ("text", 2)], [("chunk", 1, 5, None), ("text", 4)]]
+    plan = build_plan(reqs, 2)
+    hq, hkv, d = 6, 2, 8
+    rng = np.random.default_rng(21)
+    n = int(plan["ctx_off"][-1])
+    K, V = rng.standard_normal((n, hkv, d)), rng.standard_normal((n, hkv, d))
+    q, nk, nv = rng.standard_normal((2, hq, d)), rng.standard_normal((2, hkv, d)), rng.standard_normal((2, hkv, d))
+    o, lse = decode_attend(q, K, V, plan, 0.3, nk, nv)
+    for b in range(2):
+        lo, hi = int(plan["ctx_off"][b]), int(plan["ctx_off"][b + 1])
+        kk, vv = np.concatenate([K[lo:hi], nk[b][None]]), np.concatenate([V[lo:hi], nv[b][None]])
+        qq = np.concatenate([rng.standard_normal((hi - lo, hq, d)), q[b][None]])   # earlier rows are irrelevant
+        np.testing.assert_allclose(o[b], _sdpa(qq, kk, vv, 0.3, hq // hkv)[-1], rtol=1e-11, atol=1e-12)
+
+
+def test_decode_step_without_self_equals_attend_row_of_a_final_text_token():
+    """A request that ends in a text token: that token is in the recompute set, sees every
+    position up to itself, so its row of selective attention equals a decode step over the
+    whole context with the same query and no appended token."""
+    _, plan, q, k, v = _tiny_problem(seed=3)
+    o, lse = attend(q, k, v, plan, 0.37)
+    last = [int(plan["q_off"][b + 1]) - 1 for b in range(2)]
+    for b in range(2):
+        assert plan["q_pos"][last[b]] == plan["ctx_off"][b + 1] - plan["ctx_off"][b] - 1
+    od, ld = decode_attend(q[last], k, v, plan, 0.37)
+    np.testing.assert_allclose(od, o[last], rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(ld, lse[last], rtol=1e-12, atol=1e-13)
+
+
+def test_decode_step_closed_forms():
+    reqs = [[("chunk", 0, 7, None)], [("text", 0)], [("text", 2), ("chunk", 1, 3, None)]]
+    plan = build_plan(reqs, 1)
+    hq, hkv, d = 4, 4, 8
+    rng = np.random.default_rng(22)
+    n = int(plan["ctx_off"][-1])
+    K, V = rng.standard_normal((n, hkv, d)), rng.standard_normal((n, hkv, d))
+    zero_q = np.zeros((3, hq, d))
+    o, lse = decode_attend(zero_q, K, V, plan, 1.0)
+    np.testing.assert_allclose(o[0], V[:7].mean(axis=0), atol=1e-13)       # uniform weights
+    np.testing.assert_allclose(lse[0], np.log(7.0), atol=1e-13)
+    assert np.array_equal(o[1], np.zeros((hq, d))) and np.isneginf(lse[1]).all()   # no key at all
+    nk, nv = rng.standard_normal((3, hkv, d)), rng.standard_normal((3, hkv, d))
+    o2, lse2 = decode_attend(zero_q, K, V, plan, 1.0, nk, nv)
+    np.testing.assert_allclose(o2[1], nv[1], atol=1e-13)                   # the token sees only itself
+    np.testing.assert_allclose(lse2[:, 0], np.log([8.0, 1.0, 6.0]), atol=1e-13)
+    # a key aligned with the query and scaled up takes all the weight
+    q = rng.standard_normal((3, hq, d))
+    big = K.copy(); big[9] = 50.0 * q[2] / np.linalg.norm(q[2], axis=-1, keepdims=True)
+    o3, _ = decode_attend(q, big, V, plan, 1.0)
+    np.testing.assert_allclose(o3[2], V[9], atol=1e-6)
