@@ -241,6 +241,36 @@ int mpic_selective_attn(mpic_ctx* ctx, mpic_plan* plan, const void* fresh_q, int
                         const void* k_ctx, const void* v_ctx, int64_t n_ctx_slots,
                         double softmax_scale, void* out, float* lse, void* stream);
 
+/*
+ * Decode-step attention over a linked context (App. A, autoregressive generation: the
+ * query of the next token attends to every cached position and, its key and value being
+ * appended to the cache, to itself).  For every request b of the plan and query head h
+ * (kv head h / (Hq/Hkv)), with N_b the request's context length:
+ *   s_j    = softmax_scale * <q[b][h], K_ctx[slot(j)][kv]>      for positions j = 0..N_b-1
+ *   s_self = softmax_scale * <q[b][h], new_k[b][kv]>            (when new_k is given)
+ *   out[b][h] = softmax-weighted sum of V_ctx[slot(j)][kv] and new_v[b][kv]
+ *   lse[b][h] = log of the softmax denominator                  (optional)
+ * BF16: products on the matrix cores with fp32 accumulation, probabilities rounded to bf16
+ * before the second product, one final rounding of out; the new token's own term is
+ * computed in fp32.  F32: fp32 throughout.
+ *
+ *   q                 device [B][Hq][D], rotated for position N_b by the caller (also on
+ *                     fresh_pre_rope contexts: the plan holds no angle for that position)
+ *   new_k, new_v      device [B][Hkv][D], key (rotated for position N_b) and value of the new
+ *                     token; both NULL to attend to the linked context only
+ *   k_ctx, v_ctx      device [n_ctx_slots][Hkv][D] as written by mpic_assemble_kv
+ *   out               device [B][Hq][D], written; a request with no key at all (N_b = 0 and
+ *                     no new_k) gets zeros and lse = -infinity
+ *   lse               device float [B][Hq], written; may be NULL
+ * Partial results of the key splits live in a workspace owned by the context, allocated on
+ * the first call and grown (with a device synchronisation) when a later call needs more;
+ * calls on one context must therefore not overlap on different streams.
+ * Errors: MPIC_ERR_INVALID, MPIC_ERR_OOM (workspace), MPIC_ERR_HIP.
+ */
+int mpic_decode_attn(mpic_ctx* ctx, mpic_plan* plan, const void* q, const void* new_k,
+                     const void* new_v, const void* k_ctx, const void* v_ctx, int64_t n_ctx_slots,
+                     double softmax_scale, void* out, float* lse, void* stream);
+
 /* Static description of a status code. */
 const char* mpic_strerror(int status);
 

@@ -76,6 +76,8 @@ def load_library():
     lib.mpic_assemble_kv_parts.restype = C.c_int
     lib.mpic_selective_attn.argtypes = [vp, vp, vp, i64, vp, vp, i64, C.c_double, vp, vp, vp]
     lib.mpic_selective_attn.restype = C.c_int
+    lib.mpic_decode_attn.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, C.c_double, vp, vp, vp]
+    lib.mpic_decode_attn.restype = C.c_int
     lib.mpic_strerror.argtypes = [C.c_int]
     lib.mpic_strerror.restype = C.c_char_p
     lib.mpic_last_error.argtypes = [vp]
@@ -226,6 +228,13 @@ def mpic_selective_attn(ctx, plan, fresh_q, k_ctx, v_ctx, softmax_scale, out, ls
     rc = load_library().mpic_selective_attn(ctx, plan, _ptr(fresh_q), n_fresh, _ptr(k_ctx), _ptr(v_ctx),
                                             k_ctx.shape[0], float(softmax_scale), _ptr(out), _ptr(lse),
                                             _stream(stream))
+    _check(rc, ctx)
+
+
+def mpic_decode_attn(ctx, plan, q, new_k, new_v, k_ctx, v_ctx, softmax_scale, out, lse=None, stream=None):
+    rc = load_library().mpic_decode_attn(ctx, plan, _ptr(q), _ptr(new_k), _ptr(new_v), _ptr(k_ctx), _ptr(v_ctx),
+                                         0 if k_ctx is None else k_ctx.shape[0], float(softmax_scale),
+                                         _ptr(out), _ptr(lse), _stream(stream))
     _check(rc, ctx)
 
 

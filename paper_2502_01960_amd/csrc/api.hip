@@ -68,10 +68,13 @@ int upload_plan(mpic_ctx* ctx, mpic_plan* p) {
       (void)hipFree(base);
       return fail(ctx, MPIC_ERR_UNSUPPORTED, "context buffers of 64 GiB or more are not supported");
     }
-    // kTablePad zero entries follow the table: the attention kernel fetches offsets eight
-    // at a time and may run up to one key block past the last key of a tile
+    // kTablePad entries follow the table: the attention kernels fetch offsets eight at a
+    // time and may run up to one key block past the last key of a tile.  They repeat the
+    // last row of the batch, so that what is staged beyond a request's end is always a
+    // linked row (its weight is zero, but 0 x NaN from an untouched slot would not be)
     std::vector<uint32_t> off(n + kTablePad, 0u);
     for (size_t i = 0; i < n; ++i) off[i] = static_cast<uint32_t>(static_cast<uint64_t>(p->dst_slot[i]) * units);
+    for (size_t i = n; i < off.size() && n > 0; ++i) off[i] = off[n - 1];
     if (e == hipSuccess) d.kv_off16 = static_cast<uint32_t*>(put(off.data(), off.size() * 4, padded<int32_t>(off.size())));
   }
   {
@@ -126,6 +129,7 @@ extern "C" void mpic_destroy(mpic_ctx* ctx) {
     for (hipEvent_t ev : ctx->ev_copy) (void)hipEventDestroy(ev);
     for (void* buf : ctx->staging)
       if (buf) (void)hipFree(buf);
+    if (ctx->decode_ws) (void)hipFree(ctx->decode_ws);
     if (cur >= 0) (void)hipSetDevice(cur);
   }
   delete ctx;
@@ -388,5 +392,78 @@ extern "C" int mpic_selective_attn(mpic_ctx* ctx, mpic_plan* plan, const void* f
   } else {
     MPIC_HIP(ctx, mpic::launch_attn_bf16(a, stream));
   }
+  return MPIC_OK;
+}
+
+extern "C" int mpic_decode_attn(mpic_ctx* ctx, mpic_plan* plan, const void* q, const void* new_k,
+                                const void* new_v, const void* k_ctx, const void* v_ctx,
+                                int64_t n_ctx_slots, double softmax_scale, void* out, float* lse,
+                                void* stream_) {
+  if (!ctx) return MPIC_ERR_INVALID;
+  if (!plan || plan->ctx != ctx) return fail(ctx, MPIC_ERR_INVALID, "decode_attn: plan does not belong to this context");
+  if (!(softmax_scale > 0.0) || !std::isfinite(softmax_scale)) return fail(ctx, MPIC_ERR_INVALID, "decode_attn: softmax_scale must be finite and positive");
+  if (!q || !out) return fail(ctx, MPIC_ERR_INVALID, "decode_attn: null buffer");
+  if ((new_k == nullptr) != (new_v == nullptr)) return fail(ctx, MPIC_ERR_INVALID, "decode_attn: new_k and new_v go together");
+  if (plan->n_ctx > 0 && (!k_ctx || !v_ctx)) return fail(ctx, MPIC_ERR_INVALID, "decode_attn: k_ctx / v_ctx missing");
+  if (plan->n_ctx > 0 && n_ctx_slots <= plan->max_slot) return fail(ctx, MPIC_ERR_INVALID, "decode_attn: context buffers smaller than the plan's largest slot");
+  if (!mpic::aligned16(q) || !mpic::aligned16(out) || !mpic::aligned16(k_ctx) || !mpic::aligned16(v_ctx) ||
+      !mpic::aligned16(new_k) || !mpic::aligned16(new_v))
+    return fail(ctx, MPIC_ERR_INVALID, "decode_attn: buffers must be 16-byte aligned");
+  int rc = mpic::bind_device(ctx);
+  if (rc != MPIC_OK) return rc;
+  rc = mpic::upload_plan(ctx, plan);
+  if (rc != MPIC_OK) return rc;
+  const mpic_config& c = ctx->cfg;
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  int32_t max_ctx = 0;
+  for (int b = 0; b < plan->n_requests; ++b) max_ctx = std::max(max_ctx, plan->ctx_off[b + 1] - plan->ctx_off[b]);
+  // Splits: enough workgroups to keep every compute unit streaming (a workgroup fills a
+  // compute unit's LDS, so about two rounds of them), each split a multiple of 128 keys.
+  int32_t n_splits = 1, keys_per_split = std::max(max_ctx, 1);
+  if (c.dtype == MPIC_BF16 && max_ctx > 0) {
+    constexpr int64_t kTargetWorkgroups = 512;
+    const int64_t lanes = static_cast<int64_t>(plan->n_requests) * c.n_kv_heads * ((ctx->group + 31) / 32);
+    const int64_t want = std::max<int64_t>(1, kTargetWorkgroups / lanes);
+    int64_t kps = (max_ctx + want - 1) / want;
+    kps = (kps + mpic::kDecodeBlockKeys - 1) / mpic::kDecodeBlockKeys * mpic::kDecodeBlockKeys;
+    keys_per_split = static_cast<int32_t>(kps);
+    n_splits = static_cast<int32_t>((max_ctx + kps - 1) / kps);
+  }
+  const size_t rows = static_cast<size_t>(plan->n_requests) * c.n_q_heads;
+  const size_t need = rows * n_splits * (c.head_dim + 1) * sizeof(float);
+  if (need > ctx->decode_ws_bytes) {
+    // growing the workspace is rare (first call / larger batch): drain what may still read it
+    MPIC_HIP(ctx, hipDeviceSynchronize());
+    if (ctx->decode_ws) MPIC_HIP(ctx, hipFree(ctx->decode_ws));
+    ctx->decode_ws = nullptr;
+    ctx->decode_ws_bytes = 0;
+    if (hipMalloc(&ctx->decode_ws, need) != hipSuccess) {
+      (void)hipGetLastError();
+      return fail(ctx, MPIC_ERR_OOM, "decode_attn: workspace allocation failed");
+    }
+    ctx->decode_ws_bytes = need;
+  }
+  mpic::DecodeArgs a{};
+  a.ctx_off = plan->dev.ctx_off;
+  a.dst_slot = plan->dev.dst_slot;
+  a.kv_off16 = plan->dev.kv_off16;
+  a.q = q;
+  a.new_k = new_k;
+  a.new_v = new_v;
+  a.k_ctx = k_ctx;
+  a.v_ctx = v_ctx;
+  a.out = out;
+  a.lse = lse;
+  a.ws_o = static_cast<float*>(ctx->decode_ws);
+  a.ws_lse = a.ws_o + rows * n_splits * c.head_dim;
+  a.scale = static_cast<float>(softmax_scale);
+  a.n_q_heads = c.n_q_heads;
+  a.n_kv_heads = c.n_kv_heads;
+  a.head_dim = c.head_dim;
+  a.n_requests = plan->n_requests;
+  a.n_splits = n_splits;
+  a.keys_per_split = keys_per_split;
+  a.max_ctx = max_ctx;
+  MPIC_HIP(ctx, mpic::launch_decode(c.dtype, a, stream));
   return MPIC_OK;
 }

@@ -60,6 +60,9 @@ struct mpic_ctx {
   bool ev_done_valid[2] = {false, false};
   int next_staging = 0;
   std::vector<hipEvent_t> ev_copy;             // one per transfer group
+  // partial results of the decode step (one per key split), grown on demand
+  void* decode_ws = nullptr;
+  size_t decode_ws_bytes = 0;
 };
 
 struct mpic_plan {
@@ -144,6 +147,28 @@ struct AttnArgs {
   int32_t interleaved;
 };
 hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t stream);
+
+// Keys of a decode split are a multiple of this (four wavefronts x 32-key blocks).
+constexpr int kDecodeBlockKeys = 128;
+struct DecodeArgs {
+  const int32_t* ctx_off;
+  const int32_t* dst_slot;
+  const uint32_t* kv_off16;
+  const void* q;
+  const void* new_k;  // null: the new token does not attend to itself
+  const void* new_v;
+  const void* k_ctx;
+  const void* v_ctx;
+  void* out;
+  float* lse;
+  float* ws_o;    // [B][Hq][n_splits][D] normalised partial outputs
+  float* ws_lse;  // [B][Hq][n_splits] their log-sum-exp
+  float scale;
+  int32_t n_q_heads, n_kv_heads, head_dim, n_requests;
+  int32_t n_splits, keys_per_split;
+  int32_t max_ctx;  // longest context of the batch
+};
+hipError_t launch_decode(int dtype, const DecodeArgs& a, hipStream_t stream);
 hipError_t launch_attn_f32(const AttnArgs& a, int64_t n_q, hipStream_t stream);
 
 }  // namespace mpic

@@ -6,7 +6,7 @@ import torch
 
 import workloads
 import paper_2502_01960_amd as mpic
-from oracle import attend, build_plan, link_kv, position_fresh
+from oracle import attend, build_plan, decode_attend, link_kv, position_fresh
 
 
 class Problem:
@@ -85,6 +85,27 @@ class Problem:
     def gpu_attend(self, lse=True):
         mpic.mpic_selective_attn(self.ctx.handle, self.plan.handle, self.d_q, self.k_ctx, self.v_ctx,
                                  self.sh.softmax_scale, self.out, self.lse if lse else None)
+
+    # ---- decode step after the prefill --------------------------------------
+    def decode_inputs(self):
+        """Seeded query, key and value of the next token of every request (storage dtype)."""
+        n_req = len(self.requests)
+        rows = [workloads.gen_fresh(self.sh, self.layer + 1000, b, 1) for b in range(n_req)]
+        return (torch.cat([r[0] for r in rows]), torch.cat([r[1] for r in rows]), torch.cat([r[2] for r in rows]))
+
+    def gpu_decode(self, q, new_k, new_v, lse=True):
+        dev = self.k_ctx.device
+        out = torch.full(tuple(q.shape), float("nan"), dtype=self.sh.torch_dtype, device=dev)
+        l = torch.full(tuple(q.shape[:2]), float("nan"), dtype=torch.float32, device=dev) if lse else None
+        mpic.mpic_decode_attn(self.ctx.handle, self.plan.handle, q.to(dev),
+                              None if new_k is None else new_k.to(dev), None if new_v is None else new_v.to(dev),
+                              self.k_ctx, self.v_ctx, self.sh.softmax_scale, out, l)
+        torch.cuda.synchronize()
+        return out.to(torch.float64).cpu().numpy(), (l.to(torch.float64).cpu().numpy() if lse else None)
+
+    def oracle_decode(self, K, V, q, new_k, new_v):
+        f64 = lambda t: None if t is None else t.to(torch.float64).numpy()
+        return decode_attend(f64(q), K, V, self.oplan, self.sh.softmax_scale, f64(new_k), f64(new_v))
 
     def gpu_logical_kv(self):
         """Context rows in logical order (request after request), float64 numpy."""

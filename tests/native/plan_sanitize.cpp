@@ -13,6 +13,7 @@ namespace mpic {
 hipError_t launch_assemble(int, const AssembleArgs&, const AssembleSrcTable&, hipStream_t) { return hipSuccess; }
 hipError_t launch_attn_bf16(const AttnArgs&, hipStream_t) { return hipSuccess; }
 hipError_t launch_attn_f32(const AttnArgs&, int64_t, hipStream_t) { return hipSuccess; }
+hipError_t launch_decode(int, const DecodeArgs&, hipStream_t) { return hipSuccess; }
 }  // namespace mpic
 
 #define CHECK(c) do { if (!(c)) { std::fprintf(stderr, "check failed: %s (line %d)\n", #c, __LINE__); return 1; } } while (0)
@@ -99,6 +100,7 @@ int main() {
     // argument checks that fail before any GPU call
     CHECK(mpic_assemble_kv(ctx, plan, nullptr, 0, nullptr, nullptr, static_cast<int64_t>(n_q) + 1, nullptr, nullptr, 0, nullptr) == MPIC_ERR_INVALID);
     CHECK(mpic_selective_attn(ctx, plan, nullptr, static_cast<int64_t>(n_q) + 1, nullptr, nullptr, 0, 1.0, nullptr, nullptr, nullptr) == MPIC_ERR_INVALID);
+    CHECK(mpic_decode_attn(ctx, plan, nullptr, nullptr, nullptr, nullptr, nullptr, 0, 1.0, nullptr, nullptr, nullptr) == MPIC_ERR_INVALID);
     CHECK(mpic_plan_get(plan, 99, &p, &n) == MPIC_ERR_INVALID);
     if (sum == 42) std::puts("");
     mpic_plan_destroy(plan);

@@ -310,3 +310,84 @@ def test_linking_in_two_parts_equals_one_call():
         assert torch.equal(p.v_ctx.view(torch.int16), v_ref.view(torch.int16))
     with pytest.raises(mpic.MpicError):
         mpic.mpic_assemble_kv_parts(p.ctx.handle, p.plan.handle, p.srcs, p.d_fk, p.d_fv, p.k_ctx, p.v_ctx, 0)
+
+
+def _check_decode(p, with_self=True):
+    """Decode step over the context that p has linked on the GPU: oracle fed the oracle's
+    own linked context (end to end)."""
+    bf16 = p.sh.dtype == "bf16"
+    K_ref, V_ref = p.oracle_link()
+    q, nk, nv = p.decode_inputs()
+    if not with_self:
+        nk = nv = None
+    O, L = p.gpu_decode(q, nk, nv)
+    O_ref, L_ref = p.oracle_decode(K_ref, V_ref, q, nk, nv)
+    empty = np.isneginf(L_ref)
+    assert np.array_equal(np.isneginf(L), empty)
+    if bf16:
+        assert_bf16_close(O, O_ref, "decode output")
+        assert np.abs(L[~empty] - L_ref[~empty]).max(initial=0.0) < 2e-2
+    else:
+        assert_f32_close(O, O_ref, "decode output")
+        assert np.abs(L[~empty] - L_ref[~empty]).max(initial=0.0) <= 1e-5 * max(1.0, np.abs(L_ref[~empty]).max(initial=0.0))
+
+
+def test_decode_step_after_prefill():
+    """One query per request over the linked context (contiguous and paged, fp32 and bf16,
+    ragged lengths that end inside a 32-key block and inside a split), with and without
+    the new token's own key and value."""
+    cases = [Problem(1),
+             Problem(2, n_chunks=2, chunk_len=150, text_len=13),
+             Problem(3, n_chunks=3, chunk_len=301, text_len=37, batch=2),
+             Problem(4, k=16, n_chunks=4, chunk_len=160, text_len=70, batch=3),
+             Problem(5, n_chunks=5, chunk_len=203, text_len=21)]
+    for p in cases:
+        p.gpu_setup(False)
+        p.gpu_assemble()
+        _check_decode(p, True)
+        _check_decode(p, False)
+
+
+def test_decode_step_edge_cases():
+    # requests of very different lengths in one batch, one of them empty, one a single token
+    reqs = [[("text", 1)], [], [("chunk", 0, 700, None), ("text", 3)], [("chunk", 1, 33, 0)]]
+    for paged in (0, 16):
+        p = _custom(reqs, 2, [700, 33], 5, paged=paged)
+        p.gpu_setup(False)
+        p.gpu_assemble()
+        _check_decode(p, True)
+        _check_decode(p, False)     # the empty request has no key at all: zeros, lse = -inf
+    # head groupings: multi-head (1 column in use), a group of 7, a group wider than one tile
+    import dataclasses
+    for hq, hkv in [(4, 4), (7, 1), (80, 2)]:
+        p = _custom([[("text", 40), ("chunk", 0, 300, None), ("text", 9)], [("chunk", 0, 300, 2)]], 1, [300], 4)
+        p.sh = dataclasses.replace(p.sh, n_q_heads=hq, n_kv_heads=hkv)
+        p.chunks = {s: workloads.gen_chunk(p.sh, 0, s, 300) for s in p.chunks}
+        q_off = p.oplan["q_off"]
+        fresh = [workloads.gen_fresh(p.sh, 0, b, int(q_off[b + 1] - q_off[b])) for b in range(2)]
+        p.q = torch.cat([f[0] for f in fresh]); p.fresh_k = torch.cat([f[1] for f in fresh]); p.fresh_v = torch.cat([f[2] for f in fresh])
+        p.gpu_setup(False)
+        p.gpu_assemble()
+        _check_decode(p, True)
+    with pytest.raises(mpic.MpicError):
+        mpic.mpic_decode_attn(p.ctx.handle, p.plan.handle, p.d_q[:2], p.d_fk[:2], None, p.k_ctx, p.v_ctx, 1.0, p.out[:2])
+
+
+def test_rows_staged_past_a_request_end_are_linked_rows():
+    """Paged layout whose page 0 is in no table and holds NaN: the last key block of a request
+    is staged past the request's end, and what is staged there must never be an untouched
+    slot (zero weight times NaN would poison the output)."""
+    reqs = [[("text", 5), ("chunk", 0, 90, None), ("text", 6)]]      # 101 tokens: ends inside a page and a block
+    p = _custom(reqs, 1, [90], 4, paged=16)
+    tables = [np.asarray(t).copy() for t in p.page_tables]
+    used = set(np.concatenate(tables).tolist())
+    spare = next(i for i in range(1, p.n_pool_pages) if i not in used)
+    for t in tables:
+        t[t == 0] = spare
+    p.page_tables = tables
+    from oracle import build_plan
+    p.oplan = build_plan(reqs, 4, 16, tables)
+    assert 0 not in set(np.concatenate(tables).tolist())
+    _run_full(p, host_sourced=False)
+    assert torch.isnan(p.k_ctx[:16].float()).all()
+    _check_decode(p, True)
