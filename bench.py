@@ -178,6 +178,20 @@ def main():
     attn_ms = timed(attend, args.steps)
     asm_ms = timed(assemble, args.steps)
 
+    # ---- decode step right after the prefill (extra figure; HBM-bound) ----------
+    for l, s in enumerate(sets):
+        s["dec"] = [torch.cat([workloads.gen_fresh(sh, 1000 + l, b, 1)[i] for b in range(len(requests))]).to(dev)
+                    for i in range(3)]
+    dec_out = torch.empty_like(sets[0]["dec"][0])
+
+    def decode(s):
+        dq, dk, dv = s["dec"]
+        mpic.mpic_decode_attn(ctx.handle, plan.handle, dq, dk, dv, s["k_ctx"], s["v_ctx"],
+                              sh.softmax_scale, dec_out, None, stream)
+
+    decode(sets[0])
+    dec_ms = timed(decode, args.steps)
+
     if args.calibrate_copy:
         x = torch.zeros(256 * 1024 * 1024, dtype=torch.bfloat16, device=dev)
         y = torch.empty_like(x)
@@ -196,6 +210,9 @@ def main():
     attn_tflops = attn_flops / (attn_ms * 1e-3) / 1e12
     asm_gbs = asm_bytes / (asm_ms * 1e-3) / 1e9
     value = attn_flops / (ms_per_step * 1e-3) / 1e12
+    # decode step: every context row of K and V is read once
+    dec_bytes = 2.0 * n_ctx * row_bytes
+    dec_gbs = dec_bytes / (dec_ms * 1e-3) / 1e9
 
     # ---- host-sourced chunks (PCIe inclusive; never `value`) -------------------
     host = None
@@ -282,6 +299,8 @@ def main():
                       "pct_mfma_peak": round(100 * attn_tflops / PEAK_BF16_TFLOPS, 3), "flops": attn_flops},
         "assembly": {"ms": round(asm_ms, 5), "GBps": round(asm_gbs, 2), "pct_hbm_peak": round(100 * asm_gbs / PEAK_HBM_GBS, 3),
                      "bytes": asm_bytes},
+        "decode_step": {"ms": round(dec_ms, 5), "GBps": round(dec_gbs, 2), "pct_hbm_peak": round(100 * dec_gbs / PEAK_HBM_GBS, 3),
+                        "bytes": dec_bytes, "note": "one query per request over the linked context plus itself; two launches"},
         "plan_ms": round(plan_ms, 4),
         "first_layer_ms": round(first_layer_ms, 4),
         "host_sourced": host,

@@ -417,17 +417,21 @@ extern "C" int mpic_decode_attn(mpic_ctx* ctx, mpic_plan* plan, const void* q, c
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   int32_t max_ctx = 0;
   for (int b = 0; b < plan->n_requests; ++b) max_ctx = std::max(max_ctx, plan->ctx_off[b + 1] - plan->ctx_off[b]);
-  // Splits: enough workgroups to keep every compute unit streaming (a workgroup fills a
-  // compute unit's LDS, so about two rounds of them), each split a multiple of 128 keys.
+  // Splits: a workgroup fills a compute unit's LDS, so the keys are cut so that one round of
+  // workgroups covers the chip (fewer when the batch alone supplies that many); each split
+  // is a multiple of 128 keys.
   int32_t n_splits = 1, keys_per_split = std::max(max_ctx, 1);
   if (c.dtype == MPIC_BF16 && max_ctx > 0) {
-    constexpr int64_t kTargetWorkgroups = 512;
+#ifndef MPIC_DECODE_TARGET
+#define MPIC_DECODE_TARGET 256
+#endif
+    constexpr int64_t kTargetWorkgroups = MPIC_DECODE_TARGET;
     const int64_t lanes = static_cast<int64_t>(plan->n_requests) * c.n_kv_heads * ((ctx->group + 31) / 32);
     const int64_t want = std::max<int64_t>(1, kTargetWorkgroups / lanes);
     int64_t kps = (max_ctx + want - 1) / want;
     kps = (kps + mpic::kDecodeBlockKeys - 1) / mpic::kDecodeBlockKeys * mpic::kDecodeBlockKeys;
     keys_per_split = static_cast<int32_t>(kps);
-    n_splits = static_cast<int32_t>((max_ctx + kps - 1) / kps);
+    n_splits = static_cast<int32_t>((max_ctx + kps - 1) / kps);  // <= 256, the merge kernel holds up to 1024 weights
   }
   const size_t rows = static_cast<size_t>(plan->n_requests) * c.n_q_heads;
   const size_t need = rows * n_splits * (c.head_dim + 1) * sizeof(float);

@@ -29,18 +29,26 @@ typedef float f32x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x8_a4 __attribute__((ext_vector_type(8), aligned(4)));
 
+#ifndef MPIC_DECODE_WAVES
+#define MPIC_DECODE_WAVES 4
+#endif
+#ifndef MPIC_DECODE_STAGES
+#define MPIC_DECODE_STAGES 2
+#endif
 constexpr int D = 128;
-constexpr int WAVES = 4;
+constexpr int WAVES = MPIC_DECODE_WAVES;
+constexpr int THREADS = WAVES * 64;
 constexpr int BN = 32;                           // keys per wavefront block
 constexpr int ROW_BYTES = D * 2;
 constexpr int TILE_BYTES = BN * ROW_BYTES;       // one staged K (or V) block: 8 KB
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;      // K block followed by V block
-constexpr int STAGES = 2;
-constexpr int WAVE_LDS = STAGES * STAGE_BYTES;   // 32 KB per wavefront
-constexpr int LDS_BYTES = WAVES * WAVE_LDS;      // 128 KB
+constexpr int STAGES = MPIC_DECODE_STAGES;       // blocks in flight per wavefront: STAGES - 1
+constexpr int WAVE_LDS = STAGES * STAGE_BYTES;
+constexpr int LDS_BYTES = WAVES * WAVE_LDS;
 constexpr int LOADS_PER_BLOCK = 16;              // direct loads per wavefront and block
 constexpr float kSlack = 8.0f;                   // lazy-rescale threshold, log2 units
-static_assert(kDecodeBlockKeys == WAVES * BN, "split granularity and kernel shape must agree");
+static_assert(kDecodeBlockKeys % BN == 0, "a split is a whole number of key blocks");
+static_assert(LDS_BYTES <= 160 * 1024 && LOADS_PER_BLOCK * (STAGES - 1) <= 63, "LDS size / load counter range");
 static_assert(WAVES * 32 * D * 4 + 2 * WAVES * 32 * 4 <= LDS_BYTES, "merge area must fit the staging area");
 
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
@@ -56,10 +64,14 @@ __device__ inline void load_to_lds_16B(const void* gptr, uint32_t lds_addr) {
 // s_waitcnt vmcnt(n) only (expcnt / lgkmcnt fields left at "no wait").  The builtin rather
 // than inline assembly: the compiler's own wait insertion sees it and adds nothing on top.
 #define WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
-// wait until at most one block's loads (or none) are outstanding; the empty asm keeps the
+// wait until at most `blocks` blocks of loads are outstanding; the empty asm keeps the
 // compiler from moving an LDS read above the wait
-__device__ inline void wait_loads(bool next_in_flight) {
-  if (next_in_flight) {
+__device__ inline void wait_loads(int blocks) {
+  if (blocks >= 3) {
+    WAIT_VMCNT(48);
+  } else if (blocks == 2) {
+    WAIT_VMCNT(32);
+  } else if (blocks == 1) {
     WAIT_VMCNT(16);
   } else {
     WAIT_VMCNT(0);
@@ -68,7 +80,7 @@ __device__ inline void wait_loads(bool next_in_flight) {
 }
 static_assert(LOADS_PER_BLOCK == 16, "wait_loads spells the count out");
 
-__global__ __launch_bounds__(WAVES * 64) void decode_bf16_kernel(DecodeArgs a) {
+__global__ __launch_bounds__(THREADS) void decode_bf16_kernel(DecodeArgs a) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -154,21 +166,29 @@ __global__ __launch_bounds__(WAVES * 64) void decode_bf16_kernel(DecodeArgs a) {
   WAIT_VMCNT(0);
   __builtin_amdgcn_sched_barrier(0);
 
-  // row offsets are fetched (scalar loads) one block ahead of the loads that use them
-  int blk = wave;
-  Rows rows = fetch_rows(blk);
-  if (blk < n_blk) {
-    issue_loads(rows, 0);
-    rows = fetch_rows(blk + WAVES);
-  }
-  int stage = 0;
-  for (; blk < n_blk; blk += WAVES, stage ^= 1) {
-    const bool more = blk + WAVES < n_blk;
-    if (more) {
-      issue_loads(rows, stage ^ 1);
-      rows = fetch_rows(blk + 2 * WAVES);
+  // Software pipeline: the loads of the next STAGES-1 blocks of this wavefront are in
+  // flight while one block is consumed; row offsets (scalar loads) are fetched one block
+  // ahead of the loads that use them.
+  const int first = wave;
+  const int my_blocks = first < n_blk ? (n_blk - first + WAVES - 1) / WAVES : 0;
+  Rows rows = fetch_rows(first);
+  int issued = 0;
+#pragma unroll
+  for (int i = 0; i < STAGES - 1; ++i)
+    if (issued < my_blocks) {
+      issue_loads(rows, issued % STAGES);
+      ++issued;
+      rows = fetch_rows(first + issued * WAVES);
     }
-    wait_loads(more);
+  for (int it = 0; it < my_blocks; ++it) {
+    const int blk = first + it * WAVES;
+    const int stage = it % STAGES;
+    if (issued < my_blocks) {
+      issue_loads(rows, issued % STAGES);
+      ++issued;
+      rows = fetch_rows(first + issued * WAVES);
+    }
+    wait_loads(issued - it - 1);
     const char* st = my_lds + stage * STAGE_BYTES;
 
     // S^T = K . Q^T for 32 keys x 32 query columns
@@ -247,10 +267,10 @@ __global__ __launch_bounds__(WAVES * 64) void decode_bf16_kernel(DecodeArgs a) {
   }
   __syncthreads();
   {
-    const int c = tid >> 3;        // column handled by this thread
-    const int d0 = (tid & 7) * 16; // its 16 output coordinates
-    const int hg = cb * 32 + c;
-    if (hg < group) {
+    const int d0 = (tid & 7) * 16;  // this thread's 16 output coordinates
+    for (int c = tid >> 3; c < 32; c += THREADS / 8) {  // of these columns
+      const int hg = cb * 32 + c;
+      if (hg >= group) break;
       float m_tot = -INFINITY;
 #pragma unroll
       for (int w = 0; w < WAVES; ++w) m_tot = fmaxf(m_tot, m_m[w * 32 + c]);
@@ -278,10 +298,16 @@ __global__ __launch_bounds__(WAVES * 64) void decode_bf16_kernel(DecodeArgs a) {
 }
 
 // Merge the splits of one (request, query head) and the new token itself; one thread per
-// output coordinate.
+// output coordinate.  The partials were written by other compute units, so every read
+// here goes to memory: the split weights are computed once by the first wavefront (one
+// split per lane) and the partial outputs are fetched eight at a time before they are
+// used, so that the latencies overlap instead of adding up.
 template <typename T, int kD>
 __global__ __launch_bounds__(kD) void decode_merge_kernel(DecodeArgs a) {
+  constexpr int kMaxSplits = 1024;
   __shared__ float red[kD / 64];
+  __shared__ float wgt[kMaxSplits];
+  __shared__ float stat[2];  // reference maximum, denominator
   const int d = threadIdx.x;
   const int64_t row = blockIdx.x;  // b * Hq + h
   const int b = static_cast<int>(row / a.n_q_heads);
@@ -289,8 +315,6 @@ __global__ __launch_bounds__(kD) void decode_merge_kernel(DecodeArgs a) {
   const int g = h / (a.n_q_heads / a.n_kv_heads);
   const int n_ctx = a.ctx_off[b + 1] - a.ctx_off[b];
   const int n_s = (n_ctx + a.keys_per_split - 1) / a.keys_per_split;
-  float m = -INFINITY;
-  for (int s = 0; s < n_s; ++s) m = fmaxf(m, a.ws_lse[row * a.n_splits + s]);
   float self = -INFINITY;
   float v_new = 0.f;
   if (a.new_k) {
@@ -300,21 +324,51 @@ __global__ __launch_bounds__(kD) void decode_merge_kernel(DecodeArgs a) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off);
     if ((d & 63) == 0) red[d >> 6] = part;
-    __syncthreads();
+    v_new = static_cast<float>(static_cast<const T*>(a.new_v)[kv]);
+  }
+  __syncthreads();
+  if (a.new_k) {
     float dot = 0.f;
 #pragma unroll
     for (int i = 0; i < kD / 64; ++i) dot += red[i];
     self = dot * a.scale;
-    v_new = static_cast<float>(static_cast<const T*>(a.new_v)[kv]);
-    m = fmaxf(m, self);
   }
-  float z = 0.f, o = 0.f;
-  if (m != -INFINITY) {
-    for (int s = 0; s < n_s; ++s) {
-      const float w = expf(a.ws_lse[row * a.n_splits + s] - m);
-      z += w;
-      o = fmaf(w, a.ws_o[(row * a.n_splits + s) * kD + d], o);
+  if (d < 64) {
+    // lane l owns splits l, l + 64, ...
+    float m = self;
+    for (int s = d; s < n_s; s += 64) m = fmaxf(m, a.ws_lse[row * a.n_splits + s]);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+    float z = 0.f;
+    if (m != -INFINITY) {
+      for (int s = d; s < n_s; s += 64) {
+        const float w = expf(a.ws_lse[row * a.n_splits + s] - m);
+        wgt[s] = w;
+        z += w;
+      }
     }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) z += __shfl_xor(z, off);
+    if (d == 0) {
+      stat[0] = m;
+      stat[1] = z;
+    }
+  }
+  __syncthreads();
+  const float m = stat[0];
+  float z = stat[1];
+  float o = 0.f;
+  if (m != -INFINITY) {
+    const float* po = a.ws_o + row * a.n_splits * kD + d;
+    int s = 0;
+    for (; s + 8 <= n_s; s += 8) {
+      float x[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) x[i] = po[static_cast<int64_t>(s + i) * kD];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) o = fmaf(wgt[s + i], x[i], o);
+    }
+    for (; s < n_s; ++s) o = fmaf(wgt[s], po[static_cast<int64_t>(s) * kD], o);
     if (a.new_k) {
       const float w = expf(self - m);
       z += w;
@@ -425,7 +479,7 @@ hipError_t launch_decode(int dtype, const DecodeArgs& a, hipStream_t stream) {
   }
   const int group = a.n_q_heads / a.n_kv_heads;
   const dim3 grid(a.n_splits, a.n_kv_heads * ((group + 31) / 32), a.n_requests);
-  if (a.max_ctx > 0) hipLaunchKernelGGL(decode_bf16_kernel, grid, dim3(WAVES * 64), LDS_BYTES, stream, a);
+  if (a.max_ctx > 0) hipLaunchKernelGGL(decode_bf16_kernel, grid, dim3(THREADS), LDS_BYTES, stream, a);
   hipLaunchKernelGGL((decode_merge_kernel<__bf16, 128>), dim3(static_cast<unsigned>(rows)), dim3(128), 0, stream, a);
   return hipGetLastError();
 }
