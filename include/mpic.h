@@ -100,8 +100,12 @@ enum {
   MPIC_PLAN_INST_REQ = 12,   /* [n_inst] owning request                                        */
   MPIC_PLAN_RUNS = 13,       /* [n_runs][4] (request, first fresh row, length, first position) */
   MPIC_PLAN_ATTN_TILES = 14  /* [n_tiles][8] launch order of the attention kernel: (request,   */
-                             /* kv head, first flattened row, rows, keys, 0, 0, 0); flattened  */
-                             /* row = (fresh row - q_off[request]) * (Hq/Hkv) + head in group  */
+                             /* kv head, first flattened row, rows, end key, first key, slot   */
+                             /* of the partial result or -1, 0); flattened row = (fresh row -  */
+                             /* q_off[request]) * (Hq/Hkv) + head in group.  A tile visits     */
+                             /* keys first..end-1; tiles whose first key is > 0 or whose slot  */
+                             /* is >= 0 are pieces of one tile cut along the keys, merged by a */
+                             /* second kernel                                                  */
 };
 
 /*
@@ -235,7 +239,11 @@ int mpic_assemble_kv_parts(mpic_ctx* ctx, mpic_plan* plan, const mpic_chunk_src*
  *   out               device [n_fresh_rows][Hq][D], written
  *   lse               device float [n_fresh_rows][Hq], written; may be NULL
  * A plan with no fresh row is a no-op that returns MPIC_OK.
- * Errors: MPIC_ERR_INVALID, MPIC_ERR_HIP.
+ * Small and medium batches are cut along the keys as well as along the rows (see
+ * MPIC_PLAN_ATTN_TILES); the partial results live in a workspace owned by the context,
+ * allocated on first use and grown (with a device synchronisation) when a later call needs
+ * more, so calls of one context that use it must not overlap on different streams.
+ * Errors: MPIC_ERR_INVALID, MPIC_ERR_OOM (workspace), MPIC_ERR_HIP.
  */
 int mpic_selective_attn(mpic_ctx* ctx, mpic_plan* plan, const void* fresh_q, int64_t n_fresh_rows,
                         const void* k_ctx, const void* v_ctx, int64_t n_ctx_slots,

@@ -40,7 +40,8 @@ int upload_plan(mpic_ctx* ctx, mpic_plan* p) {
   const size_t n = p->n_ctx, nq = p->n_q, B = p->n_requests;
   size_t total = 3 * padded<int32_t>(n) + padded<int32_t>(n + kTablePad) + padded<int32_t>(nq) + padded<int32_t>(nq) + 2 * padded<int32_t>(B + 1) +
                  2 * padded<float>(p->rope_cos.size()) + padded<AttnTile>(p->tiles.size()) + 256 +
-                 padded<int32_t>(p->fresh_rot.size()) + 2 * padded<float>(p->fresh_cos.size());
+                 padded<int32_t>(p->fresh_rot.size()) + 2 * padded<float>(p->fresh_cos.size()) +
+                 padded<AttnMerge>(p->merges.size());
   char* base = nullptr;
   hipError_t e = hipMalloc(reinterpret_cast<void**>(&base), total);
   if (e != hipSuccess) {
@@ -97,6 +98,9 @@ int upload_plan(mpic_ctx* ctx, mpic_plan* p) {
   if (e == hipSuccess)
     d.tiles = static_cast<AttnTile*>(put(p->tiles.data(), p->tiles.size() * sizeof(AttnTile),
                                          padded<AttnTile>(p->tiles.size())));
+  if (e == hipSuccess)
+    d.merges = static_cast<AttnMerge*>(put(p->merges.data(), p->merges.size() * sizeof(AttnMerge),
+                                           padded<AttnMerge>(p->merges.size())));
   if (e != hipSuccess) {
     (void)hipFree(base);
     return fail_hip(ctx, e, "upload of the plan");
@@ -130,6 +134,7 @@ extern "C" void mpic_destroy(mpic_ctx* ctx) {
     for (void* buf : ctx->staging)
       if (buf) (void)hipFree(buf);
     if (ctx->decode_ws) (void)hipFree(ctx->decode_ws);
+    if (ctx->attn_ws) (void)hipFree(ctx->attn_ws);
     if (cur >= 0) (void)hipSetDevice(cur);
   }
   delete ctx;
@@ -382,6 +387,26 @@ extern "C" int mpic_selective_attn(mpic_ctx* ctx, mpic_plan* plan, const void* f
   a.n_kv_heads = c.n_kv_heads;
   a.head_dim = c.head_dim;
   a.n_requests = plan->n_requests;
+  if (c.dtype == MPIC_BF16 && plan->n_parts > 0) {
+    const size_t slots = static_cast<size_t>(plan->n_parts) * mpic::kAttnTileRows;
+    const size_t need = slots * (c.head_dim + 1) * sizeof(float);
+    if (need > ctx->attn_ws_bytes) {
+      // growing the workspace is rare (first call / larger batch): drain what may still read it
+      MPIC_HIP(ctx, hipDeviceSynchronize());
+      if (ctx->attn_ws) MPIC_HIP(ctx, hipFree(ctx->attn_ws));
+      ctx->attn_ws = nullptr;
+      ctx->attn_ws_bytes = 0;
+      if (hipMalloc(&ctx->attn_ws, need) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(ctx, MPIC_ERR_OOM, "selective_attn: workspace allocation failed");
+      }
+      ctx->attn_ws_bytes = need;
+    }
+    a.ws_o = static_cast<float*>(ctx->attn_ws);
+    a.ws_lse = a.ws_o + slots * c.head_dim;
+    a.merges = plan->dev.merges;
+    a.n_merges = static_cast<int32_t>(plan->merges.size());
+  }
   a.q_rot = plan->dev.fresh_rot;
   a.q_cos = plan->dev.fresh_cos;
   a.q_sin = plan->dev.fresh_sin;

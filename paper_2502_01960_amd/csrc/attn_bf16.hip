@@ -108,11 +108,12 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a) {
   const int hi = lane >> 5;   // which half of the contraction index this lane feeds
   const int group = a.n_q_heads / a.n_kv_heads;
   const int b = tile.req, g = tile.kv_head;
-  const int n_keys = tile.n_keys;
+  const int key0 = tile.key0;              // pieces of a tile cut along the keys start here;
+  const int n_keys = tile.n_keys - key0;   // from here on keys and positions are relative to it
   // context row offsets in 16-byte units; read with scalar loads (the table is padded so
   // that reading up to 64 entries past the last key of the tile stays in bounds)
   const __attribute__((address_space(4))) uint32_t* off_of =
-      (const __attribute__((address_space(4))) uint32_t*)(a.kv_off16 + a.ctx_off[b]);
+      (const __attribute__((address_space(4))) uint32_t*)(a.kv_off16 + a.ctx_off[b] + key0);
   const char* kbase = static_cast<const char*>(a.k_ctx) + g * ROW_BYTES;
   const char* vbase = static_cast<const char*>(a.v_ctx) + g * ROW_BYTES;
   const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(LDS_PTR(char, lds)));
@@ -123,7 +124,8 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a) {
   const int flat = tile.row0 + (valid ? local : 0);
   const int64_t fresh_row = a.q_off[b] + flat / group;
   const int head = g * group + flat % group;
-  const int my_pos = valid ? a.q_pos[fresh_row] : 0x7fffffff;  // padding columns see every key
+  // padding columns see every key; a row below key0 (negative here) sees none of this piece
+  const int my_pos = valid ? a.q_pos[fresh_row] - key0 : 0x7fffffff;
   const __bf16* qp = static_cast<const __bf16*>(a.q) + (fresh_row * a.n_q_heads + head) * D;
   bf16x8 qf[8];
 #pragma unroll
@@ -164,7 +166,7 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a) {
   }
 
   const float posf = static_cast<float>(valid ? my_pos : -1);
-  const int wave_hi_pos = static_cast<int>(wave_max(posf));  // -1: idle wave
+  const int wave_hi_pos = static_cast<int>(wave_max(posf));  // negative: idle wave
   const int wave_lo_pos = static_cast<int>(wave_min(valid ? posf : 3.0e9f));
 
   const float scale_log2 = a.scale * 1.4426950408889634f;
@@ -397,6 +399,26 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a) {
   // ---- epilogue: normalise and store this lane's query column ----
   if (!valid) return;
   const float l_tot = l_run + __shfl_xor(l_run, 32);
+  if (tile.part >= 0) {
+    // piece of a tile cut along the keys: normalised fp32 partial + log-sum-exp for the merge
+    // kernel.  A row that lies below key0 saw no key (its registers may hold NaN: selected
+    // away, never multiplied).
+    const bool seen = my_pos >= 0;
+    const float inv_p = seen ? 1.f / l_tot : 0.f;
+    const int64_t slot = static_cast<int64_t>(tile.part) * kAttnTileRows + local;
+    float* po = a.ws_o + slot * D;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        f32x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = seen ? acc_o[db][q4 * 4 + e] * inv_p : 0.f;
+        *reinterpret_cast<f32x4*>(po + db * 32 + q4 * 8 + hi * 4) = o;
+      }
+    if (hi == 0) a.ws_lse[slot] = seen ? m_run * a.scale + logf(l_tot) : -INFINITY;
+    return;
+  }
   const float inv = 1.f / l_tot;
   __bf16* op = static_cast<__bf16*>(a.out) + (fresh_row * a.n_q_heads + head) * D;
 #pragma unroll
@@ -412,6 +434,51 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a) {
   if (a.lse && hi == 0)
     a.lse[fresh_row * a.n_q_heads + head] = m_run * a.scale + logf(l_tot);
 #endif
+}
+
+
+// Merge the pieces of tiles that were cut along the keys: one workgroup per 8 rows of a
+// cut tile, a thread per four output coordinates of one row.  Every read misses (other
+// compute units wrote the partials), so the pieces are fetched four at a time before they
+// are combined, with a running reference maximum (one pass).
+__global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
+  const AttnMerge m = a.merges[blockIdx.x];
+  const int local = blockIdx.y * 8 + (threadIdx.x >> 5);
+  if (local >= m.n_rows) return;
+  const int group = a.n_q_heads / a.n_kv_heads;
+  const int d = (threadIdx.x & 31) * 4;
+  const int flat = m.row0 + local;
+  const int64_t fresh_row = a.q_off[m.req] + flat / group;
+  const int head = m.kv_head * group + flat % group;
+  const int64_t slot0 = static_cast<int64_t>(m.first_part) * kAttnTileRows + local;
+  // the first piece starts at key 0, which every row sees: the maximum is finite from the
+  // first piece on; later pieces a row did not reach carry -inf and weigh nothing
+  float mx = -INFINITY, z = 0.f;
+  f32x4 o = f32x4{0};
+  for (int p0 = 0; p0 < m.n_parts; p0 += 4) {
+    float lse[4];
+    f32x4 x[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int64_t slot = slot0 + static_cast<int64_t>(min(p0 + i, m.n_parts - 1)) * kAttnTileRows;
+      lse[i] = p0 + i < m.n_parts ? a.ws_lse[slot] : -INFINITY;
+      x[i] = *reinterpret_cast<const f32x4*>(a.ws_o + slot * D + d);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (lse[i] == -INFINITY) continue;
+      const float m_new = fmaxf(mx, lse[i]);
+      const float keep = expf(mx - m_new);  // first piece: exp(-inf) = 0
+      const float w = expf(lse[i] - m_new);
+      z = z * keep + w;
+      o = o * keep + w * x[i];
+      mx = m_new;
+    }
+  }
+  o *= 1.f / z;
+  *reinterpret_cast<bf16x4*>(static_cast<__bf16*>(a.out) + (fresh_row * a.n_q_heads + head) * D + d) =
+      __builtin_convertvector(o, bf16x4);
+  if (a.lse && d == 0) a.lse[fresh_row * a.n_q_heads + head] = mx + logf(z);
 }
 
 }  // namespace
@@ -430,6 +497,8 @@ hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t stream) {
     opted_in[dev] = true;
   }
   hipLaunchKernelGGL(attn_bf16_kernel, dim3(a.n_tiles), dim3(THREADS), LDS_BYTES, stream, a);
+  if (a.n_merges > 0)
+    hipLaunchKernelGGL(attn_merge_kernel, dim3(a.n_merges, kAttnTileRows / 8), dim3(256), 0, stream, a);
   return hipGetLastError();
 }
 

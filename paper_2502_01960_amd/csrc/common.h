@@ -17,10 +17,20 @@ struct AttnTile {
   int32_t kv_head;  // key/value head g
   int32_t row0;     // first flattened row: (fresh row - q_off[b]) * G + head-in-group
   int32_t n_rows;   // rows in this tile (0 = padding entry, the workgroup exits)
-  int32_t n_keys;   // keys 0..n_keys-1 are visited (= largest position in the tile + 1)
-  int32_t pad[3];
+  int32_t n_keys;   // keys key0..n_keys-1 are visited (at most the largest position in the tile + 1)
+  int32_t key0;     // first key (a multiple of 64); > 0 only for pieces of a tile cut along the keys
+  int32_t part;     // -1: the tile writes the output; >= 0: slot of its partial result
+  int32_t pad;
 };
 static_assert(sizeof(AttnTile) == 32, "tile layout is part of the ABI");
+
+// Rows whose keys were cut into several tiles: their partial results are merged afterwards.
+struct AttnMerge {
+  int32_t req, kv_head, row0, n_rows;
+  int32_t first_part, n_parts;  // partial slots first_part .. first_part + n_parts - 1, in key order
+  int32_t pad[2];
+};
+static_assert(sizeof(AttnMerge) == 32, "merge item layout");
 
 // Device-resident copy of a plan.
 struct PlanDevice {
@@ -38,6 +48,7 @@ struct PlanDevice {
   float* fresh_cos = nullptr;
   float* fresh_sin = nullptr;
   AttnTile* tiles = nullptr;
+  AttnMerge* merges = nullptr;
   void* block = nullptr;  // the single allocation all of the above point into
   int device = -1;
 };
@@ -63,6 +74,9 @@ struct mpic_ctx {
   // partial results of the decode step (one per key split), grown on demand
   void* decode_ws = nullptr;
   size_t decode_ws_bytes = 0;
+  // partial results of prefill tiles that were cut along the keys, grown on demand
+  void* attn_ws = nullptr;
+  size_t attn_ws_bytes = 0;
 };
 
 struct mpic_plan {
@@ -75,6 +89,8 @@ struct mpic_plan {
   std::vector<int32_t> ctx_off, q_off, q_pos, q_req, slot_map, src_inst, src_row, dst_slot;
   std::vector<int32_t> inst_src, inst_delta, inst_len, inst_k, inst_req, runs;
   std::vector<mpic::AttnTile> tiles;
+  std::vector<mpic::AttnMerge> merges;  // tiles cut along the keys
+  int32_t n_parts = 0;                  // partial-result slots those tiles use
   std::vector<float> rope_cos, rope_sin;
   std::vector<int32_t> fresh_rot;            // contexts with fresh_pre_rope only
   std::vector<float> fresh_cos, fresh_sin;   // one row per distinct position id
@@ -141,6 +157,10 @@ struct AttnArgs {
   float scale;
   int32_t n_q_heads, n_kv_heads, head_dim;
   int32_t n_requests;
+  float* ws_o;    // [n_parts][kAttnTileRows][D] normalised partial outputs of cut tiles
+  float* ws_lse;  // [n_parts][kAttnTileRows] their log-sum-exp (-inf: the row saw no key of the piece)
+  const AttnMerge* merges;
+  int32_t n_merges;
   const int32_t* q_rot;  // non-null: queries are rotated with row q_rot[r] of q_cos / q_sin on load
   const float* q_cos;
   const float* q_sin;

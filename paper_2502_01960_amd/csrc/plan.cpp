@@ -28,6 +28,9 @@ int fail_hip(mpic_ctx* ctx, hipError_t e, const char* what) {
 
 namespace {
 
+#ifndef MPIC_SPLIT_ROUNDS
+#define MPIC_SPLIT_ROUNDS 2
+#endif
 constexpr int kXcds = 8;  // L2 domains of the chip; workgroup i is dispatched to domain i % 8
 constexpr int kComputeUnits = 256;
 
@@ -38,50 +41,118 @@ constexpr int kComputeUnits = 256;
 // are cut every kAttnTileRows rows regardless of run boundaries: the kernel masks per
 // row and every wavefront stops at the last key its own rows can see, so a tile that
 // straddles two runs costs no more than its parts while full tiles keep the K/V
-// stream per flop low.  Launch order: tiles that read the same K/V (same request and
-// kv head) are dealt to the same L2 domain, and inside a domain the longest tiles come
-// first so the tail of the launch is made of short work.
+// stream per flop low.
+//
+// Small and medium problems do not have a tile per compute unit, or only a few, very
+// unequal ones (a tile's work grows with the position of its rows).  Such tiles are also
+// cut along the keys: every piece visits a range of 64-key blocks and leaves a partial
+// result (normalised output + log-sum-exp) that a merge kernel combines.  The piece size
+// is chosen so that the pieces make kSplitRounds rounds over the chip at most -- one round
+// when the whole problem is only a few blocks per compute unit -- and never less than
+// kMinPieceBlocks blocks (the fixed cost of a workgroup is about one and a half blocks).
+// Large problems (more blocks per compute unit than the longest tile has) are not cut.
+//
+// Launch order: tiles that read the same K/V (same request and kv head) are dealt to the
+// same L2 domain, and inside a domain the longest tiles come first so the tail of the
+// launch is made of short work.
 void build_tiles(mpic_plan& p, int group, int n_kv_heads) {
   struct Item {
     AttnTile t;
     int64_t cost;
   };
+  constexpr int64_t kBlock = 64;          // keys per block of the attention kernel
+  constexpr int64_t kMinPieceBlocks = 4;
+  constexpr int64_t kSplitRounds = MPIC_SPLIT_ROUNDS;
   const int B = p.n_requests;
   const int n_combo = B * n_kv_heads;
   std::vector<std::vector<Item>> per_combo(n_combo);
-  // Small problems: full tiles would leave most of the chip idle, so the tile height is
-  // halved (down to two wavefronts' worth of rows) until there is a tile per compute unit.
+  auto last_pos = [&](int b, int64_t row_end) {  // position of the last fresh row below flattened row `row_end`
+    return static_cast<int64_t>(p.q_pos[p.q_off[b] + (row_end - 1) / group]);
+  };
+  // Tile height: full tiles unless even pieces of the smallest size would leave compute
+  // units without work; then the height is halved (down to two wavefronts' worth of rows).
   int64_t tile_rows = kAttnTileRows;
-  auto count_tiles = [&](int64_t h) {
+  auto count_pieces = [&](int64_t h, int64_t* total_blocks) {
+    int64_t n = 0, tot = 0;
+    for (int b = 0; b < B; ++b) {
+      const int64_t rows = static_cast<int64_t>(p.q_off[b + 1] - p.q_off[b]) * group;
+      for (int64_t row = 0; row < rows; row += h) {
+        const int64_t blocks = (last_pos(b, std::min(rows, row + h)) + 1 + kBlock - 1) / kBlock;
+        n += (blocks + kMinPieceBlocks - 1) / kMinPieceBlocks * n_kv_heads;
+        tot += blocks * n_kv_heads;
+      }
+    }
+    if (total_blocks) *total_blocks = tot;
+    return n;
+  };
+  while (tile_rows > 64 && count_pieces(tile_rows, nullptr) < kComputeUnits) tile_rows /= 2;
+  int64_t total_blocks = 0;
+  count_pieces(tile_rows, &total_blocks);
+  const int64_t per_cu = (total_blocks + kComputeUnits - 1) / kComputeUnits;
+  const int64_t rounds = std::max<int64_t>(1, std::min<int64_t>(kSplitRounds, per_cu / 16));
+  const bool no_cut = kSplitRounds == 0;
+  int64_t cap = std::max<int64_t>(kMinPieceBlocks, (total_blocks + kComputeUnits * rounds - 1) / (kComputeUnits * rounds));
+  // rounding up per tile makes more pieces than total / cap: grow the cap until they fit the rounds
+  auto count_at_cap = [&](int64_t c) {
     int64_t n = 0;
     for (int b = 0; b < B; ++b) {
       const int64_t rows = static_cast<int64_t>(p.q_off[b + 1] - p.q_off[b]) * group;
-      n += (rows + h - 1) / h * n_kv_heads;
+      for (int64_t row = 0; row < rows; row += tile_rows) {
+        const int64_t blocks = (last_pos(b, std::min(rows, row + tile_rows)) + 1 + kBlock - 1) / kBlock;
+        n += (blocks + c - 1) / c * n_kv_heads;
+      }
     }
     return n;
   };
-  while (tile_rows > 64 && count_tiles(tile_rows) < kComputeUnits) tile_rows /= 2;
+  while (count_at_cap(cap) > kComputeUnits * rounds && cap < total_blocks) cap += std::max<int64_t>(1, cap / 16);
+  p.merges.clear();
+  p.n_parts = 0;
   for (int b = 0; b < B; ++b) {
     const int64_t rows = static_cast<int64_t>(p.q_off[b + 1] - p.q_off[b]) * group;
     for (int64_t row = 0; row < rows; row += tile_rows) {
       const int64_t n = std::min<int64_t>(tile_rows, rows - row);
-      // keys visited by the tile = position of its last row + 1; cost = keys summed over
-      // its wavefronts of 32 rows (each stops at its own last row)
-      int64_t cost = 64;
-      for (int64_t w = row; w < row + n; w += 32) {
-        const int64_t last = p.q_off[b] + (std::min(w + 32, row + n) - 1) / group;
-        cost += p.q_pos[last] + 1;
+      const int64_t n_keys = last_pos(b, row + n) + 1;
+      const int64_t blocks = (n_keys + kBlock - 1) / kBlock;
+      int64_t parts = (blocks > cap && !no_cut) ? (blocks + cap - 1) / cap : 1;
+      const int64_t per = (blocks + parts - 1) / parts;  // blocks per piece
+      parts = (blocks + per - 1) / per;
+      for (int64_t i = 0; i < parts; ++i) {
+        const int64_t key0 = i * per * kBlock;
+        const int64_t key1 = std::min<int64_t>(n_keys, (i + 1) * per * kBlock);
+        // cost = keys visited, summed over the wavefronts of 32 rows (each stops at its own last row)
+        int64_t cost = 64;
+        for (int64_t w = row; w < row + n; w += 32)
+          cost += std::max<int64_t>(0, std::min<int64_t>(last_pos(b, std::min(w + 32, row + n)) + 1, key1) - key0);
+        for (int g = 0; g < n_kv_heads; ++g) {
+          Item it{};
+          it.t.req = b;
+          it.t.kv_head = g;
+          it.t.row0 = static_cast<int32_t>(row);
+          it.t.n_rows = static_cast<int32_t>(n);
+          it.t.n_keys = static_cast<int32_t>(key1);
+          it.t.key0 = static_cast<int32_t>(key0);
+          it.t.part = -1 - static_cast<int32_t>(i);  // resolved below, once the merge item of (tile, g) exists
+          it.cost = cost;
+          per_combo[b * n_kv_heads + g].push_back(it);
+        }
       }
-      const int64_t last_fresh = p.q_off[b] + (row + n - 1) / group;
-      for (int g = 0; g < n_kv_heads; ++g) {
-        Item it{};
-        it.t.req = b;
-        it.t.kv_head = g;
-        it.t.row0 = static_cast<int32_t>(row);
-        it.t.n_rows = static_cast<int32_t>(n);
-        it.t.n_keys = p.q_pos[last_fresh] + 1;
-        it.cost = cost;
-        per_combo[b * n_kv_heads + g].push_back(it);
+      if (parts > 1) {
+        for (int g = 0; g < n_kv_heads; ++g) {
+          AttnMerge m{};
+          m.req = b;
+          m.kv_head = g;
+          m.row0 = static_cast<int32_t>(row);
+          m.n_rows = static_cast<int32_t>(n);
+          m.first_part = p.n_parts;
+          m.n_parts = static_cast<int32_t>(parts);
+          p.n_parts += static_cast<int32_t>(parts);
+          p.merges.push_back(m);
+          // the pieces of this (tile, g) were pushed last into their combo, in key order
+          auto& v = per_combo[b * n_kv_heads + g];
+          for (int64_t i = 0; i < parts; ++i) v[v.size() - parts + i].t.part = m.first_part + static_cast<int32_t>(i);
+        }
+      } else {
+        for (int g = 0; g < n_kv_heads; ++g) per_combo[b * n_kv_heads + g].back().t.part = -1;
       }
     }
   }

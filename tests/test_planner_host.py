@@ -48,21 +48,37 @@ def test_plan_matches_oracle_on_benchmark_layouts(cfg):
 
 
 def _check_tiles(plan, want, group, n_kv):
-    """Tiles cover every (fresh row, query head) exactly once, stay inside one request
-    and carry the key count of their last row."""
+    """Tiles cover every (fresh row, query head, visible key) exactly once: row ranges stay
+    inside one request; a tile cut along the keys comes as pieces whose key ranges are
+    64-aligned, contiguous from 0 to the key count of its last row, with distinct partial
+    slots; an uncut tile writes the output itself."""
     tiles = plan.get("attn_tiles")
     nq = len(want["q_pos"])
     seen = np.zeros((nq, n_kv * group), dtype=np.int32)
-    for (b, g, row0, n_rows, n_keys, *_rest) in tiles.tolist():
+    pieces = {}
+    for (b, g, row0, n_rows, key_end, key0, part, _pad) in tiles.tolist():
         if n_rows == 0:
             continue
         assert 0 < n_rows <= 256
+        pieces.setdefault((b, g, row0, n_rows), []).append((key0, key_end, part))
+    slots = []
+    for (b, g, row0, n_rows), parts in pieces.items():
         flat = np.arange(row0, row0 + n_rows)
         fresh = int(want["q_off"][b]) + flat // group
         assert fresh.max() < want["q_off"][b + 1]
-        assert n_keys == want["q_pos"][fresh].max() + 1
+        n_keys = int(want["q_pos"][fresh].max()) + 1
+        parts.sort()
+        assert parts[0][0] == 0 and parts[-1][1] == n_keys
+        for (k0, k1, part), nxt in zip(parts, parts[1:] + [None]):
+            assert k0 % 64 == 0 and k0 < k1
+            if nxt is not None:
+                assert k1 == nxt[0]
+            assert (part == -1) == (len(parts) == 1)
+            if part >= 0:
+                slots.append(part)
         seen[fresh, g * group + flat % group] += 1
     assert (seen == 1).all()
+    assert sorted(slots) == list(range(len(slots)))
 
 
 segment = st.one_of(
