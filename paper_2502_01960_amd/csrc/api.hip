@@ -4,6 +4,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <new>
 
 #include "common.h"
 
@@ -26,85 +27,83 @@ int bind_device(mpic_ctx* ctx) {
 
 constexpr size_t kTablePad = 128;
 
-template <typename T>
-size_t padded(size_t n) {
-  return (n * sizeof(T) + 255) / 256 * 256;
-}
-
-// Copy the integer maps, rotary tables and tile list to the GPU (once per plan).
+// Copy the integer maps, rotary tables and tile list to the GPU (once per plan): the tables
+// are packed into one host image that crosses the bus in a single copy into a single
+// allocation.  May throw std::bad_alloc (host image); the entry points catch it.
 int upload_plan(mpic_ctx* ctx, mpic_plan* p) {
   if (p->dev.block) {
     if (p->dev.device != ctx->device) return fail(ctx, MPIC_ERR_INVALID, "plan lives on another GPU");
     return MPIC_OK;
   }
   const size_t n = p->n_ctx, nq = p->n_q, B = p->n_requests;
-  size_t total = 3 * padded<int32_t>(n) + padded<int32_t>(n + kTablePad) + padded<int32_t>(nq) + padded<int32_t>(nq) + 2 * padded<int32_t>(B + 1) +
-                 2 * padded<float>(p->rope_cos.size()) + padded<AttnTile>(p->tiles.size()) + 256 +
-                 padded<int32_t>(p->fresh_rot.size()) + 2 * padded<float>(p->fresh_cos.size()) +
-                 padded<AttnMerge>(p->merges.size());
+  // byte offset of every context row in 16-byte units (saves the attention kernel a
+  // 64-bit multiply per staged row); fits 32 bits for context buffers below 64 GiB
+  const uint64_t units = static_cast<uint64_t>(ctx->cfg.n_kv_heads) * ctx->cfg.head_dim *
+                         (ctx->cfg.dtype == MPIC_F32 ? 4 : 2) / 16;
+  if (static_cast<uint64_t>(p->max_slot + 1) * units > 0xffffffffull)
+    return fail(ctx, MPIC_ERR_UNSUPPORTED, "context buffers of 64 GiB or more are not supported");
+  // kTablePad entries follow the table: the attention kernels fetch offsets eight at a
+  // time and may run up to one key block past the last key of a tile.  They repeat the
+  // last row of the batch, so that what is staged beyond a request's end is always a
+  // linked row (its weight is zero, but 0 x NaN from an untouched slot would not be)
+  std::vector<uint32_t> off(n + kTablePad, 0u);
+  for (size_t i = 0; i < n; ++i) off[i] = static_cast<uint32_t>(static_cast<uint64_t>(p->dst_slot[i]) * units);
+  for (size_t i = n; i < off.size() && n > 0; ++i) off[i] = off[n - 1];
+  std::vector<int32_t> fp(nq);  // batch-flattened context position of every fresh row
+  for (size_t r = 0; r < nq; ++r) fp[r] = p->ctx_off[p->q_req[r]] + p->q_pos[r];
+
+  std::vector<char> image;
+  auto put = [&](const void* src, size_t bytes) -> size_t {
+    const size_t at = image.size();
+    image.resize(at + (bytes + 255) / 256 * 256, 0);
+    if (bytes) std::memcpy(image.data() + at, src, bytes);
+    return at;
+  };
+  const size_t o_src_inst = put(p->src_inst.data(), n * 4);
+  const size_t o_src_row = put(p->src_row.data(), n * 4);
+  const size_t o_dst_slot = put(p->dst_slot.data(), n * 4);
+  const size_t o_kv_off16 = put(off.data(), off.size() * 4);
+  const size_t o_fresh_pos = put(fp.data(), nq * 4);
+  const size_t o_q_pos = put(p->q_pos.data(), nq * 4);
+  const size_t o_q_off = put(p->q_off.data(), (B + 1) * 4);
+  const size_t o_ctx_off = put(p->ctx_off.data(), (B + 1) * 4);
+  const size_t o_rope_cos = put(p->rope_cos.data(), p->rope_cos.size() * 4);
+  const size_t o_rope_sin = put(p->rope_sin.data(), p->rope_sin.size() * 4);
+  const size_t o_fresh_rot = put(p->fresh_rot.data(), p->fresh_rot.size() * 4);
+  const size_t o_fresh_cos = put(p->fresh_cos.data(), p->fresh_cos.size() * 4);
+  const size_t o_fresh_sin = put(p->fresh_sin.data(), p->fresh_sin.size() * 4);
+  const size_t o_tiles = put(p->tiles.data(), p->tiles.size() * sizeof(AttnTile));
+  const size_t o_merges = put(p->merges.data(), p->merges.size() * sizeof(AttnMerge));
+  image.resize(image.size() + 256, 0);
+
   char* base = nullptr;
-  hipError_t e = hipMalloc(reinterpret_cast<void**>(&base), total);
-  if (e != hipSuccess) {
+  if (hipMalloc(reinterpret_cast<void**>(&base), image.size()) != hipSuccess) {
     (void)hipGetLastError();
     return fail(ctx, MPIC_ERR_OOM, "device allocation of the plan failed");
   }
-  size_t at = 0;
-  auto put = [&](const void* src, size_t bytes, size_t reserve) -> void* {
-    void* dst = base + at;
-    if (bytes) e = hipMemcpy(dst, src, bytes, hipMemcpyHostToDevice);
-    at += reserve;
-    return dst;
-  };
-  PlanDevice d;
-  e = hipSuccess;
-  d.src_inst = static_cast<int32_t*>(put(p->src_inst.data(), n * 4, padded<int32_t>(n)));
-  if (e == hipSuccess) d.src_row = static_cast<int32_t*>(put(p->src_row.data(), n * 4, padded<int32_t>(n)));
-  if (e == hipSuccess) d.dst_slot = static_cast<int32_t*>(put(p->dst_slot.data(), n * 4, padded<int32_t>(n)));
-  {
-    // byte offset of every context row in 16-byte units (saves the attention kernel a
-    // 64-bit multiply per staged row); fits 32 bits for context buffers below 64 GiB
-    const uint64_t units = static_cast<uint64_t>(ctx->cfg.n_kv_heads) * ctx->cfg.head_dim *
-                           (ctx->cfg.dtype == MPIC_F32 ? 4 : 2) / 16;
-    if (static_cast<uint64_t>(p->max_slot + 1) * units > 0xffffffffull) {
-      (void)hipFree(base);
-      return fail(ctx, MPIC_ERR_UNSUPPORTED, "context buffers of 64 GiB or more are not supported");
-    }
-    // kTablePad entries follow the table: the attention kernels fetch offsets eight at a
-    // time and may run up to one key block past the last key of a tile.  They repeat the
-    // last row of the batch, so that what is staged beyond a request's end is always a
-    // linked row (its weight is zero, but 0 x NaN from an untouched slot would not be)
-    std::vector<uint32_t> off(n + kTablePad, 0u);
-    for (size_t i = 0; i < n; ++i) off[i] = static_cast<uint32_t>(static_cast<uint64_t>(p->dst_slot[i]) * units);
-    for (size_t i = n; i < off.size() && n > 0; ++i) off[i] = off[n - 1];
-    if (e == hipSuccess) d.kv_off16 = static_cast<uint32_t*>(put(off.data(), off.size() * 4, padded<int32_t>(off.size())));
-  }
-  {
-    std::vector<int32_t> fp(nq);
-    for (size_t r = 0; r < nq; ++r) fp[r] = p->ctx_off[p->q_req[r]] + p->q_pos[r];
-    if (e == hipSuccess) d.fresh_pos = static_cast<int32_t*>(put(fp.data(), nq * 4, padded<int32_t>(nq)));
-  }
-  if (e == hipSuccess) d.q_pos = static_cast<int32_t*>(put(p->q_pos.data(), nq * 4, padded<int32_t>(nq)));
-  if (e == hipSuccess) d.q_off = static_cast<int32_t*>(put(p->q_off.data(), (B + 1) * 4, padded<int32_t>(B + 1)));
-  if (e == hipSuccess) d.ctx_off = static_cast<int32_t*>(put(p->ctx_off.data(), (B + 1) * 4, padded<int32_t>(B + 1)));
-  const size_t nr = p->rope_cos.size();
-  if (e == hipSuccess) d.rope_cos = static_cast<float*>(put(p->rope_cos.data(), nr * 4, padded<float>(nr)));
-  if (e == hipSuccess) d.rope_sin = static_cast<float*>(put(p->rope_sin.data(), nr * 4, padded<float>(nr)));
-  if (!p->fresh_rot.empty()) {
-    const size_t nf = p->fresh_cos.size();
-    if (e == hipSuccess) d.fresh_rot = static_cast<int32_t*>(put(p->fresh_rot.data(), nq * 4, padded<int32_t>(nq)));
-    if (e == hipSuccess) d.fresh_cos = static_cast<float*>(put(p->fresh_cos.data(), nf * 4, padded<float>(nf)));
-    if (e == hipSuccess) d.fresh_sin = static_cast<float*>(put(p->fresh_sin.data(), nf * 4, padded<float>(nf)));
-  }
-  if (e == hipSuccess)
-    d.tiles = static_cast<AttnTile*>(put(p->tiles.data(), p->tiles.size() * sizeof(AttnTile),
-                                         padded<AttnTile>(p->tiles.size())));
-  if (e == hipSuccess)
-    d.merges = static_cast<AttnMerge*>(put(p->merges.data(), p->merges.size() * sizeof(AttnMerge),
-                                           padded<AttnMerge>(p->merges.size())));
+  const hipError_t e = hipMemcpy(base, image.data(), image.size(), hipMemcpyHostToDevice);
   if (e != hipSuccess) {
     (void)hipFree(base);
     return fail_hip(ctx, e, "upload of the plan");
   }
+  PlanDevice d;
+  d.src_inst = reinterpret_cast<int32_t*>(base + o_src_inst);
+  d.src_row = reinterpret_cast<int32_t*>(base + o_src_row);
+  d.dst_slot = reinterpret_cast<int32_t*>(base + o_dst_slot);
+  d.kv_off16 = reinterpret_cast<uint32_t*>(base + o_kv_off16);
+  d.fresh_pos = reinterpret_cast<int32_t*>(base + o_fresh_pos);
+  d.q_pos = reinterpret_cast<int32_t*>(base + o_q_pos);
+  d.q_off = reinterpret_cast<int32_t*>(base + o_q_off);
+  d.ctx_off = reinterpret_cast<int32_t*>(base + o_ctx_off);
+  d.rope_cos = reinterpret_cast<float*>(base + o_rope_cos);
+  d.rope_sin = reinterpret_cast<float*>(base + o_rope_sin);
+  if (!p->fresh_rot.empty()) {  // null pointers tell the kernels that fresh rows arrive rotated
+    d.fresh_rot = reinterpret_cast<int32_t*>(base + o_fresh_rot);
+    d.fresh_cos = reinterpret_cast<float*>(base + o_fresh_cos);
+    d.fresh_sin = reinterpret_cast<float*>(base + o_fresh_sin);
+  }
+  d.tiles = reinterpret_cast<AttnTile*>(base + o_tiles);
+  d.merges = reinterpret_cast<AttnMerge*>(base + o_merges);
   d.block = base;
   d.device = ctx->device;
   p->dev = d;
@@ -160,10 +159,10 @@ extern "C" int mpic_assemble_kv(mpic_ctx* ctx, mpic_plan* plan, const mpic_chunk
                                 n_ctx_slots, MPIC_PART_CACHED | MPIC_PART_FRESH, stream_);
 }
 
-extern "C" int mpic_assemble_kv_parts(mpic_ctx* ctx, mpic_plan* plan, const mpic_chunk_src* srcs,
-                                      int32_t n_srcs, const void* fresh_k, const void* fresh_v,
-                                      int64_t n_fresh_rows, void* k_ctx, void* v_ctx,
-                                      int64_t n_ctx_slots, uint32_t parts, void* stream_) {
+static int assemble_kv_parts_impl(mpic_ctx* ctx, mpic_plan* plan, const mpic_chunk_src* srcs,
+                                  int32_t n_srcs, const void* fresh_k, const void* fresh_v,
+                                  int64_t n_fresh_rows, void* k_ctx, void* v_ctx,
+                                  int64_t n_ctx_slots, uint32_t parts, void* stream_) {
   if (!ctx) return MPIC_ERR_INVALID;
   if (parts == 0 || (parts & ~static_cast<uint32_t>(MPIC_PART_CACHED | MPIC_PART_FRESH)))
     return fail(ctx, MPIC_ERR_INVALID, "assemble_kv: parts must be MPIC_PART_CACHED, MPIC_PART_FRESH or both");
@@ -351,10 +350,10 @@ extern "C" int mpic_assemble_kv_parts(mpic_ctx* ctx, mpic_plan* plan, const mpic
   return MPIC_OK;
 }
 
-extern "C" int mpic_selective_attn(mpic_ctx* ctx, mpic_plan* plan, const void* fresh_q,
-                                   int64_t n_fresh_rows, const void* k_ctx, const void* v_ctx,
-                                   int64_t n_ctx_slots, double softmax_scale, void* out, float* lse,
-                                   void* stream_) {
+static int selective_attn_impl(mpic_ctx* ctx, mpic_plan* plan, const void* fresh_q,
+                               int64_t n_fresh_rows, const void* k_ctx, const void* v_ctx,
+                               int64_t n_ctx_slots, double softmax_scale, void* out, float* lse,
+                               void* stream_) {
   if (!ctx) return MPIC_ERR_INVALID;
   if (!plan || plan->ctx != ctx) return fail(ctx, MPIC_ERR_INVALID, "selective_attn: plan does not belong to this context");
   if (n_fresh_rows != plan->n_q) return fail(ctx, MPIC_ERR_INVALID, "selective_attn: n_fresh_rows differs from the plan's recompute set");
@@ -420,10 +419,10 @@ extern "C" int mpic_selective_attn(mpic_ctx* ctx, mpic_plan* plan, const void* f
   return MPIC_OK;
 }
 
-extern "C" int mpic_decode_attn(mpic_ctx* ctx, mpic_plan* plan, const void* q, const void* new_k,
-                                const void* new_v, const void* k_ctx, const void* v_ctx,
-                                int64_t n_ctx_slots, double softmax_scale, void* out, float* lse,
-                                void* stream_) {
+static int decode_attn_impl(mpic_ctx* ctx, mpic_plan* plan, const void* q, const void* new_k,
+                            const void* new_v, const void* k_ctx, const void* v_ctx,
+                            int64_t n_ctx_slots, double softmax_scale, void* out, float* lse,
+                            void* stream_) {
   if (!ctx) return MPIC_ERR_INVALID;
   if (!plan || plan->ctx != ctx) return fail(ctx, MPIC_ERR_INVALID, "decode_attn: plan does not belong to this context");
   if (!(softmax_scale > 0.0) || !std::isfinite(softmax_scale)) return fail(ctx, MPIC_ERR_INVALID, "decode_attn: softmax_scale must be finite and positive");
@@ -495,4 +494,37 @@ extern "C" int mpic_decode_attn(mpic_ctx* ctx, mpic_plan* plan, const void* q, c
   a.max_ctx = max_ctx;
   MPIC_HIP(ctx, mpic::launch_decode(c.dtype, a, stream));
   return MPIC_OK;
+}
+
+// The entry points proper: nothing may be thrown across the C boundary, so a failed host
+// allocation inside the implementations above becomes MPIC_ERR_OOM here.
+#define MPIC_GUARDED(ctx, call)                                         \
+  try {                                                                 \
+    return call;                                                        \
+  } catch (const std::bad_alloc&) {                                     \
+    return fail(ctx, MPIC_ERR_OOM, "out of host memory");               \
+  }
+
+extern "C" int mpic_assemble_kv_parts(mpic_ctx* ctx, mpic_plan* plan, const mpic_chunk_src* srcs,
+                                      int32_t n_srcs, const void* fresh_k, const void* fresh_v,
+                                      int64_t n_fresh_rows, void* k_ctx, void* v_ctx,
+                                      int64_t n_ctx_slots, uint32_t parts, void* stream) {
+  MPIC_GUARDED(ctx, assemble_kv_parts_impl(ctx, plan, srcs, n_srcs, fresh_k, fresh_v, n_fresh_rows, k_ctx, v_ctx,
+                                           n_ctx_slots, parts, stream))
+}
+
+extern "C" int mpic_selective_attn(mpic_ctx* ctx, mpic_plan* plan, const void* fresh_q,
+                                   int64_t n_fresh_rows, const void* k_ctx, const void* v_ctx,
+                                   int64_t n_ctx_slots, double softmax_scale, void* out, float* lse,
+                                   void* stream) {
+  MPIC_GUARDED(ctx, selective_attn_impl(ctx, plan, fresh_q, n_fresh_rows, k_ctx, v_ctx, n_ctx_slots, softmax_scale,
+                                        out, lse, stream))
+}
+
+extern "C" int mpic_decode_attn(mpic_ctx* ctx, mpic_plan* plan, const void* q, const void* new_k,
+                                const void* new_v, const void* k_ctx, const void* v_ctx,
+                                int64_t n_ctx_slots, double softmax_scale, void* out, float* lse,
+                                void* stream) {
+  MPIC_GUARDED(ctx, decode_attn_impl(ctx, plan, q, new_k, new_v, k_ctx, v_ctx, n_ctx_slots, softmax_scale, out, lse,
+                                     stream))
 }
