@@ -3,6 +3,10 @@
 Selection rule (Sec. 4.2, last paragraph): the recompute set holds every text
 token and the first k tokens of every image chunk.  Text tokens are always in the
 set because their cache is only a placeholder (Sec. 4.1, the "dummy cache").
+A chunk may instead name the tokens to recompute one by one (any selection policy,
+e.g. the tokens of largest deviation that Sec. 5.1 attributes to CacheBlend-r, or
+the ranking by K distance of Sec. 4.2); the rest of the plan does not care how the
+set was chosen.
 Linking (Sec. 3.1 item 5; Fig. 7 step 2): every context position has exactly one
 source, either a stored chunk row or a freshly computed row that replaces it.
 """
@@ -11,7 +15,8 @@ import numpy as np
 
 def build_plan(requests, default_k, page_size=0, page_tables=None):
     """requests: list (batch) of segment lists; a segment is ("text", L) or
-    ("chunk", src_id, L, k) with k None -> default_k.
+    ("chunk", src_id, L, k) with k None -> default_k; k may also be a sequence of
+    chunk-local token indices (0 <= index < L), the explicit recompute set of the chunk.
 
     Returns a dict of int32 arrays.  Positions are request-local ("global" in the
     paper's sense: offset inside the linked context); rows of the fresh tensors and
@@ -26,7 +31,8 @@ def build_plan(requests, default_k, page_size=0, page_tables=None):
       inst_src/inst_delta/inst_len/inst_k/inst_req[n_inst]
                                  per chunk instance: caller's source id, position
                                  shift (= offset of its first token), length,
-                                 effective k, owning request
+                                 effective k (explicit set: length of its leading
+                                 run 0, 1, 2, ...), owning request
       runs[n_runs][4]            (request, first fresh row, length, first position)
                                  maximal runs of consecutive positions in the set
     """
@@ -46,14 +52,22 @@ def build_plan(requests, default_k, page_size=0, page_tables=None):
                     selected.add(off + t)
             elif seg[0] == "chunk":
                 _, src, L, k = seg
-                k = default_k if k is None or k < 0 else k
-                k_eff = min(k, L)
+                if k is None or isinstance(k, (int, np.integer)):
+                    k = default_k if k is None or k < 0 else k
+                    chosen = set(range(min(k, L)))
+                else:
+                    chosen = set(int(t) for t in k)
+                    if any(t < 0 or t >= L for t in chosen):
+                        raise ValueError("selected token outside its chunk")
+                k_eff = 0
+                while k_eff in chosen:
+                    k_eff += 1
                 inst = len(inst_src)
                 inst_src.append(src); inst_delta.append(off); inst_len.append(L)
                 inst_k.append(k_eff); inst_req.append(b)
                 for t in range(L):
                     owner[off + t] = (inst, t)
-                    if t < k_eff:
+                    if t in chosen:
                         selected.add(off + t)
             else:
                 raise ValueError(seg[0])

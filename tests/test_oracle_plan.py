@@ -52,11 +52,23 @@ def test_closed_form_counts(cfg, k, n, nq, sum_p1):
     assert int((p["q_pos"].astype(np.int64) + 1).sum()) == sum_p1
 
 
-segment = st.one_of(
-    st.tuples(st.just("text"), st.integers(0, 9)),
-    st.tuples(st.just("chunk"), st.integers(0, 3), st.integers(1, 12),
-              st.one_of(st.none(), st.integers(0, 14))),
-)
+@st.composite
+def _chunk(draw):
+    L = draw(st.integers(1, 12))
+    k = draw(st.one_of(st.none(), st.integers(0, 14),
+                       st.lists(st.integers(0, L - 1), max_size=L).map(tuple)))   # explicit token set
+    return ("chunk", draw(st.integers(0, 3)), L, k)
+
+
+segment = st.one_of(st.tuples(st.just("text"), st.integers(0, 9)), _chunk())
+
+
+def _chosen(seg, default_k):
+    """Chunk-local tokens a chunk segment asks to recompute, from its k or its explicit set."""
+    k = seg[3]
+    if k is None or isinstance(k, int):
+        return set(range(min(default_k if k is None else k, seg[2])))
+    return set(k)
 
 
 def _check_invariants(reqs, default_k, p, page_size=0, tables=None):
@@ -69,15 +81,15 @@ def _check_invariants(reqs, default_k, p, page_size=0, tables=None):
             if s[0] == "text":
                 label += [("t", None)] * s[1]
             else:
-                k = default_k if s[3] is None else s[3]
-                label += [("c", t < k) for t in range(s[2])]
+                pick = _chosen(s, default_k)
+                label += [("c", t in pick) for t in range(s[2])]
         c0, c1 = int(p["ctx_off"][b]), int(p["ctx_off"][b + 1])
         q0, q1 = int(p["q_off"][b]), int(p["q_off"][b + 1])
         assert c1 - c0 == len(label)
         want = [i for i, (kind, first) in enumerate(label) if kind == "t" or first]
         assert p["q_pos"][q0:q1].tolist() == want
         n_text = sum(s[1] for s in segs if s[0] == "text")
-        n_head = sum(min(default_k if s[3] is None else s[3], s[2]) for s in segs if s[0] == "chunk")
+        n_head = sum(len(_chosen(s, default_k)) for s in segs if s[0] == "chunk")
         assert q1 - q0 == n_text + n_head
         # every position has one source; fresh rows and positions are mutual inverses
         for i, r in enumerate(range(q0, q1)):
@@ -134,6 +146,24 @@ def test_random_layouts_paged(reqs, default_k, ps, rnd):
         tables.append(pool[at:at + n]); at += n
     p = build_plan(reqs, default_k, page_size=ps, page_tables=tables)
     _check_invariants(reqs, default_k, p, ps, tables)
+
+
+def test_explicit_token_sets_by_hand():
+    """A chunk that names its recompute tokens one by one: T2 C6{1,4,5} T1 C4{0,1,3}.
+    Positions: text 0,1; chunk tokens 2..7 of which 3,6,7; text 8; chunk 9..12 of which 9,10,12."""
+    reqs = [[("text", 2), ("chunk", 0, 6, (4, 1, 5, 1)), ("text", 1), ("chunk", 1, 4, [0, 1, 3])]]
+    p = build_plan(reqs, 99)
+    assert p["q_pos"].tolist() == [0, 1, 3, 6, 7, 8, 9, 10, 12]
+    assert p["runs"].tolist() == [[0, 0, 2, 0], [0, 2, 1, 3], [0, 3, 5, 6], [0, 8, 1, 12]]
+    assert p["inst_k"].tolist() == [0, 2]               # leading runs of the two sets
+    assert p["src_inst"].tolist() == [-1, -1, 0, -1, 0, 0, -1, -1, -1, -1, -1, 1, -1]
+    assert p["src_row"].tolist() == [0, 1, 0, 2, 2, 3, 3, 4, 5, 6, 7, 2, 8]
+    # an explicit prefix set is the first-k rule
+    a = build_plan([[("text", 3), ("chunk", 0, 9, (0, 1, 2, 3))]], 0)
+    b = build_plan([[("text", 3), ("chunk", 0, 9, 4)]], 0)
+    assert all(np.array_equal(a[f], b[f]) for f in a)
+    with pytest.raises(ValueError):
+        build_plan([[("chunk", 0, 4, (4,))]], 0)
 
 
 def test_missing_chunk_equals_text():
