@@ -70,10 +70,12 @@ typedef struct mpic_segment {
   int32_t kind;  /* 0 = text (always recomputed), 1 = cached chunk                       */
   int32_t len;   /* tokens, >= 0                                                         */
   int32_t chunk; /* kind 1: index into the srcs[] array given to mpic_assemble_kv        */
-  int32_t k;     /* kind 1: tokens recomputed at the head of the chunk; < 0 = default_k; */
+  int32_t k;     /* kind 1: tokens recomputed at the head of the chunk; -1 = default_k;  */
                  /*         >= len recomputes the whole chunk (a cache that is missing   */
-                 /*         or failed to load, Sec. 3.2)                                 */
+                 /*         or failed to load, Sec. 3.2); MPIC_K_LISTED: the tokens are  */
+                 /*         named one by one (mpic_plan_create_selected only)            */
 } mpic_segment;
+#define MPIC_K_LISTED (-2)
 
 /* Stored cache of one chunk for the layer being assembled. */
 typedef struct mpic_chunk_src {
@@ -96,7 +98,7 @@ enum {
   MPIC_PLAN_INST_SRC = 8, /* [n_inst] srcs[] index of each chunk instance                    */
   MPIC_PLAN_INST_DELTA = 9,  /* [n_inst] rotary shift = position of the instance's first token */
   MPIC_PLAN_INST_LEN = 10,   /* [n_inst] tokens                                                */
-  MPIC_PLAN_INST_K = 11,     /* [n_inst] effective k = min(k, len)                             */
+  MPIC_PLAN_INST_K = 11,     /* [n_inst] effective k = min(k, len); listed set: its leading run */
   MPIC_PLAN_INST_REQ = 12,   /* [n_inst] owning request                                        */
   MPIC_PLAN_RUNS = 13,       /* [n_runs][4] (request, first fresh row, length, first position) */
   MPIC_PLAN_ATTN_TILES = 14  /* [n_tiles][8] launch order of the attention kernel: (request,   */
@@ -148,6 +150,23 @@ void mpic_destroy(mpic_ctx* ctx);
 int mpic_plan_create(mpic_ctx* ctx, int32_t n_requests, const int32_t* seg_off,
                      const mpic_segment* segs, int32_t default_k, const int32_t* page_table,
                      const int32_t* page_table_off, int64_t n_pool_pages, mpic_plan** out);
+
+/*
+ * The same plan for recompute sets chosen by another policy than "the first k tokens"
+ * (Sec. 4.2 derives that rule from a ranking of tokens by K distance; Sec. 5.1 compares with
+ * recomputing the tokens of largest deviation): a chunk segment whose k is MPIC_K_LISTED
+ * recomputes exactly the chunk-local tokens sel_idx[sel_off[s] .. sel_off[s+1]), s being
+ * the segment's index in segs (any order, duplicates allowed, each 0 <= index < len; an
+ * empty range recomputes nothing).  Other segments follow their k as in mpic_plan_create.
+ * Text tokens are always recomputed.  sel_off [n_segs + 1] and sel_idx are host arrays and
+ * may be NULL when no segment is listed.
+ * Errors: as mpic_plan_create; MPIC_ERR_INVALID for a listed token outside its chunk or a
+ * listed segment without sel_off.
+ */
+int mpic_plan_create_selected(mpic_ctx* ctx, int32_t n_requests, const int32_t* seg_off,
+                              const mpic_segment* segs, int32_t default_k, const int32_t* sel_off,
+                              const int32_t* sel_idx, const int32_t* page_table,
+                              const int32_t* page_table_off, int64_t n_pool_pages, mpic_plan** out);
 
 /* Borrow one host array of the plan; valid until mpic_plan_destroy. */
 int mpic_plan_get(const mpic_plan* plan, int32_t what, const int32_t** host_ptr, size_t* n);

@@ -60,6 +60,10 @@ def load_library():
     lib.mpic_plan_create.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(_Segment), i32,
                                      C.POINTER(i32), C.POINTER(i32), i64, C.POINTER(vp)]
     lib.mpic_plan_create.restype = C.c_int
+    lib.mpic_plan_create_selected.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(_Segment), i32,
+                                              C.POINTER(i32), C.POINTER(i32),
+                                              C.POINTER(i32), C.POINTER(i32), i64, C.POINTER(vp)]
+    lib.mpic_plan_create_selected.restype = C.c_int
     lib.mpic_plan_get.argtypes = [vp, i32, C.POINTER(C.POINTER(i32)), C.POINTER(C.c_size_t)]
     lib.mpic_plan_get.restype = C.c_int
     lib.mpic_plan_get_rope.argtypes = [vp, C.POINTER(C.POINTER(C.c_float)),
@@ -118,17 +122,29 @@ def _i32_array(values):
     return arr, arr.ctypes.data_as(C.POINTER(C.c_int32))
 
 
+MPIC_K_LISTED = -2
+
+
 def mpic_plan_create(ctx, requests, default_k, page_tables=None, n_pool_pages=0):
-    """requests: list of segment lists, ("text", L) / ("chunk", src, L, k or None)."""
+    """requests: list of segment lists, ("text", L) / ("chunk", src, L, k or None); k may be a
+    sequence of chunk-local token indices, in which case mpic_plan_create_selected is called."""
     seg_off, flat = [0], []
+    sel_off, sel_idx, listed = [0], [], False
     for segs in requests:
         for s in segs:
             if s[0] == "text":
                 flat.append(_Segment(0, s[1], 0, -1))
             elif s[0] == "chunk":
-                flat.append(_Segment(1, s[2], s[1], -1 if s[3] is None else s[3]))
+                k = s[3]
+                if k is None or isinstance(k, (int, np.integer)):
+                    flat.append(_Segment(1, s[2], s[1], -1 if k is None else int(k)))
+                else:
+                    flat.append(_Segment(1, s[2], s[1], MPIC_K_LISTED))
+                    sel_idx.extend(int(t) for t in k)
+                    listed = True
             else:
                 raise ValueError(f"unknown segment kind {s[0]!r}")
+            sel_off.append(len(sel_idx))
         seg_off.append(len(flat))
     segs_c = (_Segment * max(1, len(flat)))(*flat)
     off_keep, off_p = _i32_array(seg_off)
@@ -140,8 +156,14 @@ def mpic_plan_create(ctx, requests, default_k, page_tables=None, n_pool_pages=0)
     else:
         pt_p = pto_p = None
     h = C.c_void_p()
-    rc = load_library().mpic_plan_create(ctx, len(requests), off_p, segs_c, default_k, pt_p, pto_p,
-                                         n_pool_pages, C.byref(h))
+    if listed:
+        so_keep, so_p = _i32_array(sel_off)
+        si_keep, si_p = _i32_array(sel_idx)
+        rc = load_library().mpic_plan_create_selected(ctx, len(requests), off_p, segs_c, default_k, so_p, si_p,
+                                                      pt_p, pto_p, n_pool_pages, C.byref(h))
+    else:
+        rc = load_library().mpic_plan_create(ctx, len(requests), off_p, segs_c, default_k, pt_p, pto_p,
+                                             n_pool_pages, C.byref(h))
     _check(rc, ctx)
     return h
 

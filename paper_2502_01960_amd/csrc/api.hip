@@ -181,7 +181,7 @@ static int assemble_kv_parts_impl(mpic_ctx* ctx, mpic_plan* plan, const mpic_chu
   for (size_t i = 0; i < n_inst; ++i) {
     const mpic_chunk_src& s = srcs[plan->inst_src[i]];
     if (s.len != plan->inst_len[i]) return fail(ctx, MPIC_ERR_INVALID, "assemble_kv: chunk source length differs from its segment");
-    if (plan->inst_k[i] < plan->inst_len[i]) {  // some rows are actually read
+    if (plan->inst_cached[i] > 0) {  // some rows are actually read
       if (!s.k || !s.v || !mpic::aligned16(s.k) || !mpic::aligned16(s.v))
         return fail(ctx, MPIC_ERR_INVALID, "assemble_kv: chunk source pointer missing or not 16-byte aligned");
       any_host = any_host || s.on_host != 0;
@@ -209,12 +209,12 @@ static int assemble_kv_parts_impl(mpic_ctx* ctx, mpic_plan* plan, const mpic_chu
   if (any_host) {
     for (size_t i = 0; i < n_inst; ++i) {
       const int32_t s = plan->inst_src[i];
-      if (srcs[s].on_host && plan->inst_k[i] < plan->inst_len[i])
+      if (srcs[s].on_host && plan->inst_cached[i] > 0)
         first_row[s] = std::min(first_row[s], plan->inst_k[i]);
     }
     for (size_t i = 0; i < n_inst; ++i) {
       const int32_t s = plan->inst_src[i];
-      if (srcs[s].on_host && plan->inst_k[i] < plan->inst_len[i] && stage_off[s] == SIZE_MAX) {
+      if (srcs[s].on_host && plan->inst_cached[i] > 0 && stage_off[s] == SIZE_MAX) {
         stage_off[s] = need;  // room for the whole chunk keeps row addressing trivial
         need += 2 * static_cast<size_t>(srcs[s].len) * row_bytes;
         host_srcs.push_back(s);
@@ -301,7 +301,7 @@ static int assemble_kv_parts_impl(mpic_ctx* ctx, mpic_plan* plan, const mpic_chu
     mpic::AssembleSrcTable tab{};
     for (size_t i = i0; i < i1; ++i) {
       const mpic_chunk_src& s = srcs[plan->inst_src[i]];
-      const bool deferred = s.on_host && plan->inst_k[i] < plan->inst_len[i];
+      const bool deferred = s.on_host && plan->inst_cached[i] > 0;
       tab.k[i - i0] = deferred ? nullptr : s.k;
       tab.v[i - i0] = deferred ? nullptr : s.v;
     }
@@ -321,7 +321,7 @@ static int assemble_kv_parts_impl(mpic_ctx* ctx, mpic_plan* plan, const mpic_chu
     std::vector<size_t> order;
     for (size_t i = 0; i < n_inst; ++i) {
       const int32_t s = plan->inst_src[i];
-      if (srcs[s].on_host && plan->inst_k[i] < plan->inst_len[i]) order.push_back(i);
+      if (srcs[s].on_host && plan->inst_cached[i] > 0) order.push_back(i);
     }
     std::stable_sort(order.begin(), order.end(), [&](size_t x, size_t y) {
       return group_of[plan->inst_src[x]] < group_of[plan->inst_src[y]];

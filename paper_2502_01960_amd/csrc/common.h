@@ -88,6 +88,7 @@ struct mpic_plan {
   int32_t max_src = -1;   // largest srcs[] index used
   std::vector<int32_t> ctx_off, q_off, q_pos, q_req, slot_map, src_inst, src_row, dst_slot;
   std::vector<int32_t> inst_src, inst_delta, inst_len, inst_k, inst_req, runs;
+  std::vector<int32_t> inst_cached;  // rows each chunk instance actually takes from its stored cache
   std::vector<mpic::AttnTile> tiles;
   std::vector<mpic::AttnMerge> merges;  // tiles cut along the keys
   int32_t n_parts = 0;                  // partial-result slots those tiles use

@@ -283,6 +283,15 @@ extern "C" int mpic_plan_create(mpic_ctx* ctx, int32_t n_requests, const int32_t
                                 const mpic_segment* segs, int32_t default_k,
                                 const int32_t* page_table, const int32_t* page_table_off,
                                 int64_t n_pool_pages, mpic_plan** out) {
+  return mpic_plan_create_selected(ctx, n_requests, seg_off, segs, default_k, nullptr, nullptr, page_table,
+                                   page_table_off, n_pool_pages, out);
+}
+
+extern "C" int mpic_plan_create_selected(mpic_ctx* ctx, int32_t n_requests, const int32_t* seg_off,
+                                         const mpic_segment* segs, int32_t default_k,
+                                         const int32_t* sel_off, const int32_t* sel_idx,
+                                         const int32_t* page_table, const int32_t* page_table_off,
+                                         int64_t n_pool_pages, mpic_plan** out) {
   if (!ctx) return MPIC_ERR_INVALID;
   if (!out) return fail(ctx, MPIC_ERR_INVALID, "plan_create: out is NULL");
   *out = nullptr;
@@ -305,6 +314,12 @@ extern "C" int mpic_plan_create(mpic_ctx* ctx, int32_t n_requests, const int32_t
     n_ctx += g.len;
     if (g.kind == 0) {
       n_q += g.len;
+    } else if (g.k == MPIC_K_LISTED) {
+      if (!sel_off || sel_off[s + 1] < sel_off[s] || (sel_off[s + 1] > sel_off[s] && !sel_idx))
+        return fail(ctx, MPIC_ERR_INVALID, "plan_create: a listed recompute set needs sel_off / sel_idx");
+      for (int32_t i = sel_off[s]; i < sel_off[s + 1]; ++i)
+        if (sel_idx[i] < 0 || sel_idx[i] >= g.len) return fail(ctx, MPIC_ERR_INVALID, "plan_create: listed token outside its chunk");
+      n_q += std::min<int64_t>(sel_off[s + 1] - sel_off[s], g.len);  // upper bound (duplicates allowed)
     } else {
       const int64_t k = g.k < 0 ? default_k : g.k;
       n_q += std::min<int64_t>(k, g.len);
@@ -320,7 +335,6 @@ extern "C" int mpic_plan_create(mpic_ctx* ctx, int32_t n_requests, const int32_t
     p->ctx = ctx;
     p->n_requests = n_requests;
     p->n_ctx = n_ctx;
-    p->n_q = n_q;
     p->ctx_off.assign(1, 0);
     p->q_off.assign(1, 0);
     p->q_pos.reserve(n_q);
@@ -329,7 +343,7 @@ extern "C" int mpic_plan_create(mpic_ctx* ctx, int32_t n_requests, const int32_t
     p->src_inst.resize(n_ctx);
     p->src_row.resize(n_ctx);
     p->dst_slot.resize(n_ctx);
-    std::vector<char> page_used;
+    std::vector<char> page_used, mark;
     if (ps > 0) page_used.assign(n_pool_pages, 0);
 
     for (int b = 0; b < n_requests; ++b) {
@@ -359,8 +373,16 @@ extern "C" int mpic_plan_create(mpic_ctx* ctx, int32_t n_requests, const int32_t
         if (g.kind == 0) {
           take_fresh(pos, g.len);
         } else {
-          const int64_t k = g.k < 0 ? default_k : g.k;
-          const int32_t k_eff = static_cast<int32_t>(std::min<int64_t>(k, g.len));
+          // which tokens of the chunk are recomputed: the first k, or the listed ones
+          mark.assign(g.len, 0);
+          if (g.k == MPIC_K_LISTED) {
+            for (int32_t i = sel_off[s]; i < sel_off[s + 1]; ++i) mark[sel_idx[i]] = 1;
+          } else {
+            const int64_t k = g.k < 0 ? default_k : g.k;
+            std::fill(mark.begin(), mark.begin() + std::min<int64_t>(k, g.len), 1);
+          }
+          int32_t k_eff = 0;  // length of the leading recomputed run
+          while (k_eff < g.len && mark[k_eff]) ++k_eff;
           const int32_t inst = static_cast<int32_t>(p->inst_src.size());
           p->inst_src.push_back(g.chunk);
           p->inst_delta.push_back(pos);
@@ -368,11 +390,23 @@ extern "C" int mpic_plan_create(mpic_ctx* ctx, int32_t n_requests, const int32_t
           p->inst_k.push_back(k_eff);
           p->inst_req.push_back(b);
           p->max_src = std::max(p->max_src, g.chunk);
-          take_fresh(pos, k_eff);
-          for (int32_t t = k_eff; t < g.len; ++t) {
-            p->src_inst[ctx0 + pos + t] = inst;
-            p->src_row[ctx0 + pos + t] = t;
+          int32_t cached = 0;
+          for (int32_t t = 0; t < g.len;) {
+            int32_t e = t;
+            if (mark[t]) {
+              while (e < g.len && mark[e]) ++e;
+              take_fresh(pos + t, e - t);
+            } else {
+              while (e < g.len && !mark[e]) {
+                p->src_inst[ctx0 + pos + e] = inst;
+                p->src_row[ctx0 + pos + e] = e;
+                ++e;
+              }
+              cached += e - t;
+            }
+            t = e;
           }
+          p->inst_cached.push_back(cached);
         }
         pos += g.len;
       }
@@ -402,6 +436,7 @@ extern "C" int mpic_plan_create(mpic_ctx* ctx, int32_t n_requests, const int32_t
       p->q_off.push_back(row);
     }
     for (int32_t s : p->dst_slot) p->max_slot = std::max<int64_t>(p->max_slot, s);
+    p->n_q = static_cast<int64_t>(p->q_pos.size());
 
     // rotary tables: one angle vector per chunk instance, evaluated in double
     const int half = ctx->cfg.head_dim / 2;

@@ -66,10 +66,22 @@ int main() {
         table_off.push_back(static_cast<int32_t>(table.size()));
       }
     }
+    // every fourth batch names the recompute tokens of some chunks one by one
+    std::vector<int32_t> sel_off(1, 0), sel_idx;
+    const bool listed = iter % 4 == 1;
+    for (mpic_segment& g : segs) {
+      if (listed && g.kind == 1 && rnd(0, 1)) {
+        g.k = MPIC_K_LISTED;
+        const int cnt = rnd(0, g.len + 3);
+        for (int i = 0; i < cnt; ++i) sel_idx.push_back(rnd(0, g.len - 1));
+      }
+      sel_off.push_back(static_cast<int32_t>(sel_idx.size()));
+    }
     mpic_plan* plan = nullptr;
-    const int rc = mpic_plan_create(ctx, B, seg_off.data(), segs.data(), rnd(0, 40),
-                                    cfg.page_size ? table.data() : nullptr,
-                                    cfg.page_size ? table_off.data() : nullptr, pool, &plan);
+    const int rc = mpic_plan_create_selected(ctx, B, seg_off.data(), segs.data(), rnd(0, 40),
+                                             listed ? sel_off.data() : nullptr, listed ? sel_idx.data() : nullptr,
+                                             cfg.page_size ? table.data() : nullptr,
+                                             cfg.page_size ? table_off.data() : nullptr, pool, &plan);
     CHECK(rc == MPIC_OK);
     // every array is readable end to end and consistent in size
     const int32_t* p = nullptr;

@@ -332,6 +332,26 @@ def _check_decode(p, with_self=True):
         assert np.abs(L[~empty] - L_ref[~empty]).max(initial=0.0) <= 1e-5 * max(1.0, np.abs(L_ref[~empty]).max(initial=0.0))
 
 
+def test_recompute_sets_named_token_by_token():
+    """Recompute sets from another policy than first-k (scattered tokens, many short runs):
+    a seeded 12 % of every chunk plus its first token, contiguous and paged, device and
+    host sources; and a set that is everything / nothing."""
+    rng = np.random.default_rng(77)
+    for paged, host in ((0, False), (16, True)):
+        reqs = []
+        for b in range(3):
+            segs = [("text", 9 + b)]
+            for c in range(3):
+                L = 257
+                pick = sorted(set([0] + rng.choice(L, size=L // 8, replace=False).tolist()))
+                segs += [("chunk", c, L, pick), ("text", 5)]
+            reqs.append(segs)
+        reqs.append([("chunk", 0, 257, list(range(257))), ("chunk", 1, 257, []), ("text", 2)])
+        p = _custom(reqs, 3, [257, 257, 257], 4, paged=paged)
+        assert len(p.oplan["runs"]) > 200
+        _run_full(p, host_sourced=host)
+
+
 def test_decode_step_after_prefill():
     """One query per request over the linked context (contiguous and paged, fp32 and bf16,
     ragged lengths that end inside a 32-key block and inside a split), with and without

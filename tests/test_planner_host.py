@@ -81,11 +81,15 @@ def _check_tiles(plan, want, group, n_kv):
     assert sorted(slots) == list(range(len(slots)))
 
 
-segment = st.one_of(
-    st.tuples(st.just("text"), st.integers(0, 40)),
-    st.tuples(st.just("chunk"), st.integers(0, 5), st.integers(1, 70),
-              st.one_of(st.none(), st.integers(0, 80))),
-)
+@st.composite
+def _chunk(draw):
+    L = draw(st.integers(1, 70))
+    k = draw(st.one_of(st.none(), st.integers(0, 80),
+                       st.lists(st.integers(0, L - 1), max_size=L).map(tuple)))   # tokens named one by one
+    return ("chunk", draw(st.integers(0, 5)), L, k)
+
+
+segment = st.one_of(st.tuples(st.just("text"), st.integers(0, 40)), _chunk())
 
 
 @settings(max_examples=120, deadline=None)
@@ -153,6 +157,20 @@ def test_fresh_row_rotary_tables_are_float64_accurate():
     assert len(r0) == 0 and len(c0) == 0
     with pytest.raises(mpic.MpicError):
         mpic.Context(4, 4, 64, mpic.MPIC_F32, 1e4, 0, 0, 2)
+
+
+def test_listed_recompute_sets():
+    reqs = [[("text", 2), ("chunk", 0, 6, (4, 1, 5, 1)), ("text", 1), ("chunk", 1, 4, [0, 1, 3])],
+            [("chunk", 1, 4, ()), ("chunk", 0, 6, None)]]
+    want = build_plan(reqs, 3)
+    got = mpic.Plan(_ctx(), reqs, 3)
+    for f in INT_FIELDS:
+        assert np.array_equal(got.get(f), want[f]), f
+    assert got.get("q_pos").tolist() == [0, 1, 3, 6, 7, 8, 9, 10, 12, 4, 5, 6]
+    with pytest.raises(mpic.MpicError):
+        mpic.Plan(_ctx(), [[("chunk", 0, 4, (4,))]], 0)          # token outside its chunk
+    with pytest.raises(mpic.MpicError):
+        mpic.Plan(_ctx(), [[("chunk", 0, 4, mpic.MPIC_K_LISTED)]], 0)   # listed, but no list given
 
 
 def test_rejected_arguments():
