@@ -22,6 +22,9 @@ Pin status of every function (see tests/test_oracle_*.py):
   decode.decode_attend   pinned: the last row of causal prefill over context + new token
                          (library SDPA), the last row of attend when the request ends
                          in a text token, closed forms
+  select.k_distance      pinned: loop transcription, closed forms (identical caches, a
+                         constant offset), metric laws
+  select.top_tokens / top_counts   pinned: hand-ranked example with ties, counts add up
 The paper prints no worked numeric example of this path, so beyond those pins the
 values are unpinned by the paper itself.
 """
@@ -30,3 +33,4 @@ from .rope import rotate                # noqa: F401
 from .link import link_kv, position_fresh, to_slots     # noqa: F401
 from .attend import attend, attend_loops  # noqa: F401
 from .decode import decode_attend       # noqa: F401
+from .select import k_distance, top_tokens, top_counts  # noqa: F401
