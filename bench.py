@@ -204,6 +204,22 @@ def main():
     decode(sets[0])
     dec_ms = timed(decode, args.steps)
 
+    # ---- K distance of two caches (analysis kernel; every row of both is read once) ----
+    kd = None
+    if L >= 2:
+        dist = torch.empty((n_slots,), dtype=torch.float32, device=dev)
+
+        def kdist(s):
+            other = sets[1] if s is sets[0] else sets[0]
+            mpic.mpic_k_distance(ctx.handle, s["k_ctx"], other["k_ctx"], dist, stream)
+
+        kdist(sets[0])
+        kd_ms = timed(kdist, args.steps)
+        kd_bytes = 2.0 * n_slots * sh.n_kv_heads * sh.head_dim * 2
+        kd = {"ms": round(kd_ms, 5), "GBps": round(kd_bytes / (kd_ms * 1e-3) / 1e9, 2),
+              "pct_hbm_peak": round(100 * kd_bytes / (kd_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 3), "bytes": kd_bytes,
+              "note": "per-token L1 distance between two linked K caches of the whole batch"}
+
     if args.calibrate_copy:
         x = torch.zeros(256 * 1024 * 1024, dtype=torch.bfloat16, device=dev)
         y = torch.empty_like(x)
@@ -313,6 +329,7 @@ def main():
                      "bytes": asm_bytes},
         "decode_step": {"ms": round(dec_ms, 5), "GBps": round(dec_gbs, 2), "pct_hbm_peak": round(100 * dec_gbs / PEAK_HBM_GBS, 3),
                         "bytes": dec_bytes, "note": "one query per request over the linked context plus itself; two launches"},
+        "k_distance": kd,
         "plan_ms": round(plan_ms, 4),
         "first_layer_ms": round(first_layer_ms, 4),
         "first_layer_ms_warm_process": round(warm_first_layer_ms, 4),

@@ -298,6 +298,28 @@ int mpic_decode_attn(mpic_ctx* ctx, mpic_plan* plan, const void* q, const void* 
                      const void* new_v, const void* k_ctx, const void* v_ctx, int64_t n_ctx_slots,
                      double softmax_scale, void* out, float* lse, void* stream);
 
+/*
+ * K distance of every token of a chunk (Sec. 4.2: the L1 distance between the token's K
+ * tensors in two caches of the same image computed at different positions):
+ *   dist[t] = sum over kv heads and coordinates of |k_a[t] - k_b[t]|, fp32 accumulation.
+ *   k_a, k_b          device [n_tokens][Hkv][D] in the context's dtype, 16-byte aligned
+ *   dist              device float [n_tokens], written
+ * Errors: MPIC_ERR_INVALID, MPIC_ERR_HIP.
+ */
+int mpic_k_distance(mpic_ctx* ctx, const void* k_a, const void* k_b, int64_t n_tokens, float* dist,
+                    void* stream);
+
+/*
+ * Host only: the n_top tokens of largest distance (Sec. 4.2 ranks the tokens of every layer
+ * this way and keeps the first 50), as ascending chunk-local indices ready for
+ * mpic_plan_create_selected.  Of two tokens with the same distance the lower index ranks
+ * higher; NaN ranks last.  n_top is clipped to n_tokens.
+ *   dist              host float [n_tokens]
+ *   idx               host int32 [min(n_top, n_tokens)], written
+ * Errors: MPIC_ERR_INVALID, MPIC_ERR_OOM.
+ */
+int mpic_rank_tokens(const float* dist, int64_t n_tokens, int64_t n_top, int32_t* idx);
+
 /* Static description of a status code. */
 const char* mpic_strerror(int status);
 

@@ -5,6 +5,6 @@ Argument marshalling only: every step of the path runs in the HIP library.
 from .binding import (  # noqa: F401
     MpicError, Context, Plan, lib_path, load_library,
     mpic_create, mpic_destroy, mpic_plan_create, mpic_plan_get, mpic_plan_get_rope, mpic_plan_get_fresh_rope,
-    mpic_plan_destroy, mpic_assemble_kv, mpic_assemble_kv_parts, mpic_selective_attn, mpic_decode_attn, mpic_strerror, mpic_last_error,
+    mpic_plan_destroy, mpic_assemble_kv, mpic_assemble_kv_parts, mpic_selective_attn, mpic_decode_attn, mpic_k_distance, mpic_rank_tokens, mpic_strerror, mpic_last_error,
     MPIC_F32, MPIC_BF16, MPIC_PART_CACHED, MPIC_PART_FRESH, MPIC_K_LISTED, PLAN_FIELDS,
 )

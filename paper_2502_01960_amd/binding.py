@@ -82,6 +82,10 @@ def load_library():
     lib.mpic_selective_attn.restype = C.c_int
     lib.mpic_decode_attn.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, C.c_double, vp, vp, vp]
     lib.mpic_decode_attn.restype = C.c_int
+    lib.mpic_k_distance.argtypes = [vp, vp, vp, i64, vp, vp]
+    lib.mpic_k_distance.restype = C.c_int
+    lib.mpic_rank_tokens.argtypes = [C.POINTER(C.c_float), i64, i64, C.POINTER(i32)]
+    lib.mpic_rank_tokens.restype = C.c_int
     lib.mpic_strerror.argtypes = [C.c_int]
     lib.mpic_strerror.restype = C.c_char_p
     lib.mpic_last_error.argtypes = [vp]
@@ -258,6 +262,21 @@ def mpic_decode_attn(ctx, plan, q, new_k, new_v, k_ctx, v_ctx, softmax_scale, ou
                                          0 if k_ctx is None else k_ctx.shape[0], float(softmax_scale),
                                          _ptr(out), _ptr(lse), _stream(stream))
     _check(rc, ctx)
+
+
+def mpic_k_distance(ctx, k_a, k_b, dist, stream=None):
+    rc = load_library().mpic_k_distance(ctx, _ptr(k_a), _ptr(k_b), k_a.shape[0], _ptr(dist), _stream(stream))
+    _check(rc, ctx)
+
+
+def mpic_rank_tokens(dist, n_top):
+    """dist: host float32 array; returns the ascending indices of the n_top largest entries."""
+    d = np.ascontiguousarray(dist, dtype=np.float32)
+    out = np.zeros(max(0, min(int(n_top), len(d))), dtype=np.int32)
+    rc = load_library().mpic_rank_tokens(d.ctypes.data_as(C.POINTER(C.c_float)), len(d), int(n_top),
+                                         out.ctypes.data_as(C.POINTER(C.c_int32)))
+    _check(rc)
+    return out
 
 
 # ---------------------------------------------------------------- handle owners

@@ -352,6 +352,39 @@ def test_recompute_sets_named_token_by_token():
         _run_full(p, host_sourced=host)
 
 
+def test_k_distance_and_ranked_recompute_set():
+    """K distance of Sec. 4.2 on the GPU against the oracle (fp32 and bf16), then the whole
+    chain: rank the tokens of each chunk by it, recompute the top 10 %, link and attend."""
+    from oracle import k_distance, top_tokens
+    dev = torch.device("cuda:0")
+    for cfg in (1, 5):
+        sh = workloads.shape(cfg)
+        dt = mpic.MPIC_F32 if sh.dtype == "f32" else mpic.MPIC_BF16
+        ctx = mpic.Context(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, dt, sh.rope_theta)
+        L = 1153
+        a, b = workloads.gen_chunk(sh, 0, 0, L)[0], workloads.gen_chunk(sh, 1, 0, L)[0]
+        b[5] = a[5]                                  # an identical token: distance exactly 0
+        dist = torch.full((L,), float("nan"), dtype=torch.float32, device=dev)
+        mpic.mpic_k_distance(ctx.handle, a.to(dev), b.to(dev), dist)
+        torch.cuda.synchronize()
+        want = k_distance(a.to(torch.float64).numpy(), b.to(torch.float64).numpy())
+        got = dist.cpu().numpy().astype(np.float64)
+        assert got[5] == 0.0
+        assert np.abs(got - want).max() <= 1e-5 * want.max()
+        assert mpic.mpic_rank_tokens(dist.cpu().numpy(), 50).tolist() == top_tokens(dist.cpu().numpy(), 50).tolist()
+    # the chain on a reduced config 3: sets chosen by rank instead of by position
+    sh = workloads.shape(3)
+    ctx = mpic.Context(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, mpic.MPIC_BF16, sh.rope_theta)
+    L, picks = 301, []
+    for c in range(3):
+        a, b = workloads.gen_chunk(sh, 0, c, L)[0].to(dev), workloads.gen_chunk(sh, 7, c, L)[0].to(dev)
+        dist = torch.empty((L,), dtype=torch.float32, device=dev)
+        mpic.mpic_k_distance(ctx.handle, a, b, dist)
+        picks.append(mpic.mpic_rank_tokens(dist.cpu().numpy(), L // 10).tolist())
+    reqs = [[("text", 20)] + [seg for c in range(3) for seg in (("chunk", c, L, picks[c]), ("text", 11))]]
+    _run_full(_custom(reqs, 3, [L, L, L], 0), host_sourced=False)
+
+
 def test_decode_step_after_prefill():
     """One query per request over the linked context (contiguous and paged, fp32 and bf16,
     ragged lengths that end inside a 32-key block and inside a split), with and without

@@ -173,6 +173,21 @@ def test_listed_recompute_sets():
         mpic.Plan(_ctx(), [[("chunk", 0, 4, mpic.MPIC_K_LISTED)]], 0)   # listed, but no list given
 
 
+def test_token_ranking_matches_oracle():
+    from oracle import top_tokens
+    rng = np.random.default_rng(9)
+    for n in (1, 7, 50, 2304):
+        dist = rng.integers(0, 12, size=n).astype(np.float32)        # many ties
+        for n_top in (0, 1, 5, 50, n, n + 3):
+            assert mpic.mpic_rank_tokens(dist, n_top).tolist() == top_tokens(dist, n_top).tolist()
+    dist = rng.standard_normal(500).astype(np.float32)
+    assert mpic.mpic_rank_tokens(dist, 50).tolist() == top_tokens(dist, 50).tolist()
+    dist[[3, 77]] = np.nan                                            # never among the chosen unless forced
+    got = mpic.mpic_rank_tokens(dist, 498).tolist()
+    assert 3 not in got and 77 not in got and len(got) == 498
+    assert mpic.mpic_rank_tokens(np.zeros(0, np.float32), 5).tolist() == []
+
+
 def test_rejected_arguments():
     with pytest.raises(mpic.MpicError):
         _ctx(hq=6, hkv=4)                      # heads do not group
