@@ -72,15 +72,21 @@ static_assert(WAVES * ROWS_PER_WAVE == kAttnTileRows, "tile size and kernel shap
 //   K, read 16 bytes per lane by 16+ consecutive rows:      swizzle = row & 15
 //   V, transpose-read as 4 rows x 64 bytes per 32 lanes:    swizzle = (row & 3) << 2
 
-// Direct global->LDS load of 16 bytes per lane: LDS[m0 + 16*lane] = *gptr.  Written as
+// Direct global->LDS loads of 16 bytes per lane: LDS[m0 + 16*lane] = *gptr.  Written as
 // inline assembly so that the outstanding-load counter is managed by hand below: the
 // compiler would otherwise wait for *all* direct loads before any LDS read, which
-// defeats a ring that keeps three blocks in flight.
-__device__ inline void load_to_lds_16B(const void* gptr, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-               :
-               : "v"(gptr), "s"(lds_addr)
-               : "memory", "m0");
+// defeats a ring that keeps three blocks in flight.  The four loads a wavefront issues per
+// block go out back to back, each from its own address registers.
+__device__ inline void load4_to_lds_16B(const void* g0, const void* g1, const void* g2, const void* g3,
+                                        uint32_t l0, uint32_t l1, uint32_t l2, uint32_t l3) {
+  asm volatile(
+      "s_mov_b32 m0, %4\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off\n\t"
+      "s_mov_b32 m0, %5\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\t"
+      "s_mov_b32 m0, %6\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\t"
+      "s_mov_b32 m0, %7\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %3, off"
+      :
+      : "v"(g0), "v"(g1), "v"(g2), "v"(g3), "s"(l0), "s"(l1), "s"(l2), "s"(l3)
+      : "memory", "m0");
 }
 // s_waitcnt vmcnt(n) only (expcnt / lgkmcnt fields left at "no wait")
 #define WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
@@ -194,12 +200,12 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a) {
     const u32x8_a4 cur = ro;
     ro = fetch_rows(blk + 1);
     const uint32_t dst = lds_base + (blk % STAGES) * STAGE_BYTES + wave * 8 * ROW_BYTES;
-#pragma unroll
-    for (int p = 0; p < 2; ++p) {
-      const uint32_t r16 = ld_sub == 0 ? cur[4 * p] : ld_sub == 1 ? cur[4 * p + 1] : ld_sub == 2 ? cur[4 * p + 2] : cur[4 * p + 3];
-      load_to_lds_16B(kbase + (static_cast<uint64_t>(r16 + (ld_k16 ^ (4 * p))) << 4), dst + p * 4 * ROW_BYTES);
-      load_to_lds_16B(vbase + (static_cast<uint64_t>(r16 + ld_v16) << 4), dst + TILE_BYTES + p * 4 * ROW_BYTES);
-    }
+    // the four loads go out back to back, each from its own address registers
+    const uint32_t ra = ld_sub == 0 ? cur[0] : ld_sub == 1 ? cur[1] : ld_sub == 2 ? cur[2] : cur[3];
+    const uint32_t rb = ld_sub == 0 ? cur[4] : ld_sub == 1 ? cur[5] : ld_sub == 2 ? cur[6] : cur[7];
+    load4_to_lds_16B(kbase + (static_cast<uint64_t>(ra + ld_k16) << 4), vbase + (static_cast<uint64_t>(ra + ld_v16) << 4),
+                     kbase + (static_cast<uint64_t>(rb + (ld_k16 ^ 4)) << 4), vbase + (static_cast<uint64_t>(rb + ld_v16) << 4),
+                     dst, dst + TILE_BYTES, dst + 4 * ROW_BYTES, dst + TILE_BYTES + 4 * ROW_BYTES);
   };
 
   // ---- LDS byte offsets of this lane's operand fragments ----
