@@ -126,6 +126,8 @@ def _run_sampled(p, host_sourced, per_run=6):
     assert np.isfinite(O).all()
     assert_bf16_close(O[rows], O_ref[rows], "attention output (sampled rows)")
     assert np.abs(p.lse.cpu().numpy()[rows] - L_ref[rows]).max() < 2e-2
+    # the decode step over the same full-size context (every request, every head)
+    _check_decode(p, True, (K_ref, V_ref))
 
 
 def test_config3_full_size_sampled():
@@ -312,11 +314,11 @@ def test_linking_in_two_parts_equals_one_call():
         mpic.mpic_assemble_kv_parts(p.ctx.handle, p.plan.handle, p.srcs, p.d_fk, p.d_fv, p.k_ctx, p.v_ctx, 0)
 
 
-def _check_decode(p, with_self=True):
+def _check_decode(p, with_self=True, linked=None):
     """Decode step over the context that p has linked on the GPU: oracle fed the oracle's
     own linked context (end to end)."""
     bf16 = p.sh.dtype == "bf16"
-    K_ref, V_ref = p.oracle_link()
+    K_ref, V_ref = linked if linked is not None else p.oracle_link()
     q, nk, nv = p.decode_inputs()
     if not with_self:
         nk = nv = None
