@@ -82,8 +82,19 @@ typedef struct mpic_chunk_src {
   const void* k;   /* [len][Hkv][D], keys already rotated for chunk-local positions 0..len-1 */
   const void* v;   /* [len][Hkv][D]                                                          */
   int32_t len;     /* must equal the len of every segment that refers to this source         */
-  int32_t on_host; /* 0: device memory; 1: pinned host memory, staged over the side stream   */
+  int32_t on_host; /* where the cache lives, see below                                        */
 } mpic_chunk_src;
+enum {
+  MPIC_SRC_DEVICE = 0,      /* device memory, read in place                                        */
+  MPIC_SRC_HOST_STAGED = 1, /* pinned host memory: copied by the DMA engines on the library's side  */
+                            /* stream into library staging, then linked (uses no compute unit while */
+                            /* in flight, so it overlaps with whatever the GPU computes)            */
+  MPIC_SRC_HOST_MAPPED = 2  /* pinned host memory that the GPU can address (hipHostMalloc): the     */
+                            /* linking kernel reads it in place over the bus -- no staging, no     */
+                            /* copies, higher bus throughput; the launch lasts as long as the      */
+                            /* transfer, so issue it (mpic_assemble_kv_parts, MPIC_PART_CACHED) on */
+                            /* another stream than the computation it should overlap with          */
+};
 
 /* Selectors for mpic_plan_get.  All arrays are int32. */
 enum {
@@ -204,9 +215,8 @@ void mpic_plan_destroy(mpic_plan* plan);
  * touched.
  *
  *   srcs [n_srcs]     host array; every chunk index used by the plan must be < n_srcs
- *                     and srcs[i].len must match.  k / v: device, or pinned host when
- *                     on_host != 0 (copied on the library's side stream into library
- *                     staging, overlapped with the linking of other rows).
+ *                     and srcs[i].len must match.  k / v: device, or pinned host memory
+ *                     according to on_host (MPIC_SRC_*).
  *   fresh_k, fresh_v  device [n_fresh_rows][Hkv][D]; may be NULL only if the plan
  *                     has no fresh row.  Keys already carry their global position,
  *                     unless the context was created with fresh_pre_rope = 1: then each

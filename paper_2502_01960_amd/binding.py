@@ -222,23 +222,26 @@ def _stream(stream):
 
 
 MPIC_PART_CACHED, MPIC_PART_FRESH = 1, 2
+MPIC_SRC_DEVICE, MPIC_SRC_HOST_STAGED, MPIC_SRC_HOST_MAPPED = 0, 1, 2
 
 
-def mpic_assemble_kv(ctx, plan, srcs, fresh_k, fresh_v, k_ctx, v_ctx, stream=None):
-    """srcs: list of (k_tensor, v_tensor) per source id; a pinned CPU tensor is staged
-    by the library, a device tensor is read in place.  Tensors are torch tensors."""
+def mpic_assemble_kv(ctx, plan, srcs, fresh_k, fresh_v, k_ctx, v_ctx, stream=None, host_mode=MPIC_SRC_HOST_STAGED):
+    """srcs: list of (k_tensor, v_tensor) per source id; a device tensor is read in place, a
+    pinned CPU tensor is staged by the library (host_mode = MPIC_SRC_HOST_STAGED) or read in
+    place by the kernel (MPIC_SRC_HOST_MAPPED).  Tensors are torch tensors."""
     mpic_assemble_kv_parts(ctx, plan, srcs, fresh_k, fresh_v, k_ctx, v_ctx,
-                           MPIC_PART_CACHED | MPIC_PART_FRESH, stream)
+                           MPIC_PART_CACHED | MPIC_PART_FRESH, stream, host_mode)
 
 
-def mpic_assemble_kv_parts(ctx, plan, srcs, fresh_k, fresh_v, k_ctx, v_ctx, parts, stream=None):
+def mpic_assemble_kv_parts(ctx, plan, srcs, fresh_k, fresh_v, k_ctx, v_ctx, parts, stream=None,
+                           host_mode=MPIC_SRC_HOST_STAGED):
     srcs = srcs or []
     arr = (_ChunkSrc * max(1, len(srcs)))()
     for i, (k, v) in enumerate(srcs):
         if k is None:
             arr[i] = _ChunkSrc(None, None, 0, 0)
             continue
-        on_host = 0 if k.is_cuda else 1
+        on_host = MPIC_SRC_DEVICE if k.is_cuda else int(host_mode)
         if on_host and not (k.is_pinned() and v.is_pinned()):
             raise ValueError("host chunk sources must be pinned")
         arr[i] = _ChunkSrc(k.data_ptr(), v.data_ptr(), k.shape[0], on_host)

@@ -133,6 +133,7 @@ struct AssembleArgs {
   int32_t n_kv_heads, head_dim, interleaved;
   int32_t skip_fresh;          // 1: leave rows of the recompute set alone
   const int32_t* pos_list;     // non-null: the launch visits pos_list[pos_begin .. pos_end) instead of a range
+  int32_t grid_limit;          // > 0: at most this many workgroups, which stride over the work
 };
 constexpr int kMaxInstPerLaunch = 128;
 struct AssembleSrcTable {

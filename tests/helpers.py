@@ -78,9 +78,11 @@ class Problem:
         self.out = torch.full(tuple(self.q.shape), float("nan"), dtype=sh.torch_dtype, device=dev)
         self.lse = torch.full(tuple(self.q.shape[:2]), float("nan"), dtype=torch.float32, device=dev)
 
+    host_mode = mpic.MPIC_SRC_HOST_STAGED   # how pinned host chunks reach the GPU (staged copies / read in place)
+
     def gpu_assemble(self):
         mpic.mpic_assemble_kv(self.ctx.handle, self.plan.handle, self.srcs, self.d_fk, self.d_fv,
-                              self.k_ctx, self.v_ctx)
+                              self.k_ctx, self.v_ctx, None, self.host_mode)
 
     def gpu_attend(self, lse=True):
         mpic.mpic_selective_attn(self.ctx.handle, self.plan.handle, self.d_q, self.k_ctx, self.v_ctx,

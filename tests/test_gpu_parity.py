@@ -387,6 +387,35 @@ def test_k_distance_and_ranked_recompute_set():
     _run_full(_custom(reqs, 3, [L, L, L], 0), host_sourced=False)
 
 
+def test_host_chunks_read_in_place_by_the_kernel():
+    """MPIC_SRC_HOST_MAPPED: pinned host chunks are read over the bus by the linking kernel
+    itself (no staging copies).  Same gates as the other routes, bit-identical context, also
+    when only the cached part is linked, and mixed with device-resident chunks."""
+    for make in (lambda: Problem(3, n_chunks=3, chunk_len=301, text_len=37, batch=2),
+                 lambda: Problem(5, n_chunks=5, chunk_len=203, text_len=21)):
+        ref = make(); ref.gpu_setup(False); ref.gpu_assemble(); torch.cuda.synchronize()
+        p = make()
+        p.host_mode = mpic.MPIC_SRC_HOST_MAPPED
+        _run_full(p, host_sourced=True)
+        assert torch.equal(p.k_ctx[~torch.isnan(p.k_ctx.float())].view(torch.int16),
+                           ref.k_ctx[~torch.isnan(ref.k_ctx.float())].view(torch.int16))
+        # one chunk from the device, the others from the host, cached part on a second stream
+        p.srcs[0] = tuple(t.to(p.k_ctx.device) for t in p.chunks[0])
+        p.k_ctx.fill_(float("nan")); p.v_ctx.fill_(float("nan"))
+        side = torch.cuda.Stream()
+        torch.cuda.synchronize()
+        mpic.mpic_assemble_kv_parts(p.ctx.handle, p.plan.handle, p.srcs, None, None, p.k_ctx, p.v_ctx,
+                                    mpic.MPIC_PART_CACHED, side, mpic.MPIC_SRC_HOST_MAPPED)
+        mpic.mpic_assemble_kv_parts(p.ctx.handle, p.plan.handle, None, p.d_fk, p.d_fv, p.k_ctx, p.v_ctx,
+                                    mpic.MPIC_PART_FRESH)
+        torch.cuda.synchronize()
+        same = ~torch.isnan(ref.k_ctx.float())
+        assert torch.equal(p.k_ctx[same].view(torch.int16), ref.k_ctx[same].view(torch.int16))
+        assert torch.equal(p.v_ctx[same].view(torch.int16), ref.v_ctx[same].view(torch.int16))
+    with pytest.raises(mpic.MpicError):
+        mpic.mpic_assemble_kv(p.ctx.handle, p.plan.handle, p.srcs, p.d_fk, p.d_fv, p.k_ctx, p.v_ctx, None, 3)
+
+
 def test_decode_step_after_prefill():
     """One query per request over the linked context (contiguous and paged, fp32 and bf16,
     ragged lengths that end inside a 32-key block and inside a split), with and without
