@@ -190,6 +190,23 @@ def main():
     attn_ms = timed(attend, args.steps)
     asm_ms = timed(assemble, args.steps)
 
+    # ---- one layer (link + attention) captured in a HIP graph and replayed: what a
+    # launch-bound serving loop would do for small batches (extra figure) ----------
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        mpic.mpic_assemble_kv(ctx.handle, plan.handle, sets[0]["srcs"], sets[0]["fk"], sets[0]["fv"],
+                              sets[0]["k_ctx"], sets[0]["v_ctx"], None)
+        mpic.mpic_selective_attn(ctx.handle, plan.handle, sets[0]["q"], sets[0]["k_ctx"], sets[0]["v_ctx"],
+                                 sh.softmax_scale, sets[0]["out"], None, None)
+    graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    graph_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    del graph
+
     # ---- decode step right after the prefill (extra figure; HBM-bound) ----------
     for l, s in enumerate(sets):
         s["dec"] = [torch.cat([workloads.gen_fresh(sh, 1000 + l, b, 1)[i] for b in range(len(requests))]).to(dev)
@@ -341,6 +358,7 @@ def main():
         "decode_step": {"ms": round(dec_ms, 5), "GBps": round(dec_gbs, 2), "pct_hbm_peak": round(100 * dec_gbs / PEAK_HBM_GBS, 3),
                         "bytes": dec_bytes, "note": "one query per request over the linked context plus itself; two launches"},
         "k_distance": kd,
+        "graph_replay_step_ms": round(graph_ms, 5),
         "plan_ms": round(plan_ms, 4),
         "first_layer_ms": round(first_layer_ms, 4),
         "first_layer_ms_warm_process": round(warm_first_layer_ms, 4),

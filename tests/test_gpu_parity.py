@@ -475,3 +475,39 @@ def test_rows_staged_past_a_request_end_are_linked_rows():
     _run_full(p, host_sourced=False)
     assert torch.isnan(p.k_ctx[:16].float()).all()
     _check_decode(p, True)
+
+
+def test_calls_can_be_captured_in_a_graph():
+    """After one eager call (which uploads the plan and sizes the workspaces) linking, attention
+    and the decode step are plain kernel launches on the caller's stream, so a launch-bound
+    loop can be captured in a HIP graph: three replays with new inputs in the same buffers,
+    eager work between the replays, every replay bit-identical to the eager result."""
+    p = Problem(2, n_chunks=2, chunk_len=150, text_len=13)     # small: tiles cut along the keys, merge kernel
+    p.gpu_setup(False)
+    dq, dk, dv = (t.to(p.k_ctx.device) for t in p.decode_inputs())
+    dec_out = torch.empty_like(dq)
+
+    def run():
+        p.gpu_assemble()
+        p.gpu_attend()
+        mpic.mpic_decode_attn(p.ctx.handle, p.plan.handle, dq, dk, dv, p.k_ctx, p.v_ctx, p.sh.softmax_scale, dec_out)
+
+    run()                                                       # eager warm-up: uploads, workspaces
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    gen = torch.Generator(device="cpu").manual_seed(5)
+    for rep in range(3):
+        for t in (p.d_q, p.d_fk, p.d_fv, dq, dk, dv):
+            t.copy_(torch.randn(t.shape, generator=gen).to(t.dtype))
+        run()                                                   # eager reference on the new inputs
+        torch.cuda.synchronize()
+        want = [x.clone() for x in (p.k_ctx, p.v_ctx, p.out, p.lse, dec_out)]
+        for x in (p.k_ctx, p.v_ctx, p.out, dec_out):
+            x.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip((p.k_ctx, p.v_ctx, p.out, p.lse, dec_out), want):
+            assert torch.equal(got.view(torch.int16 if got.dtype == torch.bfloat16 else torch.int32),
+                               ref.view(torch.int16 if ref.dtype == torch.bfloat16 else torch.int32))
