@@ -127,7 +127,7 @@ def main():
         s = sets[i % L]
         side.wait_event(ev_free[i % L])   # the attention that last read this context has finished
         mpic.mpic_assemble_kv_parts(ctx.handle, plan.handle, srcs or s["srcs"], None, None, s["k_ctx"], s["v_ctx"],
-                                    mpic.MPIC_PART_CACHED, side, mode)
+                                    mpic.MPIC_PART_CACHED | mpic.MPIC_PART_BACKGROUND, side, mode)
         ev_cached[i % L].record(side)
 
     def step(i, n_total, srcs=None, mode=mpic.MPIC_SRC_HOST_STAGED):

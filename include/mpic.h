@@ -241,9 +241,13 @@ int mpic_assemble_kv(mpic_ctx* ctx, mpic_plan* plan, const mpic_chunk_src* srcs,
  * The two parts write disjoint rows and may run in either order or concurrently; with
  * both bits the call equals mpic_assemble_kv.  With MPIC_PART_CACHED alone fresh_k, fresh_v
  * and n_fresh_rows are ignored; with MPIC_PART_FRESH alone srcs and n_srcs are ignored.
+ * MPIC_PART_BACKGROUND may be added to either part: it tells the library that the call runs
+ * beside other GPU work on another stream, and the linking kernel is then held to a small grid
+ * that strides over the rows, so that it takes a few wave slots for longer instead of the
+ * whole chip for a moment (alone it would run several times slower).
  * Errors: as mpic_assemble_kv; MPIC_ERR_INVALID for an empty or unknown `parts`.
  */
-enum { MPIC_PART_CACHED = 1, MPIC_PART_FRESH = 2 };
+enum { MPIC_PART_CACHED = 1, MPIC_PART_FRESH = 2, MPIC_PART_BACKGROUND = 4 };
 int mpic_assemble_kv_parts(mpic_ctx* ctx, mpic_plan* plan, const mpic_chunk_src* srcs,
                            int32_t n_srcs, const void* fresh_k, const void* fresh_v,
                            int64_t n_fresh_rows, void* k_ctx, void* v_ctx, int64_t n_ctx_slots,

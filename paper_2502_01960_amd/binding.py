@@ -221,7 +221,7 @@ def _stream(stream):
     return C.c_void_p(getattr(stream, "cuda_stream", stream))
 
 
-MPIC_PART_CACHED, MPIC_PART_FRESH = 1, 2
+MPIC_PART_CACHED, MPIC_PART_FRESH, MPIC_PART_BACKGROUND = 1, 2, 4
 MPIC_SRC_DEVICE, MPIC_SRC_HOST_STAGED, MPIC_SRC_HOST_MAPPED = 0, 1, 2
 
 

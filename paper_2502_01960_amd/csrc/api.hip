@@ -164,6 +164,8 @@ static int assemble_kv_parts_impl(mpic_ctx* ctx, mpic_plan* plan, const mpic_chu
                                   int64_t n_fresh_rows, void* k_ctx, void* v_ctx,
                                   int64_t n_ctx_slots, uint32_t parts, void* stream_) {
   if (!ctx) return MPIC_ERR_INVALID;
+  const bool background = parts & MPIC_PART_BACKGROUND;
+  parts &= ~static_cast<uint32_t>(MPIC_PART_BACKGROUND);
   if (parts == 0 || (parts & ~static_cast<uint32_t>(MPIC_PART_CACHED | MPIC_PART_FRESH)))
     return fail(ctx, MPIC_ERR_INVALID, "assemble_kv: parts must be MPIC_PART_CACHED, MPIC_PART_FRESH or both");
   const bool do_cached = parts & MPIC_PART_CACHED, do_fresh = parts & MPIC_PART_FRESH;
@@ -312,11 +314,13 @@ static int assemble_kv_parts_impl(mpic_ctx* ctx, mpic_plan* plan, const mpic_chu
     a.inst_base = static_cast<int32_t>(i0);
     a.n_inst = static_cast<int32_t>(i1 - i0);
     a.skip_fresh = do_fresh ? 0 : 1;
-    // chunks read in place over the bus: a small grid that strides.  64 workgroups keep the
-    // bus busy (52 GB/s measured) and leave the wave slots and registers of the chip to a
-    // concurrent kernel; with 128 or more the attention of the previous layer no longer
-    // overlaps (measured: 3.3 ms per step at 128, 2.8 ms at 64, 2.9 ms at 16)
-    a.grid_limit = any_mapped ? 64 : 0;
+    // Launches meant to run beside other work are held to a small grid that strides.
+    // Chunks read in place over the bus: 64 workgroups keep the bus busy (52 GB/s measured)
+    // and leave the wave slots and registers of the chip to a concurrent kernel; with 128 or
+    // more the attention of the previous layer no longer overlaps (measured: 3.3 ms per step
+    // at 128, 2.8 ms at 64, 2.9 ms at 16).  Background linking from device memory: the same
+    // 64 (whole step of the 18K-token batch: 1.151 ms at 64, 1.159 at 256, 1.179 unlimited).
+    a.grid_limit = (any_mapped || background) ? 64 : 0;
     MPIC_HIP(ctx, mpic::launch_assemble(c.dtype, a, tab, stream));
   }
   a.grid_limit = 0;

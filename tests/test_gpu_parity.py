@@ -302,7 +302,7 @@ def test_linking_in_two_parts_equals_one_call():
         side = torch.cuda.Stream()
         torch.cuda.synchronize()
         mpic.mpic_assemble_kv_parts(p.ctx.handle, p.plan.handle, p.srcs, None, None, p.k_ctx, p.v_ctx,
-                                    mpic.MPIC_PART_CACHED, side)
+                                    mpic.MPIC_PART_CACHED | (mpic.MPIC_PART_BACKGROUND if host else 0), side)
         side.synchronize()
         assert torch.isnan(p.k_ctx[fresh].float()).all(), "the cached part must not touch fresh rows"
         mpic.mpic_assemble_kv_parts(p.ctx.handle, p.plan.handle, None, p.d_fk, p.d_fv, p.k_ctx, p.v_ctx,
@@ -310,8 +310,19 @@ def test_linking_in_two_parts_equals_one_call():
         torch.cuda.synchronize()
         assert torch.equal(p.k_ctx.view(torch.int16), k_ref.view(torch.int16))
         assert torch.equal(p.v_ctx.view(torch.int16), v_ref.view(torch.int16))
-    with pytest.raises(mpic.MpicError):
-        mpic.mpic_assemble_kv_parts(p.ctx.handle, p.plan.handle, p.srcs, p.d_fk, p.d_fv, p.k_ctx, p.v_ctx, 0)
+    # the background hint changes the launch shape only
+    p = Problem(3, n_chunks=3, chunk_len=301, text_len=37, batch=2)
+    p.gpu_setup(False)
+    p.gpu_assemble(); torch.cuda.synchronize()
+    k_ref = p.k_ctx.clone()
+    p.k_ctx.fill_(float("nan"))
+    mpic.mpic_assemble_kv_parts(p.ctx.handle, p.plan.handle, p.srcs, p.d_fk, p.d_fv, p.k_ctx, p.v_ctx,
+                                mpic.MPIC_PART_CACHED | mpic.MPIC_PART_FRESH | mpic.MPIC_PART_BACKGROUND)
+    torch.cuda.synchronize()
+    assert torch.equal(p.k_ctx.view(torch.int16), k_ref.view(torch.int16))
+    for bad in (0, mpic.MPIC_PART_BACKGROUND, 8):
+        with pytest.raises(mpic.MpicError):
+            mpic.mpic_assemble_kv_parts(p.ctx.handle, p.plan.handle, p.srcs, p.d_fk, p.d_fv, p.k_ctx, p.v_ctx, bad)
 
 
 def _check_decode(p, with_self=True, linked=None):
