@@ -9,6 +9,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <functional>
 #include <new>
 #include <numeric>
 
@@ -65,7 +66,6 @@ void build_tiles(mpic_plan& p, int group, int n_kv_heads) {
   constexpr int64_t kSplitRounds = MPIC_SPLIT_ROUNDS;
   const int B = p.n_requests;
   const int n_combo = B * n_kv_heads;
-  std::vector<std::vector<Item>> per_combo(n_combo);
   auto last_pos = [&](int b, int64_t row_end) {  // position of the last fresh row below flattened row `row_end`
     return static_cast<int64_t>(p.q_pos[p.q_off[b] + (row_end - 1) / group]);
   };
@@ -105,93 +105,144 @@ void build_tiles(mpic_plan& p, int group, int n_kv_heads) {
     return n;
   };
   while (count_at_cap(cap) > kComputeUnits * rounds && cap < total_blocks) cap += std::max<int64_t>(1, cap / 16);
-  p.merges.clear();
-  p.n_parts = 0;
-  for (int b = 0; b < B; ++b) {
-    const int64_t rows = static_cast<int64_t>(p.q_off[b + 1] - p.q_off[b]) * group;
-    for (int64_t row = 0; row < rows; row += tile_rows) {
-      const int64_t n = std::min<int64_t>(tile_rows, rows - row);
-      const int64_t n_keys = last_pos(b, row + n) + 1;
-      const int64_t blocks = (n_keys + kBlock - 1) / kBlock;
-      int64_t parts = (blocks > cap && !no_cut) ? (blocks + cap - 1) / cap : 1;
-      const int64_t per = (blocks + parts - 1) / parts;  // blocks per piece
-      parts = (blocks + per - 1) / per;
-      for (int64_t i = 0; i < parts; ++i) {
-        const int64_t key0 = i * per * kBlock;
-        const int64_t key1 = std::min<int64_t>(n_keys, (i + 1) * per * kBlock);
-        // cost = keys visited, summed over the wavefronts of 32 rows (each stops at its own last row)
-        int64_t cost = 64;
-        for (int64_t w = row; w < row + n; w += 32)
-          cost += std::max<int64_t>(0, std::min<int64_t>(last_pos(b, std::min(w + 32, row + n)) + 1, key1) - key0);
-        for (int g = 0; g < n_kv_heads; ++g) {
-          Item it{};
-          it.t.req = b;
-          it.t.kv_head = g;
-          it.t.row0 = static_cast<int32_t>(row);
-          it.t.n_rows = static_cast<int32_t>(n);
-          it.t.n_keys = static_cast<int32_t>(key1);
-          it.t.key0 = static_cast<int32_t>(key0);
-          it.t.part = -1 - static_cast<int32_t>(i);  // resolved below, once the merge item of (tile, g) exists
-          it.cost = cost;
-          per_combo[b * n_kv_heads + g].push_back(it);
-        }
-      }
-      if (parts > 1) {
-        for (int g = 0; g < n_kv_heads; ++g) {
-          AttnMerge m{};
-          m.req = b;
-          m.kv_head = g;
-          m.row0 = static_cast<int32_t>(row);
-          m.n_rows = static_cast<int32_t>(n);
-          m.first_part = p.n_parts;
-          m.n_parts = static_cast<int32_t>(parts);
-          p.n_parts += static_cast<int32_t>(parts);
-          p.merges.push_back(m);
-          // the pieces of this (tile, g) were pushed last into their combo, in key order
-          auto& v = per_combo[b * n_kv_heads + g];
-          for (int64_t i = 0; i < parts; ++i) v[v.size() - parts + i].t.part = m.first_part + static_cast<int32_t>(i);
-        }
-      } else {
-        for (int g = 0; g < n_kv_heads; ++g) per_combo[b * n_kv_heads + g].back().t.part = -1;
-      }
-    }
-  }
+  // One candidate launch: the tiles cut with pieces of at most `cap` blocks, dealt to the L2
+  // domains and ordered inside each.
+  struct Layout {
+    std::vector<std::vector<Item>> queue;  // per L2 domain, in launch order
+    std::vector<AttnMerge> merges;
+    int32_t n_parts = 0;
+  };
   auto by_cost = [](const Item& a, const Item& b) { return a.cost > b.cost; };
-  std::vector<std::vector<Item>> queue(kXcds);
-  if (n_combo >= kXcds) {
-    // whole (request, kv head) groups go to the currently lightest domain, heaviest first
-    std::vector<int> order(n_combo);
-    std::iota(order.begin(), order.end(), 0);
-    std::vector<int64_t> total(n_combo, 0);
-    for (int c = 0; c < n_combo; ++c)
-      for (const Item& it : per_combo[c]) total[c] += it.cost;
-    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return total[a] > total[b]; });
-    std::vector<int64_t> load(kXcds, 0);
-    for (int c : order) {
-      const int x = static_cast<int>(std::min_element(load.begin(), load.end()) - load.begin());
-      load[x] += total[c];
-      queue[x].insert(queue[x].end(), per_combo[c].begin(), per_combo[c].end());
+  auto lay_out = [&](int64_t cap_blocks) {
+    Layout out;
+    std::vector<std::vector<Item>> per_combo(n_combo);
+    for (int b = 0; b < B; ++b) {
+      const int64_t rows = static_cast<int64_t>(p.q_off[b + 1] - p.q_off[b]) * group;
+      for (int64_t row = 0; row < rows; row += tile_rows) {
+        const int64_t n = std::min<int64_t>(tile_rows, rows - row);
+        const int64_t n_keys = last_pos(b, row + n) + 1;
+        const int64_t blocks = (n_keys + kBlock - 1) / kBlock;
+        int64_t parts = (blocks > cap_blocks && !no_cut) ? (blocks + cap_blocks - 1) / cap_blocks : 1;
+        const int64_t per = (blocks + parts - 1) / parts;  // blocks per piece
+        parts = (blocks + per - 1) / per;
+        for (int64_t i = 0; i < parts; ++i) {
+          const int64_t key0 = i * per * kBlock;
+          const int64_t key1 = std::min<int64_t>(n_keys, (i + 1) * per * kBlock);
+          // cost = keys visited, summed over the wavefronts of 32 rows (each stops at its own last row)
+          int64_t cost = 64;
+          for (int64_t w = row; w < row + n; w += 32)
+            cost += std::max<int64_t>(0, std::min<int64_t>(last_pos(b, std::min(w + 32, row + n)) + 1, key1) - key0);
+          for (int g = 0; g < n_kv_heads; ++g) {
+            Item it{};
+            it.t.req = b;
+            it.t.kv_head = g;
+            it.t.row0 = static_cast<int32_t>(row);
+            it.t.n_rows = static_cast<int32_t>(n);
+            it.t.n_keys = static_cast<int32_t>(key1);
+            it.t.key0 = static_cast<int32_t>(key0);
+            it.t.part = -1;  // set below for the pieces of a cut tile
+            it.cost = cost;
+            per_combo[b * n_kv_heads + g].push_back(it);
+          }
+        }
+        if (parts > 1) {
+          for (int g = 0; g < n_kv_heads; ++g) {
+            AttnMerge m{};
+            m.req = b;
+            m.kv_head = g;
+            m.row0 = static_cast<int32_t>(row);
+            m.n_rows = static_cast<int32_t>(n);
+            m.first_part = out.n_parts;
+            m.n_parts = static_cast<int32_t>(parts);
+            out.n_parts += static_cast<int32_t>(parts);
+            out.merges.push_back(m);
+            // the pieces of this (tile, g) were pushed last into their group, in key order
+            auto& v = per_combo[b * n_kv_heads + g];
+            for (int64_t i = 0; i < parts; ++i) v[v.size() - parts + i].t.part = m.first_part + static_cast<int32_t>(i);
+          }
+        }
+      }
     }
-  } else {
-    // fewer groups than domains: spread each group over `share` domains, tile by tile
-    const int share = std::max(1, kXcds / std::max(1, n_combo));
-    for (int c = 0; c < n_combo; ++c) {
-      std::stable_sort(per_combo[c].begin(), per_combo[c].end(), by_cost);
-      for (size_t i = 0; i < per_combo[c].size(); ++i)
-        queue[(c * share + static_cast<int>(i % share)) % kXcds].push_back(per_combo[c][i]);
+    out.queue.assign(kXcds, {});
+    if (n_combo >= kXcds) {
+      // whole (request, kv head) groups go to the currently lightest domain, heaviest first
+      std::vector<int> order(n_combo);
+      std::iota(order.begin(), order.end(), 0);
+      std::vector<int64_t> total(n_combo, 0);
+      for (int c = 0; c < n_combo; ++c)
+        for (const Item& it : per_combo[c]) total[c] += it.cost;
+      std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return total[a] > total[b]; });
+      std::vector<int64_t> load(kXcds, 0);
+      for (int c : order) {
+        const int x = static_cast<int>(std::min_element(load.begin(), load.end()) - load.begin());
+        load[x] += total[c];
+        out.queue[x].insert(out.queue[x].end(), per_combo[c].begin(), per_combo[c].end());
+      }
+    } else {
+      // fewer groups than domains: spread each group over `share` domains, tile by tile
+      const int share = std::max(1, kXcds / std::max(1, n_combo));
+      for (int c = 0; c < n_combo; ++c) {
+        std::stable_sort(per_combo[c].begin(), per_combo[c].end(), by_cost);
+        for (size_t i = 0; i < per_combo[c].size(); ++i)
+          out.queue[(c * share + static_cast<int>(i % share)) % kXcds].push_back(per_combo[c][i]);
+      }
+    }
+    for (auto& q : out.queue) std::stable_sort(q.begin(), q.end(), by_cost);
+    return out;
+  };
+  // Predicted duration of a launch, in blocks: every L2 domain hands its tiles in order to
+  // whichever of its compute units is free first; a piece of a cut tile costs three blocks
+  // more than its keys (prologue, partial result, share of the merge).
+  auto predicted_makespan = [&](const Layout& l) {
+    int64_t worst = 0;
+    auto heavier = std::greater<int64_t>();
+    for (const auto& q : l.queue) {
+      std::vector<int64_t> load(kComputeUnits / kXcds, 0);  // min-heap of compute unit loads
+      for (const Item& it : q) {
+        std::pop_heap(load.begin(), load.end(), heavier);
+        load.back() += (it.t.n_keys - it.t.key0 + kBlock - 1) / kBlock + 2 + (it.t.part >= 0 ? 3 : 0);
+        std::push_heap(load.begin(), load.end(), heavier);
+      }
+      worst = std::max(worst, *std::max_element(load.begin(), load.end()));
+    }
+    return worst;
+  };
+  Layout chosen = lay_out(cap);
+  // Large problems are not cut by the rule above, but a few tiles may be so long that the
+  // launch ends with most compute units idle (one request of 75K tokens: the longest tile is
+  // two thirds of a compute unit's whole share).  Whether cutting those pays is decided by
+  // simulating the launch for a few piece sizes; the uncut launch is kept unless a cut one
+  // is predicted to finish at least 3 % earlier.
+  if (!no_cut && chosen.n_parts == 0) {
+    int64_t longest = 0;
+    for (int b = 0; b < B; ++b) {
+      const int64_t rows = static_cast<int64_t>(p.q_off[b + 1] - p.q_off[b]) * group;
+      if (rows > 0) longest = std::max(longest, (last_pos(b, rows) + 1 + kBlock - 1) / kBlock);
+    }
+    if (2 * longest > per_cu) {
+      const int64_t uncut = predicted_makespan(chosen);
+      int64_t best = uncut - uncut * 3 / 100;
+      for (const int64_t c : {per_cu * 7 / 10, per_cu * 6 / 10, per_cu / 2, per_cu * 4 / 10}) {
+        if (c < kMinPieceBlocks || c >= longest) continue;
+        Layout cand = lay_out(c);
+        const int64_t m = predicted_makespan(cand);
+        if (m < best) {
+          best = m;
+          chosen = std::move(cand);
+        }
+      }
     }
   }
+  p.merges = std::move(chosen.merges);
+  p.n_parts = chosen.n_parts;
   size_t depth = 0;
-  for (auto& q : queue) {
-    std::stable_sort(q.begin(), q.end(), by_cost);
-    depth = std::max(depth, q.size());
-  }
+  for (const auto& q : chosen.queue) depth = std::max(depth, q.size());
   p.tiles.clear();
   p.tiles.reserve(depth * kXcds);
   for (size_t i = 0; i < depth; ++i)
     for (int x = 0; x < kXcds; ++x) {
-      if (i < queue[x].size()) {
-        p.tiles.push_back(queue[x][i].t);
+      if (i < chosen.queue[x].size()) {
+        p.tiles.push_back(chosen.queue[x][i].t);
       } else {
         p.tiles.push_back(AttnTile{});  // padding keeps the i % 8 dealing intact
       }
