@@ -36,6 +36,10 @@ def parse():
     ap.add_argument("--layers", type=int, default=4, help="distinct layer input sets the steps cycle over")
     ap.add_argument("--fresh-pre-rope", action="store_true",
                     help="hand fresh Q/K over before positional embedding (the library rotates them)")
+    ap.add_argument("--k", type=int, default=None, help="recompute the first K tokens of every chunk (default: the workload's)")
+    ap.add_argument("--device-data", action="store_true",
+                    help="draw the inputs on the GPU (seeded torch generator) instead of the host generator: for sweeps "
+                         "over many layer sets, where only the timing matters")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-host-sourced", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -71,6 +75,15 @@ def main():
         tables, pool = workloads.gen_page_tables(sh, lens)
     n_slots = pool * sh.page_size if sh.page_size else sum(lens)
 
+    if args.k is not None:
+        import dataclasses
+        sh = dataclasses.replace(sh, default_k=args.k)
+    if args.device_data:
+        args.no_cpu_baseline = args.no_host_sourced = True   # both legs read the host copies of the inputs
+        gen = torch.Generator(device=dev).manual_seed(0x4D504943)
+
+        def draw(*shape):
+            return torch.randn(shape, generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
     ctx = mpic.Context(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, mpic.MPIC_BF16, sh.rope_theta, 0, sh.page_size,
                        int(args.fresh_pre_rope))
     t0 = time.perf_counter()
@@ -86,14 +99,21 @@ def main():
     sets = []
     host_chunks0 = None
     for layer in range(L):
-        chunks = {s: workloads.gen_chunk(sh, layer, s, src_len[s]) for s in used_src}
-        if layer == 0:
-            host_chunks0 = chunks
-        srcs = [tuple(t.to(dev) for t in chunks[s]) if s in chunks else (None, None) for s in range(n_src)]
-        fresh = [workloads.gen_fresh(sh, layer, b, int(q_off[b + 1] - q_off[b])) for b in range(len(requests))]
-        q = torch.cat([f[0] for f in fresh]).to(dev)
-        fk = torch.cat([f[1] for f in fresh]).to(dev)
-        fv = torch.cat([f[2] for f in fresh]).to(dev)
+        if args.device_data:
+            kv_shape = (sh.n_kv_heads, sh.head_dim)
+            srcs = [(draw(src_len[s], *kv_shape), draw(src_len[s], *kv_shape)) if s in used_src else (None, None)
+                    for s in range(n_src)]
+            q = draw(max(n_q, 1), sh.n_q_heads, sh.head_dim)[:n_q]
+            fk, fv = draw(max(n_q, 1), *kv_shape)[:n_q], draw(max(n_q, 1), *kv_shape)[:n_q]
+        else:
+            chunks = {s: workloads.gen_chunk(sh, layer, s, src_len[s]) for s in used_src}
+            if layer == 0:
+                host_chunks0 = chunks
+            srcs = [tuple(t.to(dev) for t in chunks[s]) if s in chunks else (None, None) for s in range(n_src)]
+            fresh = [workloads.gen_fresh(sh, layer, b, int(q_off[b + 1] - q_off[b])) for b in range(len(requests))]
+            q = torch.cat([f[0] for f in fresh]).to(dev)
+            fk = torch.cat([f[1] for f in fresh]).to(dev)
+            fv = torch.cat([f[2] for f in fresh]).to(dev)
         k_ctx = torch.empty((n_slots, sh.n_kv_heads, sh.head_dim), dtype=torch.bfloat16, device=dev)
         v_ctx = torch.empty_like(k_ctx)
         out = torch.empty_like(q)
@@ -340,7 +360,7 @@ def main():
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "bf16",
-        "data": "synthetic",
+        "data": "synthetic (device RNG)" if args.device_data else "synthetic",
         "config": {"workload": f"config{args.config}:{sh.name}", "batch": len(requests), "tokens_per_request": lens[0],
                    "recompute_rows": n_q, "q_heads": sh.n_q_heads, "kv_heads": sh.n_kv_heads, "head_dim": sh.head_dim,
                    "k": sh.default_k, "page_size": sh.page_size, "layer_sets": L,

@@ -318,9 +318,19 @@ static int assemble_kv_parts_impl(mpic_ctx* ctx, mpic_plan* plan, const mpic_chu
     // Chunks read in place over the bus: 64 workgroups keep the bus busy (52 GB/s measured)
     // and leave the wave slots and registers of the chip to a concurrent kernel; with 128 or
     // more the attention of the previous layer no longer overlaps (measured: 3.3 ms per step
-    // at 128, 2.8 ms at 64, 2.9 ms at 16).  Background linking from device memory: the same
-    // 64 (whole step of the 18K-token batch: 1.151 ms at 64, 1.159 at 256, 1.179 unlimited).
-    a.grid_limit = (any_mapped || background) ? 64 : 0;
+    // at 128, 2.8 ms at 64, 2.9 ms at 16).  Background linking from device memory: one
+    // workgroup per 5 MB of traffic, at least 64, so that the launch lasts about a quarter of
+    // a millisecond alone whatever the batch (18K-token batch of 4, 325 MB: whole step 1.151 ms
+    // at 64, 1.159 at 256, 1.179 unlimited; a batch whose linking moves 1.1 GB would make a
+    // 64-workgroup launch the bottleneck of a 1.1 ms step).
+    if (any_mapped) {
+      a.grid_limit = 64;
+    } else if (background) {
+      const int64_t bytes = 4 * (a.pos_end - a.pos_begin) * static_cast<int64_t>(row_bytes);
+      a.grid_limit = static_cast<int32_t>(std::max<int64_t>(64, bytes / (5 << 20)));
+    } else {
+      a.grid_limit = 0;
+    }
     MPIC_HIP(ctx, mpic::launch_assemble(c.dtype, a, tab, stream));
   }
   a.grid_limit = 0;
