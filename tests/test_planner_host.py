@@ -20,6 +20,26 @@ def _ctx(hq=4, hkv=2, d=128, dtype=mpic.MPIC_BF16, theta=1e4, page_size=0):
     return mpic.Context(hq, hkv, d, dtype, theta, 0, page_size)
 
 
+def test_header_is_plain_c():
+    """include/mpic.h compiles as C99 (no C++-isms) and the C program links against the library."""
+    import subprocess, tempfile
+    src = os.path.join(ROOT, "tests", "native", "header_is_c.c")
+    with tempfile.TemporaryDirectory() as tmp:
+        exe = os.path.join(tmp, "header_is_c")
+        cmd = ["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-Wno-pedantic", "-I", os.path.join(ROOT, "include"),
+               src, "-o", exe, mpic.lib_path(), "-Wl,-rpath," + os.path.dirname(mpic.lib_path())]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
+    # the header alone, strictly
+    r = subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-x", "c",
+                        os.path.join(ROOT, "include", "mpic.h")], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    header = open(os.path.join(ROOT, "include", "mpic.h")).read()
+    names = set(re.findall(r"\b(mpic_[a-z_]+)\s*\(", header))
+    used = set(re.findall(r"\(void\*\)(mpic_[a-z_]+)", open(src).read()))
+    assert names == used, names ^ used
+
+
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "mpic.h")).read()
     names = sorted(set(re.findall(r"\b(mpic_[a-z_]+)\s*\(", header)))
