@@ -91,6 +91,30 @@ __device__ inline void load4_to_lds_16B(const void* g0, const void* g1, const vo
 // s_waitcnt vmcnt(n) only (expcnt / lgkmcnt fields left at "no wait")
 #define WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
 
+// Combine a value with the one held by lane ^ 32 (the other half of a query column) with
+// v_permlane32_swap (verified: swapping two copies of a register leaves the low half's values
+// in one result and the high half's in the other, in both halves).  A plain cross-lane shuffle
+// would go through the LDS pipeline, whose command queue the fragment reads keep full.
+// (The two results are copied into scalars before they are reinterpreted: a bit cast applied
+// directly to an element of the returned vector reads element 0 for both.)
+struct Halves {
+  float lo, hi;
+};
+__device__ inline Halves split_halves(float x) {
+  const unsigned a = __builtin_bit_cast(unsigned, x);
+  const auto r = __builtin_amdgcn_permlane32_swap(a, a, false, false);
+  const unsigned r0 = r[0], r1 = r[1];
+  return Halves{__builtin_bit_cast(float, r0), __builtin_bit_cast(float, r1)};
+}
+__device__ inline float max_across_halves(float x) {
+  const Halves h = split_halves(x);
+  return fmaxf(h.lo, h.hi);
+}
+__device__ inline float sum_across_halves(float x) {
+  const Halves h = split_halves(x);
+  return h.lo + h.hi;
+}
+
 __device__ inline float wave_min(float x) {
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) x = fminf(x, __shfl_xor(x, off));
@@ -314,7 +338,7 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a) {
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int v = 0; v < 16; ++v) m_blk = fmaxf(m_blk, acc_s[kb][v]);
-    m_blk = fmaxf(m_blk, __shfl_xor(m_blk, 32));
+    m_blk = max_across_halves(m_blk);
     // Lazy rescale: the reference point m_run only moves when some query's block maximum
     // exceeds it by more than kSlack (in log2 units), so probabilities are at most
     // 2^kSlack before normalisation -- exact in the end because numerator and
@@ -404,7 +428,7 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a) {
 #endif
   // ---- epilogue: normalise and store this lane's query column ----
   if (!valid) return;
-  const float l_tot = l_run + __shfl_xor(l_run, 32);
+  const float l_tot = sum_across_halves(l_run);
   if (tile.part >= 0) {
     // piece of a tile cut along the keys: normalised fp32 partial + log-sum-exp for the merge
     // kernel.  A row that lies below key0 saw no key (its registers may hold NaN: selected

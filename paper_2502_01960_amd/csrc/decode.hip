@@ -81,6 +81,30 @@ __device__ inline void wait_loads(int blocks) {
 }
 static_assert(LOADS_PER_BLOCK == 16, "wait_loads spells the count out");
 
+// Combine a value with the one held by lane ^ 32 (the other half of a query column) with
+// v_permlane32_swap (verified: swapping two copies of a register leaves the low half's values
+// in one result and the high half's in the other, in both halves).  A plain cross-lane shuffle
+// would go through the LDS pipeline, whose command queue the fragment reads keep full.
+// (The two results are copied into scalars before they are reinterpreted: a bit cast applied
+// directly to an element of the returned vector reads element 0 for both.)
+struct Halves {
+  float lo, hi;
+};
+__device__ inline Halves split_halves(float x) {
+  const unsigned a = __builtin_bit_cast(unsigned, x);
+  const auto r = __builtin_amdgcn_permlane32_swap(a, a, false, false);
+  const unsigned r0 = r[0], r1 = r[1];
+  return Halves{__builtin_bit_cast(float, r0), __builtin_bit_cast(float, r1)};
+}
+__device__ inline float max_across_halves(float x) {
+  const Halves h = split_halves(x);
+  return fmaxf(h.lo, h.hi);
+}
+__device__ inline float sum_across_halves(float x) {
+  const Halves h = split_halves(x);
+  return h.lo + h.hi;
+}
+
 __global__ __launch_bounds__(THREADS) void decode_bf16_kernel(DecodeArgs a) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const int tid = threadIdx.x;
@@ -211,7 +235,7 @@ __global__ __launch_bounds__(THREADS) void decode_bf16_kernel(DecodeArgs a) {
     float m_blk = -INFINITY;
 #pragma unroll
     for (int v = 0; v < 16; ++v) m_blk = fmaxf(m_blk, acc_s[v]);
-    m_blk = fmaxf(m_blk, __shfl_xor(m_blk, 32));
+    m_blk = max_across_halves(m_blk);
     // lazy rescale: the reference maximum only moves when a block maximum exceeds it by
     // more than kSlack (log2 units); exact because numerator and denominator share it
     if (__builtin_amdgcn_ballot_w64((m_blk - m_run) * scale_log2 > kSlack) != 0) {
@@ -248,7 +272,7 @@ __global__ __launch_bounds__(THREADS) void decode_bf16_kernel(DecodeArgs a) {
   }
 
   // ---- merge the four wavefronts through LDS (the staging areas are free now) ----
-  const float l_wave = l_run + __shfl_xor(l_run, 32);
+  const float l_wave = sum_across_halves(l_run);
   __syncthreads();
   float* m_o = reinterpret_cast<float*>(lds);               // [WAVES][32 columns][D]
   float* m_m = m_o + WAVES * 32 * D;                        // [WAVES][32]
