@@ -219,10 +219,13 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a) {
     blk = blk < n_iter ? blk : n_iter - 1;
     return *reinterpret_cast<const __attribute__((address_space(4))) u32x8_a4*>(off_of + blk * BN + wave * 8);
   };
+  // `ro` holds the offsets of the block whose loads go out next.  It is refilled at the start
+  // of the wave's softmax phase, which touches neither LDS nor scalar memory: the scalar load
+  // shares its counter with the LDS reads and returns out of order, so whatever waits on
+  // that counter next (the first fragment reads of a matrix part, a barrier) waits for it.
   u32x8_a4 ro = fetch_rows(0);
   auto issue_loads = [&](int blk) {
     const u32x8_a4 cur = ro;
-    ro = fetch_rows(blk + 1);
     const uint32_t dst = lds_base + (blk % STAGES) * STAGE_BYTES + wave * 8 * ROW_BYTES;
     // the four loads go out back to back, each from its own address registers
     const uint32_t ra = ld_sub == 0 ? cur[0] : ld_sub == 1 ? cur[1] : ld_sub == 2 ? cur[2] : cur[3];
@@ -250,7 +253,9 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a) {
   WAIT_VMCNT(0);
   __builtin_amdgcn_sched_barrier(0);
   issue_loads(0);
+  ro = fetch_rows(1);
   if (n_iter > 1) issue_loads(1);
+  ro = fetch_rows(2);
 
   // Ping-pong schedule.  The two wavefronts that share a SIMD (w and w+4) belong to
   // different groups and run half a block apart: while one group keeps the matrix
@@ -407,12 +412,14 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a) {
       even_sync(t);
       matrix_part(t);
       __syncthreads();  // odd half step 2t+1
+      ro = fetch_rows(t + 3);
       if (t < n_iter && t * BN <= wave_hi_pos) softmax_block(t);
       PHASE_MARK(6)
     }
   } else {
     for (int t = 0; t <= n_iter; ++t) {
       even_sync(t);
+      ro = fetch_rows(t + 3);
       if (t >= 1 && (t - 1) * BN <= wave_hi_pos) softmax_block(t - 1);
       PHASE_MARK(6)
       __syncthreads();  // odd half step 2t+1
