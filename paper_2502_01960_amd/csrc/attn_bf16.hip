@@ -212,6 +212,8 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a) {
   const uint32_t ld_col = lane & 15;
   const uint32_t ld_k16 = ld_col ^ ld_sub ^ ((wave & 1) << 3);  // ^ (4p): K swizzle = row & 15
   const uint32_t ld_v16 = ld_col ^ (ld_sub << 2);               //          V swizzle = (row & 3) << 2
+  const uint32_t sel0 = ld_sub == 0 ? ~0u : 0u, sel1 = ld_sub == 1 ? ~0u : 0u;
+  const uint32_t sel2 = ld_sub == 2 ? ~0u : 0u, sel3 = ld_sub == 3 ? ~0u : 0u;
   // row offsets of this wave's eight rows of a block: one scalar load, issued one block
   // ahead of its use so that its latency is never waited for
   const int n_iter = (n_keys + BN - 1) / BN;
@@ -228,8 +230,9 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a) {
     const u32x8_a4 cur = ro;
     const uint32_t dst = lds_base + (blk % STAGES) * STAGE_BYTES + wave * 8 * ROW_BYTES;
     // the four loads go out back to back, each from its own address registers
-    const uint32_t ra = ld_sub == 0 ? cur[0] : ld_sub == 1 ? cur[1] : ld_sub == 2 ? cur[2] : cur[3];
-    const uint32_t rb = ld_sub == 0 ? cur[4] : ld_sub == 1 ? cur[5] : ld_sub == 2 ? cur[6] : cur[7];
+    // this lane's row of each group of four, picked with per-lane masks (branch-free)
+    const uint32_t ra = (cur[0] & sel0) | (cur[1] & sel1) | (cur[2] & sel2) | (cur[3] & sel3);
+    const uint32_t rb = (cur[4] & sel0) | (cur[5] & sel1) | (cur[6] & sel2) | (cur[7] & sel3);
     load4_to_lds_16B(kbase + (static_cast<uint64_t>(ra + ld_k16) << 4), vbase + (static_cast<uint64_t>(ra + ld_v16) << 4),
                      kbase + (static_cast<uint64_t>(rb + (ld_k16 ^ 4)) << 4), vbase + (static_cast<uint64_t>(rb + ld_v16) << 4),
                      dst, dst + TILE_BYTES, dst + 4 * ROW_BYTES, dst + TILE_BYTES + 4 * ROW_BYTES);
