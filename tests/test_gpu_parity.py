@@ -522,3 +522,46 @@ def test_calls_can_be_captured_in_a_graph():
         for got, ref in zip((p.k_ctx, p.v_ctx, p.out, p.lse, dec_out), want):
             assert torch.equal(got.view(torch.int16 if got.dtype == torch.bfloat16 else torch.int32),
                                ref.view(torch.int16 if ref.dtype == torch.bfloat16 else torch.int32))
+
+
+def test_random_feature_combinations():
+    """Seeded random mixes of everything the library takes: batch sizes, head groupings from
+    multi-head to a group of 32, first-k and listed recompute sets, contiguous and paged with
+    several page sizes, both rotary pairings, fresh rows handed over rotated or not, chunks on the
+    device, staged from the host or read in place; link, attention and the decode step against
+    the oracle for every mix."""
+    import dataclasses
+    rng = np.random.default_rng(424242)
+    groupings = [(32, 1), (16, 1), (32, 32), (28, 4), (8, 8), (12, 3)]
+    for case in range(12):
+        hq, hkv = groupings[case % len(groupings)]
+        n_src = int(rng.integers(1, 5))
+        src_len = [int(rng.integers(1, 400)) for _ in range(n_src)]
+        reqs = []
+        for _ in range(int(rng.integers(1, 7))):
+            segs = []
+            for _ in range(int(rng.integers(1, 7))):
+                if rng.random() < 0.4:
+                    segs.append(("text", int(rng.integers(0, 80))))
+                else:
+                    s_ = int(rng.integers(0, n_src))
+                    pick = rng.random()
+                    if pick < 0.35:
+                        k = sorted(set(rng.integers(0, src_len[s_], size=int(rng.integers(0, 1 + src_len[s_] // 3))).tolist()))
+                    else:
+                        k = [None, 0, 1, 33, 1000][int(rng.integers(0, 5))]
+                    segs.append(("chunk", s_, src_len[s_], k))
+            reqs.append(segs)
+        paged = [0, 16, 32, 1][case % 4]
+        p = _custom(reqs, n_src, src_len, int(rng.integers(0, 70)), paged=paged)
+        p.sh = dataclasses.replace(p.sh, n_q_heads=hq, n_kv_heads=hkv)
+        p.pre_rope, p.interleaved = bool(case % 2), bool((case // 2) % 2)
+        p.host_mode = mpic.MPIC_SRC_HOST_MAPPED if case % 3 == 0 else mpic.MPIC_SRC_HOST_STAGED
+        p.chunks = {s_: workloads.gen_chunk(p.sh, 100 + case, s_, src_len[s_]) for s_ in p.chunks}
+        q_off = p.oplan["q_off"]
+        fresh = [workloads.gen_fresh(p.sh, 100 + case, b, int(q_off[b + 1] - q_off[b])) for b in range(len(reqs))]
+        p.q = torch.cat([f[0] for f in fresh]); p.fresh_k = torch.cat([f[1] for f in fresh]); p.fresh_v = torch.cat([f[2] for f in fresh])
+        _run_full(p, host_sourced=case % 3 != 1)
+        if p.pre_rope:
+            continue      # the decode step takes rotated inputs; its oracle check links with rotated fresh keys
+        _check_decode(p, bool(case % 2 == 0))
