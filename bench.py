@@ -32,7 +32,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=60)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=3, help="workload id (BASELINE.json configs, 1-based)")
+    ap.add_argument("--config", type=int, default=3, help="workload id (1-5, see workloads/)")
     ap.add_argument("--layers", type=int, default=4, help="distinct layer input sets the steps cycle over")
     ap.add_argument("--fresh-pre-rope", action="store_true",
                     help="hand fresh Q/K over before positional embedding (the library rotates them)")
