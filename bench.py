@@ -368,7 +368,9 @@ def main():
                    "chunks": "HBM-resident", "plan": "built once per batch, reused by every step",
                    "overlap": "cached rows of step i+1 linked on a second stream while step i attends"},
         "roofline": {"bound": "mfma", "achieved": round(attn_tflops, 3), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 5), "traffic": traffic,
+                     "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 5),
+                     # HBM-side bytes per launch (FETCH_SIZE + WRITE_SIZE, scaled by the copy calibration)
+                     "traffic": traffic["total_bytes"] if traffic else None, "traffic_detail": traffic,
                      "kernel": "attn_bf16_kernel", "avg_launch_ms": round(attn_ms, 5)},
         "cpu_baseline": cpu,
         "attention": {"ms": round(attn_ms, 5), "TFLOPs": round(attn_tflops, 3),
