@@ -25,6 +25,14 @@ Pin status of every function (see tests/test_oracle_*.py):
   select.k_distance      pinned: loop transcription, closed forms (identical caches, a
                          constant offset), metric laws
   select.top_tokens / top_counts   pinned: hand-ranked example with ties, counts add up
+  store.checksum / write_chunk_file / read_chunk_file   (this build's own encoding) pinned:
+                         unbounded-integer evaluation, every single-byte change of a small
+                         buffer and file is seen, hand-decoded header
+  store.ChunkStore       pinned: hand-run sequence of put / move / expire / lookup
+  pipeline.plan_with_lookup / prefill_layers   pinned: a missing or failed cache gives the
+                         plan of a text span of the same length, all caches missing is
+                         library SDPA causal prefill of every layer, layers read their own
+                         slice
 The paper prints no worked numeric example of this path, so beyond those pins the
 values are unpinned by the paper itself.
 """
@@ -34,3 +42,5 @@ from .link import link_kv, position_fresh, to_slots     # noqa: F401
 from .attend import attend, attend_loops  # noqa: F401
 from .decode import decode_attend       # noqa: F401
 from .select import k_distance, top_tokens, top_counts  # noqa: F401
+from .store import ChunkStore            # noqa: F401
+from .pipeline import plan_with_lookup, prefill_layers  # noqa: F401
