@@ -39,13 +39,17 @@ extern "C" {
 
 typedef struct mpic_ctx mpic_ctx;   /* opaque: configuration, side stream, events, staging */
 typedef struct mpic_plan mpic_plan; /* opaque: host and device copies of the integer plan   */
+typedef struct mpic_store mpic_store; /* opaque: library of stored chunk caches in three tiers */
 
 typedef enum mpic_status {
   MPIC_OK = 0,
   MPIC_ERR_INVALID = -1,     /* an argument violates the documented contract   */
   MPIC_ERR_UNSUPPORTED = -2, /* valid request that this build has no kernel for */
   MPIC_ERR_OOM = -3,         /* host or device allocation failed                */
-  MPIC_ERR_HIP = -4          /* a HIP runtime call failed (see mpic_last_error) */
+  MPIC_ERR_HIP = -4,         /* a HIP runtime call failed (see mpic_last_error) */
+  MPIC_ERR_IO = -5,          /* a file of the disk tier could not be written     */
+  MPIC_ERR_CACHE_MISS = -6   /* a stored cache the plan reads is missing or its  */
+                             /* load failed: plan those chunks as recomputed     */
 } mpic_status;
 
 typedef enum mpic_dtype { MPIC_F32 = 0, MPIC_BF16 = 1 } mpic_dtype;
@@ -333,6 +337,121 @@ int mpic_k_distance(mpic_ctx* ctx, const void* k_a, const void* k_b, int64_t n_t
  * Errors: MPIC_ERR_INVALID, MPIC_ERR_OOM.
  */
 int mpic_rank_tokens(const float* dist, int64_t n_tokens, int64_t n_top, int32_t* idx);
+
+/* ---- library of stored caches and the layer pipeline (Sec. 3.1 items 2-3, Sec. 3.2, Fig. 6) ----
+ *
+ * A store keeps the KV cache of uploaded items, all layers of an item under one 64-bit
+ * id, in one of three places: GPU memory, pinned CPU memory, or a file (Sec. 3.2 names
+ * the three).  With a disk directory every stored cache also has its file, as in the
+ * serving workflow of Sec. 3.1 (kept for serving, copied to disk, deleted on expiry).
+ * A cache is bytes: what comes back is what went in, or the cache is reported missing.
+ *
+ * File <disk_dir>/<id as 16 hex digits>.mpickv, little endian:
+ *     0  "MPICKV01"    8  u64 id      16  i32 len   20  i32 n_layers   24  i32 n_kv_heads
+ *    28  i32 head_dim  32  i32 dtype  36  i32 0     40  u64 block_bytes = len*Hkv*D*elem
+ *    48  u64 payload_off (multiple of 4096)          56  u64 checksum of bytes [0, 56)
+ *    64  u64 x 2 x n_layers: checksum of the K block and of the V block of each layer
+ *    payload_off: K block of layer 0, V block of layer 0, K block of layer 1, ...
+ * checksum of n 8-byte words w_i: (n + sum_i w_i * P^(i+1)) mod 2^64, P = 0x9E3779B97F4A7C15.
+ *
+ * A store and the context it was made from are used by one host thread at a time; the
+ * store's own reader threads are internal.  The caller must not move, replace, expire
+ * or destroy a cache while GPU work that reads it is still enqueued.
+ */
+enum { MPIC_TIER_MISSING = 0, MPIC_TIER_HBM = 1, MPIC_TIER_HOST = 2, MPIC_TIER_DISK = 3 };
+
+/*
+ * Create a store for caches of ctx's shape (Hkv, D, dtype) with n_layers layers each.
+ * disk_dir: directory of the disk tier (must exist), or NULL for none; files already
+ * there whose header fits the shape are registered in tier DISK (a restarted server
+ * finds its caches; they do not expire until put again).  io_threads: reader threads
+ * of the disk tier (<= 0: 4).  Host only; GPU and pinned memory are touched by put /
+ * move into those tiers.
+ * Errors: INVALID (null pointer, n_layers < 1, directory missing), OOM.
+ */
+int mpic_store_create(mpic_ctx* ctx, int32_t n_layers, const char* disk_dir, int32_t io_threads,
+                      mpic_store** out);
+
+/* Destroy a store (before its context): waits for the device, frees both memory tiers,
+ * keeps the files.  NULL is allowed. */
+void mpic_store_destroy(mpic_store* store);
+
+/*
+ * Store (or replace) the cache of item `id`: k, v host pointers, [n_layers][len][Hkv][D],
+ * copied before the call returns.  tier: where it is kept (HBM / HOST / DISK).  With a
+ * disk tier the file is written in every case.  expires_at: time (caller's unit) at
+ * which mpic_store_expire deletes it; < 0 = never.
+ * Errors: INVALID (null, len < 1, unknown tier, DISK without disk_dir), OOM (device or
+ * pinned allocation), IO (file could not be written; the store is unchanged), HIP.
+ */
+int mpic_store_put(mpic_store* store, uint64_t id, int32_t len, const void* k, const void* v,
+                   int32_t tier, int64_t expires_at);
+
+/*
+ * Move a cache to another tier (promotion before use, demotion under memory pressure).
+ * Into DISK the memory copy is freed (needs the disk tier); out of DISK the file is read
+ * and verified.  Waits for the device before freeing memory.
+ * Errors: INVALID (unknown id or tier), CACHE_MISS (the file is gone or damaged; the
+ * cache is dropped from the store), OOM, HIP.
+ */
+int mpic_store_move(mpic_store* store, uint64_t id, int32_t tier);
+
+/* Delete every cache with 0 <= expires_at <= now from all tiers, its file included
+ * (Sec. 3.1: deleted after the expiration of its timeframe).  n_removed may be NULL. */
+int mpic_store_expire(mpic_store* store, int64_t now, int32_t* n_removed);
+
+/* Delete one cache from all tiers; unknown ids are ignored. */
+int mpic_store_drop(mpic_store* store, uint64_t id);
+
+/*
+ * Where are these caches (Sec. 3.2: the lookup at the beginning of processing)?  tier[i]
+ * receives MPIC_TIER_*, len[i] (may be NULL) the token count or 0.  A cache of tier DISK
+ * whose file has disappeared or changed size is dropped and reported missing.
+ */
+int mpic_store_lookup(mpic_store* store, const uint64_t* ids, int32_t n, int32_t* tier, int32_t* len);
+
+/*
+ * Pointers to one layer of a cache held in HBM or HOST, for use with mpic_assemble_kv
+ * (on_host is set to MPIC_SRC_DEVICE or MPIC_SRC_HOST_STAGED; HOST memory comes from
+ * hipHostMalloc, so MPIC_SRC_HOST_MAPPED may be chosen instead).  Valid until the cache
+ * is moved, replaced, expired or the store destroyed.
+ * Errors: INVALID (unknown id, layer out of range, cache is in tier DISK).
+ */
+int mpic_store_layer(mpic_store* store, uint64_t id, int32_t layer, mpic_chunk_src* out);
+
+/*
+ * Selective-recompute prefill of n_layers layers of one batch, caches fetched from the
+ * store while earlier layers compute (Sec. 3.2 / Fig. 6: transfer and computation run
+ * concurrently; layer by layer, as the layer-wise transfer that Sec. 3.2 calls orthogonal).
+ * ids[s] = store id of chunk source s of the plan (n_srcs entries; sources the plan does
+ * not read may carry any id).  Per layer l the call does what mpic_assemble_kv followed
+ * by mpic_selective_attn do with that layer's slices:
+ *   fresh_q[l], fresh_k[l], fresh_v[l]  device, [n_fresh_rows][H][D]
+ *   k_ctx[l], v_ctx[l]                  device, n_ctx_slots rows; the same buffer may be
+ *                                       given to several layers (the library orders the
+ *                                       linking of a later layer after the attention of
+ *                                       the earlier one), distinct buffers let linking
+ *                                       run further ahead
+ *   out[l], lse[l]                      device; lse or lse[l] may be NULL
+ * Schedule: the stored part of layer l is linked on a library stream (host and disk
+ * tiers: staged copies on the side stream; disk: read and verified by the reader
+ * threads into a ring of pinned buffers, one layer ahead of the copies), fresh rows and
+ * attention run on `stream`, joined by events.  The call returns when everything is
+ * enqueued; the host thread waits only for file reads.
+ * failed: [n_srcs] or NULL; on MPIC_ERR_CACHE_MISS failed[s] = 1 for every source whose
+ * cache is missing from the store or failed to load.  Missing caches and unreadable or
+ * mis-sized files are found before anything is enqueued; a damaged block is found when
+ * its layer is read: the call then stops enqueuing, earlier layers still complete, and
+ * the cache is dropped from the store.  In both cases the caller plans those chunks
+ * with k >= len and calls again (Sec. 3.2: fall back to computing without the cache).
+ * Errors: INVALID (as mpic_assemble_kv / mpic_selective_attn; store of another context;
+ * n_layers beyond the store's), CACHE_MISS, OOM, HIP.
+ */
+int mpic_prefill_layers(mpic_ctx* ctx, mpic_plan* plan, mpic_store* store, const uint64_t* ids,
+                        int32_t n_srcs, int32_t n_layers, const void* const* fresh_q,
+                        const void* const* fresh_k, const void* const* fresh_v, int64_t n_fresh_rows,
+                        void* const* k_ctx, void* const* v_ctx, int64_t n_ctx_slots, double softmax_scale,
+                        void* const* out, float* const* lse, void* stream, int32_t* failed);
 
 /* Static description of a status code. */
 const char* mpic_strerror(int status);

@@ -86,6 +86,27 @@ def load_library():
     lib.mpic_k_distance.restype = C.c_int
     lib.mpic_rank_tokens.argtypes = [C.POINTER(C.c_float), i64, i64, C.POINTER(i32)]
     lib.mpic_rank_tokens.restype = C.c_int
+    u64 = C.c_uint64
+    lib.mpic_store_create.argtypes = [vp, i32, C.c_char_p, i32, C.POINTER(vp)]
+    lib.mpic_store_create.restype = C.c_int
+    lib.mpic_store_destroy.argtypes = [vp]
+    lib.mpic_store_destroy.restype = None
+    lib.mpic_store_put.argtypes = [vp, u64, i32, vp, vp, i32, i64]
+    lib.mpic_store_put.restype = C.c_int
+    lib.mpic_store_move.argtypes = [vp, u64, i32]
+    lib.mpic_store_move.restype = C.c_int
+    lib.mpic_store_expire.argtypes = [vp, i64, C.POINTER(i32)]
+    lib.mpic_store_expire.restype = C.c_int
+    lib.mpic_store_drop.argtypes = [vp, u64]
+    lib.mpic_store_drop.restype = C.c_int
+    lib.mpic_store_lookup.argtypes = [vp, C.POINTER(u64), i32, C.POINTER(i32), C.POINTER(i32)]
+    lib.mpic_store_lookup.restype = C.c_int
+    lib.mpic_store_layer.argtypes = [vp, u64, i32, C.POINTER(_ChunkSrc)]
+    lib.mpic_store_layer.restype = C.c_int
+    lib.mpic_prefill_layers.argtypes = [vp, vp, vp, C.POINTER(u64), i32, i32, C.POINTER(vp), C.POINTER(vp),
+                                        C.POINTER(vp), i64, C.POINTER(vp), C.POINTER(vp), i64, C.c_double,
+                                        C.POINTER(vp), C.POINTER(vp), vp, C.POINTER(i32)]
+    lib.mpic_prefill_layers.restype = C.c_int
     lib.mpic_strerror.argtypes = [C.c_int]
     lib.mpic_strerror.restype = C.c_char_p
     lib.mpic_last_error.argtypes = [vp]
@@ -228,7 +249,8 @@ MPIC_SRC_DEVICE, MPIC_SRC_HOST_STAGED, MPIC_SRC_HOST_MAPPED = 0, 1, 2
 def mpic_assemble_kv(ctx, plan, srcs, fresh_k, fresh_v, k_ctx, v_ctx, stream=None, host_mode=MPIC_SRC_HOST_STAGED):
     """srcs: list of (k_tensor, v_tensor) per source id; a device tensor is read in place, a
     pinned CPU tensor is staged by the library (host_mode = MPIC_SRC_HOST_STAGED) or read in
-    place by the kernel (MPIC_SRC_HOST_MAPPED).  Tensors are torch tensors."""
+    place by the kernel (MPIC_SRC_HOST_MAPPED).  Tensors are torch tensors.  An entry may also
+    be the 4-tuple (k address, v address, len, on_host) that mpic_store_layer returns."""
     mpic_assemble_kv_parts(ctx, plan, srcs, fresh_k, fresh_v, k_ctx, v_ctx,
                            MPIC_PART_CACHED | MPIC_PART_FRESH, stream, host_mode)
 
@@ -237,7 +259,11 @@ def mpic_assemble_kv_parts(ctx, plan, srcs, fresh_k, fresh_v, k_ctx, v_ctx, part
                            host_mode=MPIC_SRC_HOST_STAGED):
     srcs = srcs or []
     arr = (_ChunkSrc * max(1, len(srcs)))()
-    for i, (k, v) in enumerate(srcs):
+    for i, src in enumerate(srcs):
+        if len(src) == 4:      # (k address, v address, len, on_host) as mpic_store_layer returns them
+            arr[i] = _ChunkSrc(*src)
+            continue
+        k, v = src
         if k is None:
             arr[i] = _ChunkSrc(None, None, 0, 0)
             continue
@@ -282,6 +308,83 @@ def mpic_rank_tokens(dist, n_top):
     return out
 
 
+MPIC_TIER_MISSING, MPIC_TIER_HBM, MPIC_TIER_HOST, MPIC_TIER_DISK = 0, 1, 2, 3
+MPIC_ERR_IO, MPIC_ERR_CACHE_MISS = -5, -6
+
+
+def mpic_store_create(ctx, n_layers, disk_dir=None, io_threads=0):
+    h = C.c_void_p()
+    d = None if disk_dir is None else str(disk_dir).encode()
+    _check(load_library().mpic_store_create(ctx, int(n_layers), d, int(io_threads), C.byref(h)), ctx)
+    return h
+
+
+def mpic_store_destroy(store):
+    load_library().mpic_store_destroy(store)
+
+
+def mpic_store_put(ctx, store, chunk_id, k, v, tier, expires_at=-1):
+    """k, v: contiguous host arrays or CPU tensors [n_layers][len][Hkv][D] of the storage type."""
+    def addr(x):
+        return x.data_ptr() if hasattr(x, "data_ptr") else x.ctypes.data
+    _check(load_library().mpic_store_put(store, int(chunk_id), int(k.shape[1]), C.c_void_p(addr(k)),
+                                         C.c_void_p(addr(v)), int(tier), int(expires_at)), ctx)
+
+
+def mpic_store_move(ctx, store, chunk_id, tier):
+    _check(load_library().mpic_store_move(store, int(chunk_id), int(tier)), ctx)
+
+
+def mpic_store_expire(ctx, store, now):
+    n = C.c_int32()
+    _check(load_library().mpic_store_expire(store, int(now), C.byref(n)), ctx)
+    return n.value
+
+
+def mpic_store_drop(ctx, store, chunk_id):
+    _check(load_library().mpic_store_drop(store, int(chunk_id)), ctx)
+
+
+def mpic_store_lookup(ctx, store, ids):
+    """Returns (tiers, lens) as lists."""
+    n = len(ids)
+    a = (C.c_uint64 * max(1, n))(*[int(i) for i in ids])
+    tier, length = (C.c_int32 * max(1, n))(), (C.c_int32 * max(1, n))()
+    _check(load_library().mpic_store_lookup(store, a, n, tier, length), ctx)
+    return list(tier[:n]), list(length[:n])
+
+
+def mpic_store_layer(ctx, store, chunk_id, layer):
+    """Returns (k address, v address, len, on_host) of one layer of a cache held in memory."""
+    src = _ChunkSrc()
+    _check(load_library().mpic_store_layer(store, int(chunk_id), int(layer), C.byref(src)), ctx)
+    return src.k, src.v, src.len, src.on_host
+
+
+def mpic_prefill_layers(ctx, plan, store, ids, fresh_q, fresh_k, fresh_v, k_ctx, v_ctx, softmax_scale, out,
+                        lse=None, stream=None):
+    """Per-layer lists of torch device tensors.  Returns None, or on a cache miss the list of
+    source indices whose cache is missing or failed to load (MPIC_ERR_CACHE_MISS)."""
+    n_layers = len(fresh_q)
+    vp = C.c_void_p
+
+    def ptrs(ts):
+        return (vp * max(1, n_layers))(*[None if t is None else t.data_ptr() for t in ts])
+    n_srcs = len(ids)
+    a = (C.c_uint64 * max(1, n_srcs))(*[int(i) for i in ids])
+    failed = (C.c_int32 * max(1, n_srcs))()
+    n_fresh = fresh_q[0].shape[0] if n_layers else 0
+    n_slots = k_ctx[0].shape[0] if n_layers else 0
+    rc = load_library().mpic_prefill_layers(ctx, plan, store, a, n_srcs, n_layers, ptrs(fresh_q), ptrs(fresh_k),
+                                            ptrs(fresh_v), n_fresh, ptrs(k_ctx), ptrs(v_ctx), n_slots,
+                                            float(softmax_scale), ptrs(out), None if lse is None else ptrs(lse),
+                                            _stream(stream), failed)
+    if rc == MPIC_ERR_CACHE_MISS:
+        return [s for s in range(n_srcs) if failed[s]]
+    _check(rc, ctx)
+    return None
+
+
 # ---------------------------------------------------------------- handle owners
 class Context:
     def __init__(self, n_q_heads, n_kv_heads, head_dim, dtype, rope_theta, rope_interleaved=0, page_size=0,
@@ -323,6 +426,43 @@ class Plan:
     def close(self):
         if self.handle is not None:
             mpic_plan_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Store:
+    """Owner of an mpic_store handle (destroy it before its Context)."""
+
+    def __init__(self, ctx: Context, n_layers, disk_dir=None, io_threads=0):
+        self.ctx = ctx
+        self.handle = mpic_store_create(ctx.handle, n_layers, disk_dir, io_threads)
+
+    def put(self, chunk_id, k, v, tier, expires_at=-1):
+        mpic_store_put(self.ctx.handle, self.handle, chunk_id, k, v, tier, expires_at)
+
+    def move(self, chunk_id, tier):
+        mpic_store_move(self.ctx.handle, self.handle, chunk_id, tier)
+
+    def expire(self, now):
+        return mpic_store_expire(self.ctx.handle, self.handle, now)
+
+    def drop(self, chunk_id):
+        mpic_store_drop(self.ctx.handle, self.handle, chunk_id)
+
+    def lookup(self, ids):
+        return mpic_store_lookup(self.ctx.handle, self.handle, ids)
+
+    def layer(self, chunk_id, layer):
+        return mpic_store_layer(self.ctx.handle, self.handle, chunk_id, layer)
+
+    def close(self):
+        if self.handle is not None:
+            mpic_store_destroy(self.handle)
             self.handle = None
 
     def __del__(self):

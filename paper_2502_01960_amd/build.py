@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmpic.so")
-SOURCES = ["plan.cpp", "api.hip", "assemble.hip", "attn_f32.hip", "attn_bf16.hip", "decode.hip", "select.hip"]
+SOURCES = ["plan.cpp", "api.hip", "assemble.hip", "attn_f32.hip", "attn_bf16.hip", "decode.hip", "select.hip", "store.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed fp32 instructions are switched off for device code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

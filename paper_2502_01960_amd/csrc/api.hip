@@ -9,7 +9,6 @@
 #include "common.h"
 
 namespace mpic {
-namespace {
 
 int bind_device(mpic_ctx* ctx) {
   int dev = -1;
@@ -24,6 +23,8 @@ int bind_device(mpic_ctx* ctx) {
   }
   return MPIC_OK;
 }
+
+namespace {
 
 constexpr size_t kTablePad = 128;
 
@@ -127,6 +128,11 @@ extern "C" void mpic_destroy(mpic_ctx* ctx) {
       (void)hipStreamSynchronize(ctx->side_stream);
       (void)hipStreamDestroy(ctx->side_stream);
     }
+    if (ctx->link_stream) {
+      (void)hipStreamSynchronize(ctx->link_stream);
+      (void)hipStreamDestroy(ctx->link_stream);
+    }
+    for (hipEvent_t ev : ctx->ev_layer) (void)hipEventDestroy(ev);
     for (hipEvent_t ev : ctx->ev_done)
       if (ev) (void)hipEventDestroy(ev);
     for (hipEvent_t ev : ctx->ev_copy) (void)hipEventDestroy(ev);
@@ -159,7 +165,7 @@ extern "C" int mpic_assemble_kv(mpic_ctx* ctx, mpic_plan* plan, const mpic_chunk
                                 n_ctx_slots, MPIC_PART_CACHED | MPIC_PART_FRESH, stream_);
 }
 
-static int assemble_kv_parts_impl(mpic_ctx* ctx, mpic_plan* plan, const mpic_chunk_src* srcs,
+int mpic::assemble_parts(mpic_ctx* ctx, mpic_plan* plan, const mpic_chunk_src* srcs,
                                   int32_t n_srcs, const void* fresh_k, const void* fresh_v,
                                   int64_t n_fresh_rows, void* k_ctx, void* v_ctx,
                                   int64_t n_ctx_slots, uint32_t parts, void* stream_) {
@@ -372,7 +378,7 @@ static int assemble_kv_parts_impl(mpic_ctx* ctx, mpic_plan* plan, const mpic_chu
   return MPIC_OK;
 }
 
-static int selective_attn_impl(mpic_ctx* ctx, mpic_plan* plan, const void* fresh_q,
+int mpic::attend(mpic_ctx* ctx, mpic_plan* plan, const void* fresh_q,
                                int64_t n_fresh_rows, const void* k_ctx, const void* v_ctx,
                                int64_t n_ctx_slots, double softmax_scale, void* out, float* lse,
                                void* stream_) {
@@ -531,7 +537,7 @@ extern "C" int mpic_assemble_kv_parts(mpic_ctx* ctx, mpic_plan* plan, const mpic
                                       int32_t n_srcs, const void* fresh_k, const void* fresh_v,
                                       int64_t n_fresh_rows, void* k_ctx, void* v_ctx,
                                       int64_t n_ctx_slots, uint32_t parts, void* stream) {
-  MPIC_GUARDED(ctx, assemble_kv_parts_impl(ctx, plan, srcs, n_srcs, fresh_k, fresh_v, n_fresh_rows, k_ctx, v_ctx,
+  MPIC_GUARDED(ctx, mpic::assemble_parts(ctx, plan, srcs, n_srcs, fresh_k, fresh_v, n_fresh_rows, k_ctx, v_ctx,
                                            n_ctx_slots, parts, stream))
 }
 
@@ -539,7 +545,7 @@ extern "C" int mpic_selective_attn(mpic_ctx* ctx, mpic_plan* plan, const void* f
                                    int64_t n_fresh_rows, const void* k_ctx, const void* v_ctx,
                                    int64_t n_ctx_slots, double softmax_scale, void* out, float* lse,
                                    void* stream) {
-  MPIC_GUARDED(ctx, selective_attn_impl(ctx, plan, fresh_q, n_fresh_rows, k_ctx, v_ctx, n_ctx_slots, softmax_scale,
+  MPIC_GUARDED(ctx, mpic::attend(ctx, plan, fresh_q, n_fresh_rows, k_ctx, v_ctx, n_ctx_slots, softmax_scale,
                                         out, lse, stream))
 }
 

@@ -71,6 +71,10 @@ struct mpic_ctx {
   bool ev_done_valid[2] = {false, false};
   int next_staging = 0;
   std::vector<hipEvent_t> ev_copy;             // one per transfer group
+  // layer pipeline: stream on which stored rows are linked ahead of the computation, and the
+  // events that order it against the caller's stream (two per layer in flight)
+  hipStream_t link_stream = nullptr;
+  std::vector<hipEvent_t> ev_layer;
   // partial results of the decode step (one per key split), grown on demand
   void* decode_ws = nullptr;
   size_t decode_ws_bytes = 0;
@@ -108,6 +112,17 @@ int fail_hip(mpic_ctx* ctx, hipError_t e, const char* what);
     hipError_t e_ = (call);                                  \
     if (e_ != hipSuccess) return mpic::fail_hip(ctx, e_, #call); \
   } while (0)
+
+// Implementations behind mpic_assemble_kv_parts / mpic_selective_attn (same arguments and
+// checks); they may throw std::bad_alloc, which the extern "C" entry points turn into
+// MPIC_ERR_OOM.  bind_device ties the context to the current GPU on first use.
+int bind_device(mpic_ctx* ctx);
+int assemble_parts(mpic_ctx* ctx, mpic_plan* plan, const mpic_chunk_src* srcs, int32_t n_srcs,
+                   const void* fresh_k, const void* fresh_v, int64_t n_fresh_rows, void* k_ctx,
+                   void* v_ctx, int64_t n_ctx_slots, uint32_t parts, void* stream);
+int attend(mpic_ctx* ctx, mpic_plan* plan, const void* fresh_q, int64_t n_fresh_rows,
+           const void* k_ctx, const void* v_ctx, int64_t n_ctx_slots, double softmax_scale, void* out,
+           float* lse, void* stream);
 
 // Rows of the attention tile handled by one workgroup of the bf16 kernel.
 constexpr int kAttnTileRows = 256;

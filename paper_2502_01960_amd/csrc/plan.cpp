@@ -566,6 +566,8 @@ extern "C" const char* mpic_strerror(int status) {
     case MPIC_ERR_UNSUPPORTED: return "unsupported configuration";
     case MPIC_ERR_OOM: return "out of memory";
     case MPIC_ERR_HIP: return "HIP runtime error";
+    case MPIC_ERR_IO: return "file of the disk tier could not be written";
+    case MPIC_ERR_CACHE_MISS: return "stored cache missing or failed to load";
     default: return "unknown status";
   }
 }

@@ -138,3 +138,105 @@ def assert_f32_close(got, ref, what, rel=1e-5):
     rms = np.sqrt((ref ** 2).mean())
     assert e.max() <= rel * scale, f"{what}: max err {e.max():.3e} vs {rel * scale:.3e}"
     assert (e <= rel * np.abs(ref) + rel * rms).all(), f"{what}: element-wise bound violated"
+
+
+class LayeredProblem:
+    """Several layers of one batch, cached chunks kept in a store (library on the GPU side,
+    oracle.store.ChunkStore on the oracle side, both filled with the same seeded bytes)."""
+
+    def __init__(self, cfg_id, n_layers, tiers, disk_dir, *, k=None, paged=None, io_threads=0, id_base=1000,
+                 **layout_kw):
+        from oracle.store import ChunkStore
+        self.sh = sh = workloads.shape(cfg_id)
+        self.n_layers = n_layers
+        self.k = sh.default_k if k is None else k
+        self.requests, self.n_src, self.src_len = workloads.layout(cfg_id, **layout_kw)
+        self.page_size = sh.page_size if paged is None else paged
+        lens = [workloads.request_len(r) for r in self.requests]
+        if self.page_size:
+            self.page_tables, self.n_pool_pages = workloads.gen_page_tables(sh, lens, self.page_size)
+            self.n_slots = self.n_pool_pages * self.page_size
+        else:
+            self.page_tables, self.n_pool_pages = None, 0
+            self.n_slots = sum(lens)
+        self.ids = [id_base + s for s in range(self.n_src)]
+        dt = mpic.MPIC_F32 if sh.dtype == "f32" else mpic.MPIC_BF16
+        self.ctx = mpic.Context(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, dt, sh.rope_theta, 0, self.page_size, 0)
+        self.store = mpic.Store(self.ctx, n_layers, disk_dir, io_threads)
+        self.model = ChunkStore()
+        self.raw = {}
+        for s in range(self.n_src):
+            layers = [workloads.gen_chunk(sh, l, s, self.src_len[s]) for l in range(n_layers)]
+            kk = torch.stack([x[0] for x in layers]).contiguous()
+            vv = torch.stack([x[1] for x in layers]).contiguous()
+            tier = tiers[s % len(tiers)]
+            self.store.put(self.ids[s], kk, vv, tier)
+            self.model.put(self.ids[s], kk.to(torch.float64).numpy(), vv.to(torch.float64).numpy(), tier)
+            self.raw[s] = (kk, vv)
+
+    def plan_for(self, missing=()):
+        """Library plan and oracle plan with the sources in `missing` recomputed in full."""
+        from oracle.pipeline import plan_with_lookup
+        failed = {self.ids[s] for s in missing}
+        self.oplan, reqs = plan_with_lookup(self.requests, self.ids, self.k, self.model, self.page_size,
+                                            self.page_tables, failed=failed)
+        self.plan = mpic.Plan(self.ctx, reqs, self.k, self.page_tables, self.n_pool_pages)
+        for f in ("q_pos", "slot_map", "src_inst", "src_row", "dst_slot"):
+            assert np.array_equal(self.plan.get(f), self.oplan[f]), f
+        q_off = self.oplan["q_off"]
+        self.fresh = []
+        for l in range(self.n_layers):
+            rows = [workloads.gen_fresh(self.sh, l, b, int(q_off[b + 1] - q_off[b])) for b in range(len(reqs))]
+            self.fresh.append(tuple(torch.cat([r[i] for r in rows]) for i in range(3)))
+
+    def gpu_run(self, shared_buffers=False, lse=True):
+        """One mpic_prefill_layers call; returns its list of failed sources (None = all fine)."""
+        dev = torch.device("cuda:0")
+        sh, L = self.sh, self.n_layers
+        shape = (self.n_slots, sh.n_kv_heads, sh.head_dim)
+        nan = lambda shp, dt: torch.full(shp, float("nan"), dtype=dt, device=dev)
+        n_buf = 1 if shared_buffers else L
+        kb = [nan(shape, sh.torch_dtype) for _ in range(n_buf)]
+        vb = [nan(shape, sh.torch_dtype) for _ in range(n_buf)]
+        self.k_ctx = [kb[l % n_buf] for l in range(L)]
+        self.v_ctx = [vb[l % n_buf] for l in range(L)]
+        self.d_fresh = [tuple(t.to(dev) for t in f) for f in self.fresh]
+        self.out = [nan(tuple(f[0].shape), sh.torch_dtype) for f in self.fresh]
+        self.lse = [nan(tuple(f[0].shape[:2]), torch.float32) for f in self.fresh] if lse else None
+        failed = mpic.mpic_prefill_layers(self.ctx.handle, self.plan.handle, self.store.handle, self.ids,
+                                          [f[0] for f in self.d_fresh], [f[1] for f in self.d_fresh],
+                                          [f[2] for f in self.d_fresh], self.k_ctx, self.v_ctx,
+                                          sh.softmax_scale, self.out, self.lse)
+        torch.cuda.synchronize()
+        return failed
+
+    def oracle_run(self, rows=None):
+        from oracle.pipeline import prefill_layers
+        f64 = lambda t: t.to(torch.float64).numpy()
+        return prefill_layers(self.oplan, self.ids, self.model, self.n_layers,
+                              lambda l: tuple(f64(t) for t in self.fresh[l]), self.sh.rope_theta,
+                              self.sh.softmax_scale, rows=rows)
+
+    def check(self, ref, layers=None, kv_layers=None):
+        """Outputs of `layers` and linked contexts of `kv_layers` against the oracle's."""
+        close = assert_f32_close if self.sh.dtype == "f32" else assert_bf16_close
+        slots = torch.from_numpy(self.oplan["dst_slot"].astype(np.int64)).to(self.k_ctx[0].device)
+        for l in (range(self.n_layers) if layers is None else layers):
+            K, V, O, lse = ref[l]
+            got = self.out[l].to(torch.float64).cpu().numpy()
+            seen = ~np.isnan(O)
+            assert not np.isnan(got).any(), "layer %d: output rows left unwritten" % l
+            close(got[seen], O[seen], "layer %d attention output" % l)
+            if self.lse is not None:
+                g = self.lse[l].to(torch.float64).cpu().numpy()
+                seen_l = ~np.isnan(lse)
+                assert np.abs(g[seen_l] - lse[seen_l]).max() < (1e-4 if self.sh.dtype == "f32" else 2e-2)
+        for l in (range(self.n_layers) if kv_layers is None else kv_layers):
+            K, V, O, lse = ref[l]
+            assert np.array_equal(self.v_ctx[l][slots].to(torch.float64).cpu().numpy(), V), "layer %d V" % l
+            close(self.k_ctx[l][slots].to(torch.float64).cpu().numpy(), K, "layer %d K context" % l)
+
+    def close(self):
+        self.plan = None
+        self.store.close()
+        self.ctx.close()

@@ -1,0 +1,153 @@
+"""GPU parity of the cache library and the layer pipeline (mpic_store_*, mpic_prefill_layers)
+against oracle.store / oracle.pipeline: caches spread over the three tiers, every layer's
+linked context and attention output, the fall-back for expired and damaged caches."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2502_01960_amd as mpic
+from helpers import LayeredProblem, assert_bf16_close
+from oracle.store import file_name
+
+pytestmark = pytest.mark.gpu
+HBM, HOST, DISK = mpic.MPIC_TIER_HBM, mpic.MPIC_TIER_HOST, mpic.MPIC_TIER_DISK
+SMALL3 = dict(n_chunks=3, chunk_len=300, text_len=24, batch=2)      # reduced 28/4-head GQA layout
+
+
+def test_layers_from_all_three_tiers_match_the_oracle(tmp_path):
+    print("pipeline: tiers HBM/HOST/DISK, 3 layers", flush=True)
+    p = LayeredProblem(3, 3, (HBM, HOST, DISK), tmp_path, **SMALL3)
+    assert p.store.lookup(p.ids)[0] == [(HBM, HOST, DISK)[s % 3] for s in range(p.n_src)]
+    p.plan_for()
+    assert p.gpu_run() is None
+    ref = p.oracle_run()
+    p.check(ref)
+    # a second call reuses staging and the pinned ring; one context buffer shared by all layers
+    assert p.gpu_run(shared_buffers=True) is None
+    p.check(ref, kv_layers=[p.n_layers - 1])
+    p.close()
+
+
+def test_tiny_fp32_layers_from_disk(tmp_path):
+    print("pipeline: fp32 config, all caches on disk, 4 layers, one reader", flush=True)
+    p = LayeredProblem(1, 4, (DISK,), tmp_path, io_threads=1)
+    p.plan_for()
+    assert p.gpu_run() is None
+    p.check(p.oracle_run())
+    p.close()
+
+
+def test_paged_context_and_many_layers_through_the_ring(tmp_path):
+    print("pipeline: paged layout, 6 layers, disk + host", flush=True)
+    p = LayeredProblem(5, 6, (DISK, HOST), tmp_path, n_chunks=4, chunk_len=200, text_len=20, io_threads=3)
+    p.plan_for()
+    assert p.gpu_run(lse=False) is None
+    rows = np.arange(0, int(p.oplan["q_off"][-1]), 3)
+    p.check(p.oracle_run(rows=rows))
+    p.close()
+
+
+def test_expired_cache_is_recomputed(tmp_path):
+    print("pipeline: expiry -> lookup -> plan with the chunk recomputed", flush=True)
+    p = LayeredProblem(3, 2, (HBM, DISK, HOST), tmp_path, **SMALL3)
+    victim = 1
+    kk, vv = p.raw[victim]
+    p.store.put(p.ids[victim], kk, vv, DISK, expires_at=10)
+    p.model.put(p.ids[victim], kk.to(torch.float64).numpy(), vv.to(torch.float64).numpy(), DISK, expires_at=10)
+    # planned as if every cache were there: the call names the one that is not
+    p.plan_for()
+    assert p.store.expire(10) == 1 and not os.path.exists(tmp_path / file_name(p.ids[victim]))
+    assert p.gpu_run() == [victim]
+    # the lookup at the start of the request (Sec. 3.2) finds it missing; its tokens are recomputed
+    assert p.model.expire(10) == [p.ids[victim]]
+    tiers, _ = p.store.lookup(p.ids)
+    assert tiers[victim] == mpic.MPIC_TIER_MISSING
+    p.plan_for()
+    assert p.gpu_run() is None
+    p.check(p.oracle_run())
+    p.close()
+
+
+def test_damaged_block_is_found_while_loading_and_the_request_falls_back(tmp_path):
+    print("pipeline: damaged block in layer 1 of a disk cache", flush=True)
+    p = LayeredProblem(3, 3, (DISK, HBM), tmp_path, **SMALL3)
+    victim = 2                                                    # a disk-tier source
+    assert p.store.lookup(p.ids)[0][victim] == DISK
+    path = tmp_path / file_name(p.ids[victim])
+    raw = bytearray(path.read_bytes())
+    block = p.src_len[victim] * p.sh.n_kv_heads * p.sh.head_dim * 2
+    raw[4096 + 2 * block + 1000] ^= 0x04                          # inside the K block of layer 1
+    path.write_bytes(bytes(raw))
+    p.plan_for()
+    assert p.gpu_run() == [victim]                                # found when layer 1 was read
+    assert p.store.lookup(p.ids)[0][victim] == mpic.MPIC_TIER_MISSING and not path.exists()
+    # layer 0 had been enqueued before the damage was seen: it is complete and right
+    p.model.drop(p.ids[victim])
+    p.plan_for(missing=[victim])
+    assert p.gpu_run() is None
+    p.check(p.oracle_run())
+    p.close()
+
+
+def test_moving_caches_between_tiers_keeps_their_bytes(tmp_path):
+    print("store: move DISK -> HBM -> HOST -> DISK, layer pointers", flush=True)
+    p = LayeredProblem(3, 2, (DISK,), tmp_path, **SMALL3)
+    p.plan_for()
+    assert p.gpu_run() is None
+    ref = p.oracle_run()
+    p.check(ref)
+    base_out = [o.clone() for o in p.out]
+    for s, cid in enumerate(p.ids):
+        p.store.move(cid, HBM if s % 2 else HOST)
+    for cid in p.ids[:2]:
+        p.store.move(cid, HBM)
+        p.store.move(cid, HOST)
+    assert p.gpu_run() is None
+    for a, b in zip(base_out, p.out):
+        assert torch.equal(a, b)
+    # the same layer through mpic_store_layer + the single-layer calls
+    layer = 1
+    srcs = [p.store.layer(cid, layer) for cid in p.ids]
+    assert all(s[2] == p.src_len[i] for i, s in enumerate(srcs))
+    dev = torch.device("cuda:0")
+    kc, vc = torch.full_like(p.k_ctx[0], float("nan")), torch.full_like(p.v_ctx[0], float("nan"))
+    out = torch.full_like(p.out[0], float("nan"))
+    q, fk, fv = p.d_fresh[layer]
+    mpic.mpic_assemble_kv(p.ctx.handle, p.plan.handle, srcs, fk, fv, kc, vc)
+    mpic.mpic_selective_attn(p.ctx.handle, p.plan.handle, q, kc, vc, p.sh.softmax_scale, out)
+    torch.cuda.synchronize()
+    assert torch.equal(out, p.out[layer]) and torch.equal(vc, p.v_ctx[layer])
+    # back to disk: memory is released, the files still hold the same bytes
+    for cid in p.ids:
+        p.store.move(cid, DISK)
+    with pytest.raises(mpic.MpicError):
+        p.store.layer(p.ids[0], 0)
+    assert p.gpu_run() is None
+    for a, b in zip(base_out, p.out):
+        assert torch.equal(a, b)
+    p.close()
+
+
+def test_rejected_calls_enqueue_nothing(tmp_path):
+    print("pipeline: argument checks", flush=True)
+    p = LayeredProblem(3, 2, (HBM,), tmp_path, **SMALL3)
+    p.plan_for()
+    assert p.gpu_run() is None
+    other = mpic.Context(p.sh.n_q_heads, p.sh.n_kv_heads, p.sh.head_dim, mpic.MPIC_BF16, p.sh.rope_theta)
+    foreign = mpic.Store(other, 2, None)
+    args = lambda store, ids, fq: (p.ctx.handle, p.plan.handle, store, ids, fq, [f[1] for f in p.d_fresh],
+                                   [f[2] for f in p.d_fresh], p.k_ctx, p.v_ctx, p.sh.softmax_scale, p.out)
+    fq = [f[0] for f in p.d_fresh]
+    with pytest.raises(mpic.MpicError):
+        mpic.mpic_prefill_layers(*args(foreign.handle, p.ids, fq))            # store of another context
+    with pytest.raises(mpic.MpicError):
+        mpic.mpic_prefill_layers(*args(p.store.handle, p.ids[:1], fq))        # ids too short
+    with pytest.raises(mpic.MpicError):
+        mpic.mpic_prefill_layers(*args(p.store.handle, p.ids, [fq[0], None])) # a layer's tensor missing
+    with pytest.raises(mpic.MpicError):
+        mpic.mpic_prefill_layers(*args(p.store.handle, p.ids, fq * 2))        # more layers than the store holds
+    foreign.close()
+    other.close()
+    p.close()

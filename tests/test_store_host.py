@@ -1,0 +1,148 @@
+"""Host logic of the cache library's disk tier, through the C ABI (CPU only, no GPU call is
+made): files are byte-identical to the oracle's writer, files written by the oracle are found
+again, lookup / expire / drop follow the oracle's model on random operation sequences."""
+import os
+
+import numpy as np
+import pytest
+from hypothesis import given, settings, strategies as st_
+
+import paper_2502_01960_amd as mpic
+from oracle.store import DISK, MISSING, ChunkStore, file_name, read_chunk_file, write_chunk_file
+
+HKV, D, LAYERS = 2, 128, 3
+
+
+def _ctx(dtype=mpic.MPIC_BF16):
+    return mpic.Context(4, HKV, D, dtype, 1e4)
+
+
+def _cache(seed, length, dtype=np.uint16):
+    rng = np.random.default_rng(seed)
+    shape = (LAYERS, length, HKV, D)
+    hi = np.iinfo(dtype).max
+    return rng.integers(0, hi, size=shape, dtype=dtype), rng.integers(0, hi, size=shape, dtype=dtype)
+
+
+def test_files_are_byte_identical_to_the_oracle_writer(tmp_path):
+    ctx = _ctx()
+    os.mkdir(tmp_path / "a")
+    os.mkdir(tmp_path / "b")
+    store = mpic.Store(ctx, LAYERS, tmp_path / "a")
+    for cid, length in ((5, 1), (0xFEDCBA9876543210, 37)):
+        k, v = _cache(cid % 1000, length)
+        store.put(cid, k, v, mpic.MPIC_TIER_DISK)
+        write_chunk_file(tmp_path / "b" / file_name(cid), cid, k, v, 1)
+        a = (tmp_path / "a" / file_name(cid)).read_bytes()
+        assert a == (tmp_path / "b" / file_name(cid)).read_bytes()
+        got = read_chunk_file(tmp_path / "a" / file_name(cid))
+        assert got[0] == cid and got[4] == (length, HKV, D)
+        assert got[2] == [k[l].tobytes() for l in range(LAYERS)] and got[3] == [v[l].tobytes() for l in range(LAYERS)]
+    assert sorted(os.listdir(tmp_path / "a")) == sorted(os.listdir(tmp_path / "b"))   # no temporary file left
+    store.close()
+    # fp32 contexts write 4-byte elements
+    ctx32 = _ctx(mpic.MPIC_F32)
+    s32 = mpic.Store(ctx32, LAYERS, tmp_path / "a")
+    k, v = _cache(9, 4, np.uint32)
+    s32.put(77, k, v, mpic.MPIC_TIER_DISK)
+    write_chunk_file(tmp_path / "b" / file_name(77), 77, k, v, 0)
+    assert (tmp_path / "a" / file_name(77)).read_bytes() == (tmp_path / "b" / file_name(77)).read_bytes()
+    s32.close()
+
+
+def test_a_new_store_finds_the_files_of_its_shape(tmp_path):
+    k, v = _cache(1, 6)
+    write_chunk_file(tmp_path / file_name(40), 40, k, v, 1)
+    write_chunk_file(tmp_path / file_name(41), 41, k[:2], v[:2], 1)            # another layer count
+    write_chunk_file(tmp_path / file_name(42), 42, k[:, :, :1], v[:, :, :1], 1)  # another head count
+    write_chunk_file(tmp_path / file_name(43), 44, k, v, 1)                    # id and name disagree
+    (tmp_path / file_name(45)).write_bytes((tmp_path / file_name(40)).read_bytes()[:-8])   # cut short
+    (tmp_path / "notes.txt").write_text("not a cache")
+    ctx = _ctx()
+    store = mpic.Store(ctx, LAYERS, tmp_path)
+    tiers, lens = store.lookup([40, 41, 42, 43, 44, 45, 46])
+    assert tiers == [DISK] + [MISSING] * 6 and lens == [6, 0, 0, 0, 0, 0, 0]
+    store.close()
+
+
+def test_lookup_drops_a_cache_whose_file_is_gone_or_resized(tmp_path):
+    ctx = _ctx()
+    store = mpic.Store(ctx, LAYERS, tmp_path)
+    k, v = _cache(2, 5)
+    for cid in (1, 2, 3):
+        store.put(cid, k, v, mpic.MPIC_TIER_DISK)
+    os.remove(tmp_path / file_name(1))
+    with open(tmp_path / file_name(2), "ab") as f:
+        f.write(b"\0" * 8)
+    assert store.lookup([1, 2, 3]) == ([MISSING, MISSING, DISK], [0, 0, 5])
+    assert sorted(os.listdir(tmp_path)) == [file_name(3)]
+    store.close()
+
+
+def test_rejected_arguments(tmp_path):
+    ctx = _ctx()
+    with pytest.raises(mpic.MpicError):
+        mpic.Store(ctx, 0, tmp_path)
+    with pytest.raises(mpic.MpicError):
+        mpic.Store(ctx, LAYERS, tmp_path / "nowhere")
+    k, v = _cache(3, 2)
+    no_disk = mpic.Store(ctx, LAYERS)
+    with pytest.raises(mpic.MpicError):
+        no_disk.put(1, k, v, mpic.MPIC_TIER_DISK)
+    no_disk.close()
+    store = mpic.Store(ctx, LAYERS, tmp_path)
+    for bad_tier in (mpic.MPIC_TIER_MISSING, 4, -1):
+        with pytest.raises(mpic.MpicError):
+            store.put(1, k, v, bad_tier)
+    with pytest.raises(mpic.MpicError):
+        store.move(99, mpic.MPIC_TIER_DISK)
+    with pytest.raises(mpic.MpicError):
+        store.layer(99, 0)
+    store.put(1, k, v, mpic.MPIC_TIER_DISK)
+    with pytest.raises(mpic.MpicError):
+        store.layer(1, 0)                                # in the disk tier: no pointer to hand out
+    store.close()
+    gone = tmp_path / "gone"
+    os.mkdir(gone)
+    store = mpic.Store(ctx, LAYERS, gone)
+    os.rmdir(gone)                                       # the disk goes away under the store
+    with pytest.raises(mpic.MpicError) as e:
+        store.put(2, k, v, mpic.MPIC_TIER_DISK)
+    assert e.value.status == mpic.MPIC_ERR_IO
+    assert store.lookup([2])[0] == [MISSING]
+    store.close()
+
+
+_ops = st_.lists(st_.one_of(
+    st_.tuples(st_.just("put"), st_.integers(0, 5), st_.integers(1, 4), st_.integers(-1, 30)),
+    st_.tuples(st_.just("expire"), st_.integers(0, 30)),
+    st_.tuples(st_.just("drop"), st_.integers(0, 5)),
+    st_.tuples(st_.just("lookup"))), min_size=1, max_size=25)
+
+
+@settings(max_examples=40, deadline=None)
+@given(_ops)
+def test_disk_tier_follows_the_model(tmp_path_factory, ops):
+    d = tmp_path_factory.mktemp("store")
+    ctx = _ctx()
+    store = mpic.Store(ctx, LAYERS, d)
+    model = ChunkStore()
+    ids = list(range(6))
+    for n, op in enumerate(ops):
+        if op[0] == "put":
+            k, v = _cache(n, op[2])
+            store.put(op[1], k, v, mpic.MPIC_TIER_DISK, op[3])
+            model.put(op[1], k, v, DISK, op[3])
+        elif op[0] == "expire":
+            assert store.expire(op[1]) == len(model.expire(op[1]))
+        elif op[0] == "drop":
+            store.drop(op[1])
+            model.drop(op[1])
+        place, length = model.lookup(ids)
+        assert store.lookup(ids) == (place, length)
+        assert sorted(os.listdir(d)) == sorted(file_name(i) for i in model.entries)
+        for i in model.entries:                          # and every file holds what the model holds
+            got = read_chunk_file(d / file_name(i))
+            assert got[2] == [model.layer(i, l)[0].tobytes() for l in range(LAYERS)]
+            assert got[3] == [model.layer(i, l)[1].tobytes() for l in range(LAYERS)]
+    store.close()
