@@ -33,13 +33,17 @@ def plan_with_lookup(requests, ids, default_k, store, page_size=0, page_tables=N
 
 
 def prefill_layers(plan, ids, store, n_layers, fresh, theta, scale, interleaved=False, fresh_pre_rope=False,
-                   rows=None):
+                   rows=None, layers=None):
     """fresh(layer) -> (q, k, v) float64 arrays [Nq][H][D] for the plan's recompute set.
-    Returns per layer (K, V, O, LSE) in logical order, float64."""
+    Returns per layer (K, V, O, LSE) in logical order, float64; `rows` limits the attention
+    to some fresh rows, `layers` the work to some layers (the others give None)."""
     result = []
     used = sorted(set(int(s) for i, s in enumerate(plan["inst_src"])
                       if int(plan["inst_k"][i]) < int(plan["inst_len"][i])))
     for layer in range(n_layers):
+        if layers is not None and layer not in layers:
+            result.append(None)
+            continue
         ck, cv = {}, {}
         for s in used:
             k_l, v_l = store.layer(ids[s], layer)

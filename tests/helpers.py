@@ -210,12 +210,12 @@ class LayeredProblem:
         torch.cuda.synchronize()
         return failed
 
-    def oracle_run(self, rows=None):
+    def oracle_run(self, rows=None, layers=None):
         from oracle.pipeline import prefill_layers
         f64 = lambda t: t.to(torch.float64).numpy()
         return prefill_layers(self.oplan, self.ids, self.model, self.n_layers,
                               lambda l: tuple(f64(t) for t in self.fresh[l]), self.sh.rope_theta,
-                              self.sh.softmax_scale, rows=rows)
+                              self.sh.softmax_scale, rows=rows, layers=layers)
 
     def check(self, ref, layers=None, kv_layers=None):
         """Outputs of `layers` and linked contexts of `kv_layers` against the oracle's."""

@@ -49,6 +49,28 @@ def test_paged_context_and_many_layers_through_the_ring(tmp_path):
     p.close()
 
 
+def test_config3_full_size_layers_from_the_store_sampled(tmp_path):
+    print("pipeline: 18K-token batch of 4 at full size, 3 layers, caches on disk / host / HBM", flush=True)
+    p = LayeredProblem(3, 3, (DISK, HOST, HBM), tmp_path)
+    p.plan_for()
+    assert p.gpu_run(lse=False) is None
+    rng = np.random.default_rng(1)
+    rows = []
+    for (b, r0, ln, p0) in p.oplan["runs"].tolist():          # first, last and one random row of every run
+        rows += sorted({r0, r0 + ln - 1, r0 + int(rng.integers(0, ln))})
+    check = [0, 2]
+    ref = p.oracle_run(rows=np.asarray(rows), layers=check)
+    p.check(ref, layers=check, kv_layers=check)
+    # the unchecked layer still gets the exact value rows of its own slice
+    slots = torch.from_numpy(p.oplan["dst_slot"].astype(np.int64))
+    inst = 5
+    g0 = int(p.oplan["ctx_off"][p.oplan["inst_req"][inst]]) + int(p.oplan["inst_delta"][inst])
+    k_eff, ln, src = int(p.oplan["inst_k"][inst]), int(p.oplan["inst_len"][inst]), int(p.oplan["inst_src"][inst])
+    got = p.v_ctx[1][slots[g0 + k_eff:g0 + ln].to(p.v_ctx[1].device)].cpu()
+    assert torch.equal(got, p.raw[src][1][1][k_eff:ln])
+    p.close()
+
+
 def test_expired_cache_is_recomputed(tmp_path):
     print("pipeline: expiry -> lookup -> plan with the chunk recomputed", flush=True)
     p = LayeredProblem(3, 2, (HBM, DISK, HOST), tmp_path, **SMALL3)
