@@ -152,6 +152,24 @@ def test_moving_caches_between_tiers_keeps_their_bytes(tmp_path):
     p.close()
 
 
+def test_degenerate_batches(tmp_path):
+    print("pipeline: text only, no fresh row at all, an empty request in the batch", flush=True)
+    # text only: no cache is read, the call is causal prefill of every layer
+    p = LayeredProblem(3, 2, (DISK,), tmp_path, custom=([[("text", 70)], [("text", 5)]], 0, {}))
+    p.plan_for()
+    assert p.gpu_run() is None
+    p.check(p.oracle_run())
+    p.close()
+    # nothing recomputed (k = 0, no text): the contexts are linked, attention has no rows
+    p = LayeredProblem(3, 2, (DISK, HOST), tmp_path, k=0,
+                       custom=([[("chunk", 0, 90, None), ("chunk", 1, 40, None)], []], 2, {0: 90, 1: 40}))
+    p.plan_for()
+    assert int(p.oplan["q_off"][-1]) == 0
+    assert p.gpu_run() is None
+    p.check(p.oracle_run())
+    p.close()
+
+
 def test_rejected_calls_enqueue_nothing(tmp_path):
     print("pipeline: argument checks", flush=True)
     p = LayeredProblem(3, 2, (HBM,), tmp_path, **SMALL3)

@@ -146,3 +146,42 @@ def test_disk_tier_follows_the_model(tmp_path_factory, ops):
             assert got[2] == [model.layer(i, l)[0].tobytes() for l in range(LAYERS)]
             assert got[3] == [model.layer(i, l)[1].tobytes() for l in range(LAYERS)]
     store.close()
+
+
+def test_prefill_layers_names_missing_and_unreadable_caches_before_touching_the_gpu(tmp_path):
+    """The lookup at the start of the call (Sec. 3.2): a plan that reads caches the store does
+    not have, or whose files are unusable, is refused with the list of those sources; nothing
+    has been enqueued by then, so this runs without a GPU (the buffers are never dereferenced)."""
+    import ctypes as C
+    ctx = _ctx()
+    store = mpic.Store(ctx, LAYERS, tmp_path)
+    k, v = _cache(4, 9)
+    store.put(20, k, v, mpic.MPIC_TIER_DISK)
+    store.put(21, k, v, mpic.MPIC_TIER_DISK)
+    store.put(22, k, v, mpic.MPIC_TIER_DISK)
+    raw = bytearray((tmp_path / file_name(21)).read_bytes())
+    raw[20] ^= 1                                           # header field, same file size
+    (tmp_path / file_name(21)).write_bytes(bytes(raw))
+    requests = [[("text", 2), ("chunk", 0, 9, 1), ("chunk", 1, 9, 0), ("chunk", 2, 9, 9), ("chunk", 3, 9, 2), ("text", 1)]]
+    plan = mpic.Plan(ctx, requests, 1)
+    n_q = len(plan.get("q_pos"))
+    lib = mpic.load_library()
+    fake = (C.c_void_p * LAYERS)(*[0x1000] * LAYERS)       # aligned, never read
+    ids = (C.c_uint64 * 4)(20, 21, 999, 23)                # source 2 is fully recomputed: its id is not looked at
+    failed = (C.c_int32 * 4)(7, 7, 7, 7)
+    rc = lib.mpic_prefill_layers(ctx.handle, plan.handle, store.handle, ids, 4, LAYERS, fake, fake, fake, n_q,
+                                 fake, fake, 100, 0.1, fake, None, None, failed)
+    assert rc == mpic.MPIC_ERR_CACHE_MISS
+    assert list(failed) == [0, 1, 0, 1]                    # damaged header, and an id the store never saw
+    assert store.lookup([20, 21, 22])[0] == [DISK, MISSING, DISK]     # the unusable cache was dropped
+    # argument checks come first
+    assert lib.mpic_prefill_layers(ctx.handle, plan.handle, store.handle, ids, 4, LAYERS + 1, fake, fake, fake, n_q,
+                                   fake, fake, 100, 0.1, fake, None, None, failed) == -1
+    assert lib.mpic_prefill_layers(ctx.handle, plan.handle, store.handle, ids, 4, LAYERS, fake, fake, fake, n_q + 1,
+                                   fake, fake, 100, 0.1, fake, None, None, failed) == -1
+    assert lib.mpic_prefill_layers(ctx.handle, plan.handle, store.handle, ids, 4, LAYERS, fake, fake, fake, n_q,
+                                   fake, fake, 10, 0.1, fake, None, None, failed) == -1       # context too small
+    assert lib.mpic_prefill_layers(ctx.handle, plan.handle, store.handle, ids, 4, 0, None, None, None, n_q,
+                                   None, None, 100, 0.1, None, None, None, failed) == 0       # no layers: nothing to do
+    plan.close()
+    store.close()
