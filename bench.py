@@ -45,6 +45,8 @@ def parse():
     ap.add_argument("--pipeline-layers", type=int, default=8,
                     help="layers of the mpic_prefill_layers leg (caches fetched from the store's HBM, host and disk "
                          "tiers while earlier layers compute); 0 skips it")
+    ap.add_argument("--pipeline-tiers", default="disk,host,hbm",
+                    help="tiers the mpic_prefill_layers leg is timed from, in this order (hbm alone needs no disk directory)")
     ap.add_argument("--disk-dir", default=None, help="directory of the store's disk tier (default: a temporary one)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain elementwise copy of 512 MiB (reads and writes 512 MiB per "
@@ -336,23 +338,27 @@ def main():
         import shutil
         import tempfile
         P = args.pipeline_layers
-        tmp = None if args.disk_dir else tempfile.mkdtemp(prefix="mpic_store_")
-        store = mpic.Store(ctx, P, args.disk_dir or tmp, 8)
+        tiers = [t for t in args.pipeline_tiers.split(",") if t]
+        tier_id = {"disk": mpic.MPIC_TIER_DISK, "host": mpic.MPIC_TIER_HOST, "hbm": mpic.MPIC_TIER_HBM}
+        need_disk = "disk" in tiers
+        tmp = tempfile.mkdtemp(prefix="mpic_store_") if need_disk and not args.disk_dir else None
+        store = mpic.Store(ctx, P, (args.disk_dir or tmp) if need_disk else None, 8)
         ids = [5000 + s for s in range(n_src)]
         cache_bytes = 0
         for s in used_src:
             kk = torch.stack([host_chunks[l % L][s][0] for l in range(P)]).contiguous()
             vv = torch.stack([host_chunks[l % L][s][1] for l in range(P)]).contiguous()
-            store.put(ids[s], kk, vv, mpic.MPIC_TIER_DISK)
+            store.put(ids[s], kk, vv, tier_id[tiers[0]])
             cache_bytes += 2 * kk.numel() * 2
+            del kk, vv
         lists = [[sets[l % L][f] for l in range(P)] for f in ("q", "fk", "fv", "k_ctx", "v_ctx", "out")]
         pipe = dict(layers=P, stored_bytes_per_layer=cache_bytes // P, reader_threads=8,
                     note="one mpic_prefill_layers call per batch: stored rows of later layers are read from their tier and "
-                         "linked (over the bus, in place) while earlier layers attend; ms per layer = call to stream sync / layers")
+                         "linked (read over the bus in place, or staged copies when caches are shared by requests) while earlier layers attend; ms per layer = call to stream sync / layers")
         reps = max(2, min(4, args.steps))
-        for name, tier in (("disk", mpic.MPIC_TIER_DISK), ("host", mpic.MPIC_TIER_HOST), ("hbm", mpic.MPIC_TIER_HBM)):
+        for name in tiers:
             for s in used_src:
-                store.move(ids[s], tier)
+                store.move(ids[s], tier_id[name])
 
             def call():
                 assert mpic.mpic_prefill_layers(ctx.handle, plan.handle, store.handle, ids, *lists[:5],

@@ -435,8 +435,10 @@ int mpic_store_layer(mpic_store* store, uint64_t id, int32_t layer, mpic_chunk_s
  *   out[l], lse[l]                      device; lse or lse[l] may be NULL
  * Schedule: the stored part of layer l is linked on a library stream (host and disk
  * tiers: the kernel reads pinned memory in place over the bus, held to a few workgroups
- * so that it runs beside the attention of earlier layers; disk: read and verified by
- * the reader threads into a ring of pinned buffers, one layer ahead of the linking),
+ * so that it runs beside the attention of earlier layers -- or, when the batch uses its
+ * caches more than 1.25 times on average, staged copies that fetch each cache once;
+ * disk: read and verified by the reader threads into a ring of pinned buffers, one
+ * layer ahead of the linking),
  * fresh rows and attention run on `stream`, joined by events.  The call returns when
  * everything is enqueued; the host thread waits only for file reads.
  * failed: [n_srcs] or NULL; on MPIC_ERR_CACHE_MISS failed[s] = 1 for every source whose

@@ -563,8 +563,9 @@ int prefill_layers(mpic_ctx* ctx, mpic_plan* plan, mpic_store* st, const uint64_
         batch.jobs.push_back(j);
       }
     }
-    // the ring may still be read by the linking kernels of an earlier call
+    // the ring may still be read by the linking kernels or the copies of an earlier call
     MPIC_HIP(ctx, hipStreamSynchronize(ctx->link_stream));
+    MPIC_HIP(ctx, hipStreamSynchronize(ctx->side_stream));
     if (st->readers.empty())
       for (int t = 0; t < st->n_threads; ++t) st->readers.emplace_back(reader_main, st);
     {
@@ -583,12 +584,29 @@ int prefill_layers(mpic_ctx* ctx, mpic_plan* plan, mpic_store* st, const uint64_
   } batch_end{st, &batch, n_disk > 0};
 
   // ---- layer loop ----
-  // Pinned memory of both slower tiers comes from hipHostMalloc, so the linking kernel reads it
-  // in place over the bus (held to a few workgroups on the library's stream, beside the
+  // Pinned memory of both slower tiers comes from hipHostMalloc, so the linking kernel can read
+  // it in place over the bus (held to a few workgroups on the library's stream, beside the
   // attention of the layer before).  Measured against staged copies, per layer: 18K-token
   // batch of 4, 2.79 ms against 3.88 ms from the host tier and 2.91 against 3.63 from disk;
-  // 75K-token paged request, 6.28 against 7.22 and 6.41 against 6.57.
-  const int host_route = MPIC_SRC_HOST_MAPPED;
+  // 75K-token paged request, 6.28 against 7.22 and 6.41 against 6.57.  A kernel that reads in
+  // place fetches a cache once per *use*, staged copies fetch it once per call: when the batch
+  // uses its caches more than once on average (retrieval batches that draw from a common pool:
+  // 9.1 ms against 5.9 ms per layer for 8 requests x 16 chunks out of 64), copies win.
+  int64_t rows_used = 0, rows_stored = 0;
+  {
+    std::vector<int32_t> first_row(std::max(n_srcs, 0), INT32_MAX);
+    for (size_t i = 0; i < n_inst; ++i) {
+      const int32_t s = plan->inst_src[i];
+      if (plan->inst_cached[i] > 0 && entry[s] && entry[s]->tier != MPIC_TIER_HBM) {
+        rows_used += plan->inst_cached[i];
+        first_row[s] = std::min(first_row[s], plan->inst_k[i]);
+      }
+    }
+    for (int32_t s = 0; s < n_srcs; ++s)
+      if (first_row[s] != INT32_MAX) rows_stored += entry[s]->len - first_row[s];
+  }
+  const int host_route = 4 * rows_used > 5 * rows_stored ? MPIC_SRC_HOST_STAGED : MPIC_SRC_HOST_MAPPED;
+  hipStream_t ring_reader = host_route == MPIC_SRC_HOST_MAPPED ? ctx->link_stream : ctx->side_stream;
   std::vector<mpic_chunk_src> srcs(std::max(n_srcs, 0));
   std::unordered_map<const void*, int32_t> last_reader;  // context buffer -> layer whose attention read it last
   for (int32_t l = 0; l < n_layers; ++l) {
@@ -645,7 +663,7 @@ int prefill_layers(mpic_ctx* ctx, mpic_plan* plan, mpic_store* st, const uint64_
     if (rc != MPIC_OK) return rc;
     MPIC_HIP(ctx, hipEventRecord(ctx->ev_layer[2 * l], ctx->link_stream));
     if (n_disk > 0) {
-      MPIC_HIP(ctx, hipEventRecord(batch.ev_release[l % batch.depth], ctx->link_stream));
+      MPIC_HIP(ctx, hipEventRecord(batch.ev_release[l % batch.depth], ring_reader));
       std::lock_guard<std::mutex> lock(st->mu);
       batch.layers_enqueued = l + 1;
       st->cv.notify_all();

@@ -152,6 +152,20 @@ def test_moving_caches_between_tiers_keeps_their_bytes(tmp_path):
     p.close()
 
 
+def test_caches_shared_by_several_requests(tmp_path):
+    print("pipeline: three requests draw on the same two caches (fetched once per call), 3 layers", flush=True)
+    reqs = [[("text", 9), ("chunk", 0, 150, None), ("chunk", 1, 70, None), ("text", 4)],
+            [("chunk", 1, 70, 3), ("text", 2), ("chunk", 0, 150, 0)],
+            [("chunk", 0, 150, None), ("text", 30), ("chunk", 1, 70, None), ("chunk", 0, 150, 5)]]
+    for tiers in ((HOST,), (DISK,), (DISK, HBM)):
+        p = LayeredProblem(3, 3, tiers, tmp_path, k=8, custom=(reqs, 2, {0: 150, 1: 70}))
+        p.plan_for()
+        assert p.gpu_run() is None
+        p.check(p.oracle_run())
+        assert p.gpu_run(shared_buffers=True) is None
+        p.close()
+
+
 def test_degenerate_batches(tmp_path):
     print("pipeline: text only, no fresh row at all, an empty request in the batch", flush=True)
     # text only: no cache is read, the call is causal prefill of every layer
