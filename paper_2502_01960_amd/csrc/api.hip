@@ -262,10 +262,17 @@ int mpic::assemble_parts(mpic_ctx* ctx, mpic_plan* plan, const mpic_chunk_src* s
       const size_t skip = static_cast<size_t>(first_row[si]) * row_bytes;
       const size_t bytes = static_cast<size_t>(s.len) * row_bytes;
       char* dst = staging + stage_off[si];
-      MPIC_HIP(ctx, hipMemcpyAsync(dst + skip, static_cast<const char*>(s.k) + skip, bytes - skip,
-                                   hipMemcpyHostToDevice, ctx->side_stream));
-      MPIC_HIP(ctx, hipMemcpyAsync(dst + bytes + skip, static_cast<const char*>(s.v) + skip, bytes - skip,
-                                   hipMemcpyHostToDevice, ctx->side_stream));
+      if (static_cast<const char*>(s.v) == static_cast<const char*>(s.k) + bytes) {
+        // keys and values lie back to back (the layout of the cache library): one transfer,
+        // the skipped head of V rides along
+        MPIC_HIP(ctx, hipMemcpyAsync(dst + skip, static_cast<const char*>(s.k) + skip, 2 * bytes - skip,
+                                     hipMemcpyHostToDevice, ctx->side_stream));
+      } else {
+        MPIC_HIP(ctx, hipMemcpyAsync(dst + skip, static_cast<const char*>(s.k) + skip, bytes - skip,
+                                     hipMemcpyHostToDevice, ctx->side_stream));
+        MPIC_HIP(ctx, hipMemcpyAsync(dst + bytes + skip, static_cast<const char*>(s.v) + skip, bytes - skip,
+                                     hipMemcpyHostToDevice, ctx->side_stream));
+      }
       if ((i + 1) % kGroup == 0 || i + 1 == host_srcs.size())
         MPIC_HIP(ctx, hipEventRecord(ctx->ev_copy[i / kGroup], ctx->side_stream));
     }
