@@ -327,6 +327,13 @@ def mpic_store_put(ctx, store, chunk_id, k, v, tier, expires_at=-1):
     """k, v: contiguous host arrays or CPU tensors [n_layers][len][Hkv][D] of the storage type."""
     def addr(x):
         return x.data_ptr() if hasattr(x, "data_ptr") else x.ctypes.data
+
+    def contiguous(x):
+        return x.is_contiguous() if hasattr(x, "is_contiguous") else x.flags["C_CONTIGUOUS"]
+    if tuple(k.shape) != tuple(v.shape) or len(k.shape) != 4 or not (contiguous(k) and contiguous(v)):
+        raise ValueError("k and v must be contiguous [n_layers][len][Hkv][D] arrays of one shape")
+    if getattr(k, "is_cuda", False) or getattr(v, "is_cuda", False):
+        raise ValueError("mpic_store_put takes host memory")
     _check(load_library().mpic_store_put(store, int(chunk_id), int(k.shape[1]), C.c_void_p(addr(k)),
                                          C.c_void_p(addr(v)), int(tier), int(expires_at)), ctx)
 
@@ -440,9 +447,12 @@ class Store:
 
     def __init__(self, ctx: Context, n_layers, disk_dir=None, io_threads=0):
         self.ctx = ctx
+        self.n_layers = int(n_layers)
         self.handle = mpic_store_create(ctx.handle, n_layers, disk_dir, io_threads)
 
     def put(self, chunk_id, k, v, tier, expires_at=-1):
+        if k.shape[0] != self.n_layers or tuple(k.shape[2:]) != (self.ctx.n_kv_heads, self.ctx.head_dim):
+            raise ValueError("cache shape must be [n_layers][len][Hkv][D] of this store")
         mpic_store_put(self.ctx.handle, self.handle, chunk_id, k, v, tier, expires_at)
 
     def move(self, chunk_id, tier):

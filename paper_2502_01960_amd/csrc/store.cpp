@@ -707,6 +707,10 @@ extern "C" int mpic_store_create(mpic_ctx* ctx, int32_t n_layers, const char* di
     st->n_threads = io_threads > 0 ? std::min(io_threads, 64) : 4;
     const mpic_config& c = ctx->cfg;
     st->row_bytes = static_cast<size_t>(c.n_kv_heads) * c.head_dim * (c.dtype == MPIC_F32 ? 4 : 2);
+    if (st->row_bytes % 8 != 0) {  // the checksum runs over 8-byte words
+      delete st;
+      return fail(ctx, MPIC_ERR_UNSUPPORTED, "store_create: a cache row must be a multiple of 8 bytes");
+    }
     if (disk_dir) {
       struct stat sb;
       if (stat(disk_dir, &sb) != 0 || !S_ISDIR(sb.st_mode)) {
