@@ -287,6 +287,27 @@ int mpic_selective_attn(mpic_ctx* ctx, mpic_plan* plan, const void* fresh_q, int
                         double softmax_scale, void* out, float* lse, void* stream);
 
 /*
+ * mpic_selective_attn of one layer and, in the same launch, the stored rows of the next
+ * layer's context (what mpic_assemble_kv_parts with MPIC_PART_CACHED writes): workgroups
+ * that follow the attention tiles in the grid link them while the attention drains, on
+ * the compute units its last tiles leave idle (Sec. 3.2: preparing the next KV cache and
+ * computing proceed concurrently; here without a second stream).
+ *   next_srcs[n_srcs]        chunk caches of the next layer, as for mpic_assemble_kv
+ *   next_k_ctx, next_v_ctx   device, n_ctx_slots rows each, written; must not overlap
+ *                            k_ctx / v_ctx
+ * The fused launch needs bf16, device-resident sources and at most 128 chunk instances
+ * in the plan; otherwise (and when the recompute set is empty) the call does the same
+ * work with a launch of its own after the attention.  The fresh rows of the next layer
+ * are not touched: link them (MPIC_PART_FRESH) before that layer's attention.
+ * Errors: as mpic_selective_attn and mpic_assemble_kv; INVALID if the buffers overlap.
+ */
+int mpic_selective_attn_link_next(mpic_ctx* ctx, mpic_plan* plan, const void* fresh_q, int64_t n_fresh_rows,
+                                  const void* k_ctx, const void* v_ctx, int64_t n_ctx_slots,
+                                  double softmax_scale, void* out, float* lse,
+                                  const mpic_chunk_src* next_srcs, int32_t n_srcs, void* next_k_ctx,
+                                  void* next_v_ctx, void* stream);
+
+/*
  * Decode-step attention over a linked context (App. A, autoregressive generation: the
  * query of the next token attends to every cached position and, its key and value being
  * appended to the cache, to itself).  For every request b of the plan and query head h
@@ -439,8 +460,11 @@ int mpic_store_layer(mpic_store* store, uint64_t id, int32_t layer, mpic_chunk_s
  * caches more than 1.25 times on average, staged copies that fetch each cache once;
  * disk: read and verified by the reader threads into a ring of pinned buffers, one
  * layer ahead of the linking),
- * fresh rows and attention run on `stream`, joined by events.  The call returns when
- * everything is enqueued; the host thread waits only for file reads.
+ * fresh rows and attention run on `stream`, joined by events.  When every cache the plan
+ * reads is in GPU memory there is nothing to fetch ahead: the stored rows of layer l+1 are
+ * then linked by the attention launch of layer l (mpic_selective_attn_link_next), all on
+ * `stream`.  The call returns when everything is enqueued; the host thread waits only for
+ * file reads.
  * failed: [n_srcs] or NULL; on MPIC_ERR_CACHE_MISS failed[s] = 1 for every source whose
  * cache is missing from the store or failed to load.  Missing caches and unreadable or
  * mis-sized files are found before anything is enqueued; a damaged block is found when

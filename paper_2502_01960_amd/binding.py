@@ -80,6 +80,9 @@ def load_library():
     lib.mpic_assemble_kv_parts.restype = C.c_int
     lib.mpic_selective_attn.argtypes = [vp, vp, vp, i64, vp, vp, i64, C.c_double, vp, vp, vp]
     lib.mpic_selective_attn.restype = C.c_int
+    lib.mpic_selective_attn_link_next.argtypes = [vp, vp, vp, i64, vp, vp, i64, C.c_double, vp, vp,
+                                                  C.POINTER(_ChunkSrc), i32, vp, vp, vp]
+    lib.mpic_selective_attn_link_next.restype = C.c_int
     lib.mpic_decode_attn.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, C.c_double, vp, vp, vp]
     lib.mpic_decode_attn.restype = C.c_int
     lib.mpic_k_distance.argtypes = [vp, vp, vp, i64, vp, vp]
@@ -255,8 +258,7 @@ def mpic_assemble_kv(ctx, plan, srcs, fresh_k, fresh_v, k_ctx, v_ctx, stream=Non
                            MPIC_PART_CACHED | MPIC_PART_FRESH, stream, host_mode)
 
 
-def mpic_assemble_kv_parts(ctx, plan, srcs, fresh_k, fresh_v, k_ctx, v_ctx, parts, stream=None,
-                           host_mode=MPIC_SRC_HOST_STAGED):
+def _src_array(srcs, host_mode):
     srcs = srcs or []
     arr = (_ChunkSrc * max(1, len(srcs)))()
     for i, src in enumerate(srcs):
@@ -271,8 +273,14 @@ def mpic_assemble_kv_parts(ctx, plan, srcs, fresh_k, fresh_v, k_ctx, v_ctx, part
         if on_host and not (k.is_pinned() and v.is_pinned()):
             raise ValueError("host chunk sources must be pinned")
         arr[i] = _ChunkSrc(k.data_ptr(), v.data_ptr(), k.shape[0], on_host)
+    return arr, len(srcs)
+
+
+def mpic_assemble_kv_parts(ctx, plan, srcs, fresh_k, fresh_v, k_ctx, v_ctx, parts, stream=None,
+                           host_mode=MPIC_SRC_HOST_STAGED):
+    arr, n_srcs = _src_array(srcs, host_mode)
     n_fresh = 0 if fresh_k is None else fresh_k.shape[0]
-    rc = load_library().mpic_assemble_kv_parts(ctx, plan, arr, len(srcs), _ptr(fresh_k), _ptr(fresh_v), n_fresh,
+    rc = load_library().mpic_assemble_kv_parts(ctx, plan, arr, n_srcs, _ptr(fresh_k), _ptr(fresh_v), n_fresh,
                                                _ptr(k_ctx), _ptr(v_ctx), k_ctx.shape[0], int(parts),
                                                _stream(stream))
     _check(rc, ctx)
@@ -283,6 +291,18 @@ def mpic_selective_attn(ctx, plan, fresh_q, k_ctx, v_ctx, softmax_scale, out, ls
     rc = load_library().mpic_selective_attn(ctx, plan, _ptr(fresh_q), n_fresh, _ptr(k_ctx), _ptr(v_ctx),
                                             k_ctx.shape[0], float(softmax_scale), _ptr(out), _ptr(lse),
                                             _stream(stream))
+    _check(rc, ctx)
+
+
+def mpic_selective_attn_link_next(ctx, plan, fresh_q, k_ctx, v_ctx, softmax_scale, out, next_srcs, next_k_ctx,
+                                  next_v_ctx, lse=None, stream=None, host_mode=MPIC_SRC_HOST_STAGED):
+    """Attention of one layer plus the stored rows of the next layer's context in one launch."""
+    arr, n_srcs = _src_array(next_srcs, host_mode)
+    n_fresh = 0 if fresh_q is None else fresh_q.shape[0]
+    rc = load_library().mpic_selective_attn_link_next(ctx, plan, _ptr(fresh_q), n_fresh, _ptr(k_ctx), _ptr(v_ctx),
+                                                      k_ctx.shape[0], float(softmax_scale), _ptr(out), _ptr(lse),
+                                                      arr, n_srcs, _ptr(next_k_ctx), _ptr(next_v_ctx),
+                                                      _stream(stream))
     _check(rc, ctx)
 
 

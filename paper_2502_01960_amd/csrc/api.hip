@@ -388,16 +388,52 @@ int mpic::assemble_parts(mpic_ctx* ctx, mpic_plan* plan, const mpic_chunk_src* s
 int mpic::attend(mpic_ctx* ctx, mpic_plan* plan, const void* fresh_q,
                                int64_t n_fresh_rows, const void* k_ctx, const void* v_ctx,
                                int64_t n_ctx_slots, double softmax_scale, void* out, float* lse,
-                               void* stream_) {
+                               void* stream_, const mpic::NextLink* next) {
   if (!ctx) return MPIC_ERR_INVALID;
   if (!plan || plan->ctx != ctx) return fail(ctx, MPIC_ERR_INVALID, "selective_attn: plan does not belong to this context");
   if (n_fresh_rows != plan->n_q) return fail(ctx, MPIC_ERR_INVALID, "selective_attn: n_fresh_rows differs from the plan's recompute set");
   if (!(softmax_scale > 0.0) || !std::isfinite(softmax_scale)) return fail(ctx, MPIC_ERR_INVALID, "selective_attn: softmax_scale must be finite and positive");
-  if (plan->n_q == 0) return MPIC_OK;
+  if (plan->n_q == 0) {
+    if (next)  // no attention to ride along with
+      return mpic::assemble_parts(ctx, plan, next->srcs, next->n_srcs, nullptr, nullptr, 0, next->k_ctx, next->v_ctx,
+                                  n_ctx_slots, MPIC_PART_CACHED, stream_);
+    return MPIC_OK;
+  }
   if (!fresh_q || !k_ctx || !v_ctx || !out) return fail(ctx, MPIC_ERR_INVALID, "selective_attn: null buffer");
   if (n_ctx_slots <= plan->max_slot) return fail(ctx, MPIC_ERR_INVALID, "selective_attn: context buffers smaller than the plan's largest slot");
   if (!mpic::aligned16(fresh_q) || !mpic::aligned16(k_ctx) || !mpic::aligned16(v_ctx) || !mpic::aligned16(out))
     return fail(ctx, MPIC_ERR_INVALID, "selective_attn: buffers must be 16-byte aligned");
+  bool fuse_next = false;
+  if (next) {
+    // the stored rows of the next layer, linked by the same launch when the sources allow it
+    const size_t n_inst = plan->inst_src.size();
+    if (!next->k_ctx || !next->v_ctx || !mpic::aligned16(next->k_ctx) || !mpic::aligned16(next->v_ctx))
+      return fail(ctx, MPIC_ERR_INVALID, "selective_attn: next layer's context buffers missing or not 16-byte aligned");
+    const size_t bytes = static_cast<size_t>(n_ctx_slots) * ctx->cfg.n_kv_heads * ctx->cfg.head_dim * (ctx->cfg.dtype == MPIC_F32 ? 4 : 2);
+    auto overlap = [&](const void* x, const void* y) {
+      const char* a0 = static_cast<const char*>(x);
+      const char* b0 = static_cast<const char*>(y);
+      return a0 < b0 + bytes && b0 < a0 + bytes;
+    };
+    if (overlap(next->k_ctx, k_ctx) || overlap(next->k_ctx, v_ctx) || overlap(next->v_ctx, k_ctx) || overlap(next->v_ctx, v_ctx))
+      return fail(ctx, MPIC_ERR_INVALID, "selective_attn: the next layer's context must not overlap the one being read");
+    if (n_inst > 0 && (!next->srcs || next->n_srcs <= plan->max_src))
+      return fail(ctx, MPIC_ERR_INVALID, "selective_attn: next layer's srcs does not cover every chunk index of the plan");
+    // (the trailing workgroups of 512 threads give every thread one unit pair of a row)
+    const int pairs_per_row = ctx->cfg.n_kv_heads * (ctx->cfg.head_dim / 16);
+    fuse_next = ctx->cfg.dtype == MPIC_BF16 && n_inst <= static_cast<size_t>(mpic::kMaxInstPerLaunch) &&
+                !plan->tiles.empty() && pairs_per_row <= 512 && 512 % pairs_per_row == 0;
+    for (size_t i = 0; i < n_inst; ++i) {
+      const mpic_chunk_src& sc = next->srcs[plan->inst_src[i]];
+      if (sc.len != plan->inst_len[i]) return fail(ctx, MPIC_ERR_INVALID, "selective_attn: next layer's chunk source length differs from its segment");
+      if (sc.on_host < MPIC_SRC_DEVICE || sc.on_host > MPIC_SRC_HOST_MAPPED) return fail(ctx, MPIC_ERR_INVALID, "selective_attn: unknown on_host value");
+      if (plan->inst_cached[i] > 0) {
+        if (!sc.k || !sc.v || !mpic::aligned16(sc.k) || !mpic::aligned16(sc.v))
+          return fail(ctx, MPIC_ERR_INVALID, "selective_attn: next layer's chunk source pointer missing or not 16-byte aligned");
+        if (sc.on_host != MPIC_SRC_DEVICE) fuse_next = false;  // host memory: the separate, slower launch
+      }
+    }
+  }
   int rc = mpic::bind_device(ctx);
   if (rc != MPIC_OK) return rc;
   rc = mpic::upload_plan(ctx, plan);
@@ -446,11 +482,39 @@ int mpic::attend(mpic_ctx* ctx, mpic_plan* plan, const void* fresh_q,
   a.q_sin = plan->dev.fresh_sin;
   a.interleaved = c.rope_interleaved;
   hipStream_t stream = static_cast<hipStream_t>(stream_);
+  if (fuse_next) {
+    mpic::AssembleArgs la{};
+    la.src_inst = plan->dev.src_inst;
+    la.src_row = plan->dev.src_row;
+    la.dst_slot = plan->dev.dst_slot;
+    la.rope_cos = plan->dev.rope_cos;
+    la.rope_sin = plan->dev.rope_sin;
+    la.k_ctx = next->k_ctx;
+    la.v_ctx = next->v_ctx;
+    la.pos_begin = 0;
+    la.pos_end = plan->n_ctx;
+    la.inst_base = 0;
+    la.n_inst = static_cast<int32_t>(plan->inst_src.size());
+    la.n_kv_heads = c.n_kv_heads;
+    la.head_dim = c.head_dim;
+    la.interleaved = c.rope_interleaved;
+    la.skip_fresh = 1;
+    mpic::AssembleSrcTable tab{};
+    for (size_t i = 0; i < plan->inst_src.size(); ++i) {
+      tab.k[i] = next->srcs[plan->inst_src[i]].k;
+      tab.v[i] = next->srcs[plan->inst_src[i]].v;
+    }
+    MPIC_HIP(ctx, mpic::launch_attn_bf16(a, &la, &tab, stream));
+    return MPIC_OK;
+  }
   if (c.dtype == MPIC_F32) {
     MPIC_HIP(ctx, mpic::launch_attn_f32(a, plan->n_q, stream));
   } else {
-    MPIC_HIP(ctx, mpic::launch_attn_bf16(a, stream));
+    MPIC_HIP(ctx, mpic::launch_attn_bf16(a, nullptr, nullptr, stream));
   }
+  if (next)  // same result, one launch more
+    return mpic::assemble_parts(ctx, plan, next->srcs, next->n_srcs, nullptr, nullptr, 0, next->k_ctx, next->v_ctx,
+                                n_ctx_slots, MPIC_PART_CACHED, stream_);
   return MPIC_OK;
 }
 
@@ -553,7 +617,17 @@ extern "C" int mpic_selective_attn(mpic_ctx* ctx, mpic_plan* plan, const void* f
                                    int64_t n_ctx_slots, double softmax_scale, void* out, float* lse,
                                    void* stream) {
   MPIC_GUARDED(ctx, mpic::attend(ctx, plan, fresh_q, n_fresh_rows, k_ctx, v_ctx, n_ctx_slots, softmax_scale,
-                                        out, lse, stream))
+                                        out, lse, stream, nullptr))
+}
+
+extern "C" int mpic_selective_attn_link_next(mpic_ctx* ctx, mpic_plan* plan, const void* fresh_q,
+                                             int64_t n_fresh_rows, const void* k_ctx, const void* v_ctx,
+                                             int64_t n_ctx_slots, double softmax_scale, void* out, float* lse,
+                                             const mpic_chunk_src* next_srcs, int32_t n_srcs, void* next_k_ctx,
+                                             void* next_v_ctx, void* stream) {
+  const mpic::NextLink next{next_srcs, n_srcs, next_k_ctx, next_v_ctx};
+  MPIC_GUARDED(ctx, mpic::attend(ctx, plan, fresh_q, n_fresh_rows, k_ctx, v_ctx, n_ctx_slots, softmax_scale,
+                                 out, lse, stream, &next))
 }
 
 extern "C" int mpic_decode_attn(mpic_ctx* ctx, mpic_plan* plan, const void* q, const void* new_k,

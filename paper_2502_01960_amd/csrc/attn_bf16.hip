@@ -24,7 +24,11 @@
 // exchange with lane^32, and the S^T accumulator registers already hold P^T in the
 // B-operand layout of the second product (no data movement between the two MFMAs:
 // the contraction index may be permuted freely as long as A and B agree).
+#include <algorithm>
+#include <type_traits>
+
 #include "common.h"
+#include "link_rows.h"
 
 namespace mpic {
 namespace {
@@ -50,6 +54,14 @@ constexpr int STAGE_BYTES = 2 * TILE_BYTES;      // K block followed by V block
 constexpr int STAGES = 4;                        // ring depth: loads run 3 blocks ahead
 constexpr int LDS_BYTES = STAGES * STAGE_BYTES;  // 128 KB of the CU's 160 KB
 constexpr int LOADS_PER_STAGE = 4;               // direct loads each wave issues per block
+#ifndef MPIC_LINK_ROUNDS
+#define MPIC_LINK_ROUNDS 2
+#endif
+constexpr int kLinkRounds = MPIC_LINK_ROUNDS;
+#ifndef MPIC_LINK_DEPTH
+#define MPIC_LINK_DEPTH 2
+#endif
+constexpr int kLinkDepth = MPIC_LINK_DEPTH;  // items a thread of a trailing workgroup keeps in flight
 constexpr float kSlack = 8.0f;                   // lazy-rescale threshold, log2 units
 static_assert(WAVES * ROWS_PER_WAVE == kAttnTileRows, "tile size and kernel shape must agree");
 
@@ -126,9 +138,63 @@ __device__ inline float wave_max(float x) {
   return x;
 }
 
-__global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a) {
+// Second job a launch may carry: the stored rows of the *next* layer's context, linked by
+// workgroups that come after the attention tiles in the grid.  The dispatcher hands out
+// workgroups in order, so these start as the attention drains and use the compute units its
+// last, longest tiles leave idle (the linking is bandwidth bound and needs no LDS).
+struct NoLink {};
+struct LinkNext {
+  AssembleArgs args;
+  AssembleSrcTable tab;
+  int32_t n_wgs;  // workgroups after the attention tiles
+};
+
+__device__ inline void link_share(const LinkNext& ln, int j) {
+  const link::Shape sh = link::shape_of<__bf16>(ln.args);
+  // workgroup j links rows [lo, hi) of the range; a thread keeps its unit pair and walks down
+  // the rows (the launcher only fuses shapes whose pairs per row divide the workgroup)
+  const int64_t n_rows = ln.args.pos_end - ln.args.pos_begin;
+  const int64_t per = (n_rows + ln.n_wgs - 1) / ln.n_wgs;
+  const int64_t lo = ln.args.pos_begin + j * per;
+  const int64_t hi = lo + per < ln.args.pos_end ? lo + per : ln.args.pos_end;
+  const int u = static_cast<int>(threadIdx.x) % sh.pairs_per_row;
+  const int step = THREADS / sh.pairs_per_row;  // rows the workgroup covers per pass
+  // One workgroup per compute unit fits beside nothing else (the launch reserves the LDS ring),
+  // so each thread keeps kLinkDepth items in flight, all of their loads before the first store.
+  // (Depth 1 to 4 and one to four trips per workgroup measured within 5 us of each other on the
+  // 18K-token batch of 4: the launch lasts 13-18 us longer than the attention alone, against the
+  // 51 us of a linking launch of its own; depth 8 spills and costs 45 us.)
+  auto run = [&](auto interleaved) {
+    constexpr bool kI = decltype(interleaved)::value;
+    for (int64_t r0 = lo + static_cast<int>(threadIdx.x) / sh.pairs_per_row; r0 < hi; r0 += kLinkDepth * step) {
+      link::Loaded<__bf16> it[kLinkDepth];
+#pragma unroll
+      for (int d = 0; d < kLinkDepth; ++d) {
+        const int64_t r = r0 + d * step;
+        it[d].kdst = nullptr;
+        if (r < hi) it[d] = link::load_item_at<__bf16, kI>(ln.args, ln.tab, sh, r, u);
+      }
+#pragma unroll
+      for (int d = 0; d < kLinkDepth; ++d) link::finish_item<__bf16, kI>(it[d], sh);
+    }
+  };
+  if (ln.args.interleaved) {
+    run(std::true_type{});
+  } else {
+    run(std::false_type{});
+  }
+}
+
+template <typename Extra>
+__global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra extra) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];  // LDS_BYTES: ring of K|V blocks
 
+  if constexpr (std::is_same<Extra, LinkNext>::value) {
+    if (static_cast<int>(blockIdx.x) >= a.n_tiles) {
+      link_share(extra, static_cast<int>(blockIdx.x) - a.n_tiles);
+      return;
+    }
+  }
   const AttnTile tile = a.tiles[blockIdx.x];
   if (tile.n_rows <= 0) return;  // padding entry of the launch order
   const int tid = threadIdx.x;
@@ -523,7 +589,8 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
 
 }  // namespace
 
-hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t stream) {
+hipError_t launch_attn_bf16(const AttnArgs& a, const AssembleArgs* next, const AssembleSrcTable* next_tab,
+                            hipStream_t stream) {
   if (a.n_tiles <= 0) return hipSuccess;
   // 128 KB of dynamic LDS needs an explicit opt-in, once per device
   static bool opted_in[64] = {};
@@ -531,12 +598,28 @@ hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t stream) {
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
   if (dev >= 0 && dev < 64 && !opted_in[dev]) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bf16_kernel),
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bf16_kernel<NoLink>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bf16_kernel<LinkNext>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
     if (e != hipSuccess) return e;
     opted_in[dev] = true;
   }
-  hipLaunchKernelGGL(attn_bf16_kernel, dim3(a.n_tiles), dim3(THREADS), LDS_BYTES, stream, a);
+  const int64_t n_pos = next ? next->pos_end - next->pos_begin : 0;
+  if (n_pos > 0) {
+    LinkNext ln;
+    ln.args = *next;
+    ln.tab = *next_tab;
+    // kLinkRounds trips of the loop per workgroup: short enough to fill the gaps the last
+    // attention tiles leave
+    const int64_t rows_per_pass = THREADS / (next->n_kv_heads * (next->head_dim / 2 / 8));
+    const int64_t rows_per_wg = kLinkRounds * kLinkDepth * rows_per_pass;
+    ln.n_wgs = static_cast<int32_t>(std::max<int64_t>(1, (n_pos + rows_per_wg - 1) / rows_per_wg));
+    hipLaunchKernelGGL(attn_bf16_kernel<LinkNext>, dim3(a.n_tiles + ln.n_wgs), dim3(THREADS), LDS_BYTES, stream, a, ln);
+  } else {
+    hipLaunchKernelGGL(attn_bf16_kernel<NoLink>, dim3(a.n_tiles), dim3(THREADS), LDS_BYTES, stream, a, NoLink{});
+  }
   if (a.n_merges > 0)
     hipLaunchKernelGGL(attn_merge_kernel, dim3(a.n_merges, kAttnTileRows / 8), dim3(256), 0, stream, a);
   return hipGetLastError();

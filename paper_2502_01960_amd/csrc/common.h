@@ -120,9 +120,16 @@ int bind_device(mpic_ctx* ctx);
 int assemble_parts(mpic_ctx* ctx, mpic_plan* plan, const mpic_chunk_src* srcs, int32_t n_srcs,
                    const void* fresh_k, const void* fresh_v, int64_t n_fresh_rows, void* k_ctx,
                    void* v_ctx, int64_t n_ctx_slots, uint32_t parts, void* stream);
+// Stored rows of the next layer's context, to be linked along with an attention call.
+struct NextLink {
+  const mpic_chunk_src* srcs;
+  int32_t n_srcs;
+  void* k_ctx;
+  void* v_ctx;
+};
 int attend(mpic_ctx* ctx, mpic_plan* plan, const void* fresh_q, int64_t n_fresh_rows,
            const void* k_ctx, const void* v_ctx, int64_t n_ctx_slots, double softmax_scale, void* out,
-           float* lse, void* stream);
+           float* lse, void* stream, const NextLink* next);
 
 // Rows of the attention tile handled by one workgroup of the bf16 kernel.
 constexpr int kAttnTileRows = 256;
@@ -183,7 +190,10 @@ struct AttnArgs {
   const float* q_sin;
   int32_t interleaved;
 };
-hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t stream);
+// `next` / `next_tab` non-null: workgroups after the attention tiles link those rows (stored
+// rows of the next layer's context; device-resident sources only, at most kMaxInstPerLaunch).
+hipError_t launch_attn_bf16(const AttnArgs& a, const AssembleArgs* next, const AssembleSrcTable* next_tab,
+                            hipStream_t stream);
 
 // Keys of a decode split are a multiple of this (four wavefronts x 32-key blocks).
 constexpr int kDecodeBlockKeys = 128;

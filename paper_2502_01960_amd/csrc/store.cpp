@@ -608,29 +608,9 @@ int prefill_layers(mpic_ctx* ctx, mpic_plan* plan, mpic_store* st, const uint64_
   const int host_route = 4 * rows_used > 5 * rows_stored ? MPIC_SRC_HOST_STAGED : MPIC_SRC_HOST_MAPPED;
   hipStream_t ring_reader = host_route == MPIC_SRC_HOST_MAPPED ? ctx->link_stream : ctx->side_stream;
   std::vector<mpic_chunk_src> srcs(std::max(n_srcs, 0));
-  std::unordered_map<const void*, int32_t> last_reader;  // context buffer -> layer whose attention read it last
-  for (int32_t l = 0; l < n_layers; ++l) {
-    if (n_disk > 0) {
-      std::unique_lock<std::mutex> lock(st->mu);
-      st->cv.wait(lock, [&] { return batch.done[l] == static_cast<int>(n_disk); });
-      lock.unlock();
-      bool bad = false;
-      for (size_t j = l * n_disk; j < (l + 1) * n_disk; ++j) {
-        if (!batch.jobs[j].ok) {
-          bad = true;
-          if (failed) failed[batch.jobs[j].src] = 1;
-        }
-      }
-      if (bad) {
-        end_batch(st, &batch);
-        batch_end.on = false;
-        for (size_t j = l * n_disk; j < (l + 1) * n_disk; ++j)
-          if (!batch.jobs[j].ok) drop(st, ids[batch.jobs[j].src]);
-        return fail(ctx, MPIC_ERR_CACHE_MISS, "prefill_layers: a block of a stored cache failed its check while loading");
-      }
-    }
+  auto fill_srcs = [&](int32_t l, std::vector<mpic_chunk_src>& out) {
     for (int32_t s = 0; s < n_srcs; ++s) {
-      mpic_chunk_src& c = srcs[s];
+      mpic_chunk_src& c = out[s];
       c = mpic_chunk_src{};
       if (!entry[s]) {
         // not read by the plan: only its length is looked at
@@ -652,6 +632,67 @@ int prefill_layers(mpic_ctx* ctx, mpic_plan* plan, mpic_store* st, const uint64_
         c.on_host = entry[s]->tier == MPIC_TIER_HBM ? MPIC_SRC_DEVICE : host_route;
       }
     }
+  };
+
+  // Every cache the plan reads is in GPU memory: nothing to fetch ahead, so the stored rows of
+  // layer l+1 are linked by the attention launch of layer l itself, in workgroups that run as
+  // that attention drains.  One stream, no events.  (A context buffer shared by consecutive
+  // layers cannot be written while it is read: those layers are linked by a launch of their own.)
+  if (rows_stored == 0) {
+    std::vector<mpic_chunk_src> next_srcs(std::max(n_srcs, 0));
+    const size_t ctx_bytes = static_cast<size_t>(n_ctx_slots) * st->row_bytes;
+    auto overlap = [&](const void* x, const void* y) {
+      const char* a0 = static_cast<const char*>(x);
+      const char* b0 = static_cast<const char*>(y);
+      return a0 < b0 + ctx_bytes && b0 < a0 + ctx_bytes;
+    };
+    bool linked = false;  // stored rows of the current layer are already in place
+    for (int32_t l = 0; l < n_layers; ++l) {
+      if (!linked) {
+        fill_srcs(l, srcs);
+        rc = mpic::assemble_parts(ctx, plan, srcs.data(), n_srcs, nullptr, nullptr, 0, k_ctx[l], v_ctx[l], n_ctx_slots,
+                                  MPIC_PART_CACHED, stream);
+        if (rc != MPIC_OK) return rc;
+      }
+      rc = mpic::assemble_parts(ctx, plan, nullptr, 0, fresh_k[l], fresh_v[l], n_fresh_rows, k_ctx[l], v_ctx[l],
+                                n_ctx_slots, MPIC_PART_FRESH, stream);
+      if (rc != MPIC_OK) return rc;
+      linked = l + 1 < n_layers && !overlap(k_ctx[l + 1], k_ctx[l]) && !overlap(k_ctx[l + 1], v_ctx[l]) &&
+               !overlap(v_ctx[l + 1], k_ctx[l]) && !overlap(v_ctx[l + 1], v_ctx[l]);
+      mpic::NextLink next{next_srcs.data(), n_srcs, nullptr, nullptr};
+      if (linked) {
+        fill_srcs(l + 1, next_srcs);
+        next.k_ctx = k_ctx[l + 1];
+        next.v_ctx = v_ctx[l + 1];
+      }
+      rc = mpic::attend(ctx, plan, fresh_q[l], n_fresh_rows, k_ctx[l], v_ctx[l], n_ctx_slots, softmax_scale, out[l],
+                        lse ? lse[l] : nullptr, stream, linked ? &next : nullptr);
+      if (rc != MPIC_OK) return rc;
+    }
+    return MPIC_OK;
+  }
+  std::unordered_map<const void*, int32_t> last_reader;  // context buffer -> layer whose attention read it last
+  for (int32_t l = 0; l < n_layers; ++l) {
+    if (n_disk > 0) {
+      std::unique_lock<std::mutex> lock(st->mu);
+      st->cv.wait(lock, [&] { return batch.done[l] == static_cast<int>(n_disk); });
+      lock.unlock();
+      bool bad = false;
+      for (size_t j = l * n_disk; j < (l + 1) * n_disk; ++j) {
+        if (!batch.jobs[j].ok) {
+          bad = true;
+          if (failed) failed[batch.jobs[j].src] = 1;
+        }
+      }
+      if (bad) {
+        end_batch(st, &batch);
+        batch_end.on = false;
+        for (size_t j = l * n_disk; j < (l + 1) * n_disk; ++j)
+          if (!batch.jobs[j].ok) drop(st, ids[batch.jobs[j].src]);
+        return fail(ctx, MPIC_ERR_CACHE_MISS, "prefill_layers: a block of a stored cache failed its check while loading");
+      }
+    }
+    fill_srcs(l, srcs);
     // stored rows: on the library's stream, after whatever last read these buffers
     for (const void* buf : {static_cast<const void*>(k_ctx[l]), static_cast<const void*>(v_ctx[l])}) {
       auto it = last_reader.find(buf);
@@ -674,7 +715,7 @@ int prefill_layers(mpic_ctx* ctx, mpic_plan* plan, mpic_store* st, const uint64_
     if (rc != MPIC_OK) return rc;
     MPIC_HIP(ctx, hipStreamWaitEvent(stream, ctx->ev_layer[2 * l], 0));
     rc = mpic::attend(ctx, plan, fresh_q[l], n_fresh_rows, k_ctx[l], v_ctx[l], n_ctx_slots, softmax_scale, out[l],
-                      lse ? lse[l] : nullptr, stream);
+                      lse ? lse[l] : nullptr, stream, nullptr);
     if (rc != MPIC_OK) return rc;
     MPIC_HIP(ctx, hipEventRecord(ctx->ev_layer[2 * l + 1], stream));
     last_reader[k_ctx[l]] = l;

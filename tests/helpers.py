@@ -163,7 +163,7 @@ class LayeredProblem:
         self.ids = [id_base + s for s in range(self.n_src)]
         dt = mpic.MPIC_F32 if sh.dtype == "f32" else mpic.MPIC_BF16
         self.ctx = mpic.Context(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, dt, sh.rope_theta, 0, self.page_size, 0)
-        self.store = mpic.Store(self.ctx, n_layers, disk_dir, io_threads)
+        self.store = mpic.Store(self.ctx, n_layers, None if disk_dir is None else str(disk_dir), io_threads)
         self.model = ChunkStore()
         self.raw = {}
         for s in range(self.n_src):

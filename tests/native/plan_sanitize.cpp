@@ -11,7 +11,7 @@
 
 namespace mpic {
 hipError_t launch_assemble(int, const AssembleArgs&, const AssembleSrcTable&, hipStream_t) { return hipSuccess; }
-hipError_t launch_attn_bf16(const AttnArgs&, hipStream_t) { return hipSuccess; }
+hipError_t launch_attn_bf16(const AttnArgs&, const AssembleArgs*, const AssembleSrcTable*, hipStream_t) { return hipSuccess; }
 hipError_t launch_attn_f32(const AttnArgs&, int64_t, hipStream_t) { return hipSuccess; }
 hipError_t launch_decode(int, const DecodeArgs&, hipStream_t) { return hipSuccess; }
 }  // namespace mpic

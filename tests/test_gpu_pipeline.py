@@ -30,6 +30,54 @@ def test_layers_from_all_three_tiers_match_the_oracle(tmp_path):
     p.close()
 
 
+def test_layers_from_hbm_are_linked_by_the_attention_launch(tmp_path):
+    print("pipeline: all caches in HBM, next layer linked in the tail of the attention launch", flush=True)
+    p = LayeredProblem(3, 4, (HBM,), None, **SMALL3)
+    p.plan_for()
+    assert p.gpu_run() is None
+    ref = p.oracle_run()
+    p.check(ref)
+    assert p.gpu_run(shared_buffers=True) is None           # one buffer for all layers: linked by separate launches
+    p.check(ref, kv_layers=[p.n_layers - 1])
+    p.close()
+    # paged context, key-cut tiles (one long request), fresh rows handed over rotated
+    p = LayeredProblem(5, 3, (HBM,), None, n_chunks=4, chunk_len=200, text_len=20)
+    p.plan_for()
+    assert p.gpu_run(lse=False) is None
+    p.check(p.oracle_run(rows=np.arange(0, int(p.oplan["q_off"][-1]), 3)))
+    p.close()
+
+
+def test_attention_with_the_next_layer_linked_equals_separate_calls(tmp_path):
+    print("mpic_selective_attn_link_next against mpic_selective_attn + mpic_assemble_kv_parts", flush=True)
+    from helpers import Problem
+    for cfg, kw, host in ((3, dict(n_chunks=3, chunk_len=301, text_len=37, batch=2), False),
+                          (3, dict(n_chunks=3, chunk_len=301, text_len=37, batch=2), True),     # pinned sources: own launch
+                          (1, {}, False),                                                       # fp32: own launch
+                          (5, dict(n_chunks=5, chunk_len=203, text_len=21), False)):
+        a, b = Problem(cfg, **kw), Problem(cfg, layer=1, **kw)
+        a.gpu_setup(host_sourced=host)
+        b.gpu_setup(host_sourced=host)
+        a.gpu_assemble()
+        # reference: attention of layer a, then the stored rows of layer b by a call of its own
+        a.gpu_attend()
+        ref_k, ref_v = torch.full_like(b.k_ctx, float("nan")), torch.full_like(b.v_ctx, float("nan"))
+        mpic.mpic_assemble_kv_parts(a.ctx.handle, a.plan.handle, b.srcs, None, None, ref_k, ref_v, mpic.MPIC_PART_CACHED)
+        torch.cuda.synchronize()
+        ref_out = a.out.clone()
+        a.out.fill_(float("nan"))
+        mpic.mpic_selective_attn_link_next(a.ctx.handle, a.plan.handle, a.d_q, a.k_ctx, a.v_ctx, a.sh.softmax_scale,
+                                           a.out, b.srcs, b.k_ctx, b.v_ctx, a.lse)
+        torch.cuda.synchronize()
+        bits = lambda t: t.view(torch.int16 if t.dtype == torch.bfloat16 else torch.int32)
+        assert torch.equal(bits(a.out), bits(ref_out))
+        assert torch.equal(bits(b.k_ctx), bits(ref_k)) and torch.equal(bits(b.v_ctx), bits(ref_v))
+        # overlapping buffers are refused before anything runs
+        with pytest.raises(mpic.MpicError):
+            mpic.mpic_selective_attn_link_next(a.ctx.handle, a.plan.handle, a.d_q, a.k_ctx, a.v_ctx,
+                                               a.sh.softmax_scale, a.out, b.srcs, a.k_ctx, b.v_ctx)
+
+
 def test_tiny_fp32_layers_from_disk(tmp_path):
     print("pipeline: fp32 config, all caches on disk, 4 layers, one reader", flush=True)
     p = LayeredProblem(1, 4, (DISK,), tmp_path, io_threads=1)
