@@ -116,6 +116,13 @@ enum {
   MPIC_PLAN_INST_K = 11,     /* [n_inst] effective k = min(k, len); listed set: its leading run */
   MPIC_PLAN_INST_REQ = 12,   /* [n_inst] owning request                                        */
   MPIC_PLAN_RUNS = 13,       /* [n_runs][4] (request, first fresh row, length, first position) */
+  MPIC_PLAN_LAUNCH_ESTIMATE = 15, /* [4] the planner's simulation of the attention launch: its  */
+                             /* duration and the compute-unit time it leaves idle (summed over */
+                             /* the chip), both in 64-key blocks of one tile; 1 if a launch    */
+                             /* can carry the linking of the next layer                        */
+                             /* (mpic_selective_attn_link_next); 1 if that is also predicted   */
+                             /* to pay (the linking fits into the idle time, or the launch is  */
+                             /* too short for a second stream to help)                         */
   MPIC_PLAN_ATTN_TILES = 14  /* [n_tiles][8] launch order of the attention kernel: (request,   */
                              /* kv head, first flattened row, rows, end key, first key, slot   */
                              /* of the partial result or -1, 0); flattened row = (fresh row -  */

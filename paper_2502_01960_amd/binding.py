@@ -13,7 +13,7 @@ MPIC_F32, MPIC_BF16 = 0, 1
 
 PLAN_FIELDS = dict(ctx_off=0, q_off=1, q_pos=2, q_req=3, slot_map=4, src_inst=5, src_row=6,
                    dst_slot=7, inst_src=8, inst_delta=9, inst_len=10, inst_k=11, inst_req=12,
-                   runs=13, attn_tiles=14)
+                   runs=13, attn_tiles=14, launch_estimate=15)
 
 
 class MpicError(RuntimeError):

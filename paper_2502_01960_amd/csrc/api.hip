@@ -419,10 +419,7 @@ int mpic::attend(mpic_ctx* ctx, mpic_plan* plan, const void* fresh_q,
       return fail(ctx, MPIC_ERR_INVALID, "selective_attn: the next layer's context must not overlap the one being read");
     if (n_inst > 0 && (!next->srcs || next->n_srcs <= plan->max_src))
       return fail(ctx, MPIC_ERR_INVALID, "selective_attn: next layer's srcs does not cover every chunk index of the plan");
-    // (the trailing workgroups of 512 threads give every thread one unit pair of a row)
-    const int pairs_per_row = ctx->cfg.n_kv_heads * (ctx->cfg.head_dim / 16);
-    fuse_next = ctx->cfg.dtype == MPIC_BF16 && n_inst <= static_cast<size_t>(mpic::kMaxInstPerLaunch) &&
-                !plan->tiles.empty() && pairs_per_row <= 512 && 512 % pairs_per_row == 0;
+    fuse_next = mpic::can_link_in_attention(ctx, plan);
     for (size_t i = 0; i < n_inst; ++i) {
       const mpic_chunk_src& sc = next->srcs[plan->inst_src[i]];
       if (sc.len != plan->inst_len[i]) return fail(ctx, MPIC_ERR_INVALID, "selective_attn: next layer's chunk source length differs from its segment");

@@ -96,6 +96,11 @@ struct mpic_plan {
   std::vector<mpic::AttnTile> tiles;
   std::vector<mpic::AttnMerge> merges;  // tiles cut along the keys
   int32_t n_parts = 0;                  // partial-result slots those tiles use
+  // the planner's simulation of the attention launch, in 64-key blocks of one tile: when the
+  // last workgroup ends, and the compute-unit time left idle until then (summed over the chip)
+  int64_t est_makespan_blocks = 0;
+  int64_t est_idle_blocks = 0;
+  std::vector<int32_t> launch_est;  // MPIC_PLAN_LAUNCH_ESTIMATE
   std::vector<float> rope_cos, rope_sin;
   std::vector<int32_t> fresh_rot;            // contexts with fresh_pre_rope only
   std::vector<float> fresh_cos, fresh_sin;   // one row per distinct position id
@@ -217,5 +222,27 @@ struct DecodeArgs {
 };
 hipError_t launch_decode(int dtype, const DecodeArgs& a, hipStream_t stream);
 hipError_t launch_attn_f32(const AttnArgs& a, int64_t n_q, hipStream_t stream);
+
+
+// Can the attention launch of this plan carry the linking of the next layer (device-resident
+// sources assumed)?  The trailing workgroups of 512 threads give every thread one unit pair of a row.
+inline bool can_link_in_attention(const mpic_ctx* ctx, const mpic_plan* plan) {
+  const int pairs_per_row = ctx->cfg.n_kv_heads * (ctx->cfg.head_dim / 16);
+  return ctx->cfg.dtype == MPIC_BF16 && plan->inst_src.size() <= static_cast<size_t>(kMaxInstPerLaunch) &&
+         !plan->tiles.empty() && pairs_per_row <= 512 && 512 % pairs_per_row == 0;
+}
+// ... and does it pay?  Yes when the linking is predicted to fit into the time the launch leaves
+// idle (a 64-key block of a 256-row tile takes about 2.1 us; a linking launch of its own moves
+// about 6 TB/s), and for short launches in any case: there the events of a two-stream schedule
+// cost more than the linking itself (2.6K-token request: 59 us per layer against 100 us).
+inline bool link_fits_attention_tail(const mpic_ctx* ctx, const mpic_plan* plan) {
+  int64_t rows = 0;
+  for (int32_t r : plan->inst_cached) rows += r;
+  const double row_bytes = static_cast<double>(ctx->cfg.n_kv_heads) * ctx->cfg.head_dim * (ctx->cfg.dtype == MPIC_F32 ? 4 : 2);
+  const double link_us = 4.0 * static_cast<double>(rows) * row_bytes / 6.0e6;
+  const double idle_us = static_cast<double>(plan->est_idle_blocks) * 2.1 / 256.0;
+  const double launch_us = static_cast<double>(plan->est_makespan_blocks) * 2.1;
+  return link_us <= idle_us || launch_us < 500.0;
+}
 
 }  // namespace mpic

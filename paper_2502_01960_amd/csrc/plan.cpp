@@ -193,14 +193,18 @@ void build_tiles(mpic_plan& p, int group, int n_kv_heads) {
   // Predicted duration of a launch, in blocks: every L2 domain hands its tiles in order to
   // whichever of its compute units is free first; a piece of a cut tile costs three blocks
   // more than its keys (prologue, partial result, share of the merge).
+  int64_t busy_blocks = 0;  // compute-unit time the tiles of the last simulated layout take, in blocks
   auto predicted_makespan = [&](const Layout& l) {
     int64_t worst = 0;
+    busy_blocks = 0;
     auto heavier = std::greater<int64_t>();
     for (const auto& q : l.queue) {
       std::vector<int64_t> load(kComputeUnits / kXcds, 0);  // min-heap of compute unit loads
       for (const Item& it : q) {
         std::pop_heap(load.begin(), load.end(), heavier);
-        load.back() += (it.t.n_keys - it.t.key0 + kBlock - 1) / kBlock + 2 + (it.t.part >= 0 ? 3 : 0);
+        const int64_t cost = (it.t.n_keys - it.t.key0 + kBlock - 1) / kBlock + 2 + (it.t.part >= 0 ? 3 : 0);
+        load.back() += cost;
+        busy_blocks += cost;
         std::push_heap(load.begin(), load.end(), heavier);
       }
       worst = std::max(worst, *std::max_element(load.begin(), load.end()));
@@ -233,6 +237,9 @@ void build_tiles(mpic_plan& p, int group, int n_kv_heads) {
       }
     }
   }
+  // what the launch is predicted to leave idle: room for work that rides along in its tail
+  p.est_makespan_blocks = predicted_makespan(chosen);
+  p.est_idle_blocks = p.est_makespan_blocks * kComputeUnits - busy_blocks;
   p.merges = std::move(chosen.merges);
   p.n_parts = chosen.n_parts;
   size_t depth = 0;
@@ -502,6 +509,12 @@ extern "C" int mpic_plan_create_selected(mpic_ctx* ctx, int32_t n_requests, cons
       }
     if (ctx->cfg.fresh_pre_rope) mpic::build_fresh_rope(*p, ctx->cfg);
     mpic::build_tiles(*p, ctx->group, ctx->cfg.n_kv_heads);
+    {
+      auto clamp = [](int64_t x) { return static_cast<int32_t>(std::min<int64_t>(x, INT32_MAX)); };
+      p->launch_est = {clamp(p->est_makespan_blocks), clamp(p->est_idle_blocks),
+                       mpic::can_link_in_attention(ctx, p) ? 1 : 0,
+                       mpic::can_link_in_attention(ctx, p) && mpic::link_fits_attention_tail(ctx, p) ? 1 : 0};
+    }
   } catch (const std::bad_alloc&) {
     delete p;
     return fail(ctx, MPIC_ERR_OOM, "plan_create: out of host memory");
@@ -528,6 +541,7 @@ extern "C" int mpic_plan_get(const mpic_plan* plan, int32_t what, const int32_t*
     case MPIC_PLAN_INST_K: v = &plan->inst_k; break;
     case MPIC_PLAN_INST_REQ: v = &plan->inst_req; break;
     case MPIC_PLAN_RUNS: v = &plan->runs; break;
+    case MPIC_PLAN_LAUNCH_ESTIMATE: v = &plan->launch_est; break;
     case MPIC_PLAN_ATTN_TILES:
       *host_ptr = reinterpret_cast<const int32_t*>(plan->tiles.data());
       *n = plan->tiles.size() * 8;

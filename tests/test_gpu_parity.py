@@ -13,7 +13,7 @@ from helpers import Problem, assert_bf16_close, assert_f32_close, err_stats
 
 pytestmark = pytest.mark.gpu
 
-INT_FIELDS = [f for f in mpic.PLAN_FIELDS if f != "attn_tiles"]
+INT_FIELDS = [f for f in mpic.PLAN_FIELDS if f not in ("attn_tiles", "launch_estimate")]
 
 
 def _check_plan(p):
