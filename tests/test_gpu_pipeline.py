@@ -119,6 +119,21 @@ def test_config3_full_size_layers_from_the_store_sampled(tmp_path):
     p.close()
 
 
+def test_config3_full_size_next_layer_linked_by_the_attention_launch_sampled():
+    print("pipeline: 18K-token batch of 4 at full size, caches in HBM, layer 1 linked by layer 0's attention launch", flush=True)
+    p = LayeredProblem(3, 2, (HBM,), None)
+    p.plan_for()
+    assert p.plan.get("launch_estimate")[3] == 1               # the schedule bench.py times for this workload
+    assert p.gpu_run(lse=False) is None
+    rng = np.random.default_rng(2)
+    rows = []
+    for (b, r0, ln, p0) in p.oplan["runs"].tolist():
+        rows += sorted({r0, r0 + ln - 1, r0 + int(rng.integers(0, ln))})
+    ref = p.oracle_run(rows=np.asarray(rows), layers=[1])
+    p.check(ref, layers=[1], kv_layers=[1])
+    p.close()
+
+
 def test_expired_cache_is_recomputed(tmp_path):
     print("pipeline: expiry -> lookup -> plan with the chunk recomputed", flush=True)
     p = LayeredProblem(3, 2, (HBM, DISK, HOST), tmp_path, **SMALL3)
