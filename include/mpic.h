@@ -302,10 +302,14 @@ int mpic_selective_attn(mpic_ctx* ctx, mpic_plan* plan, const void* fresh_q, int
  *   next_srcs[n_srcs]        chunk caches of the next layer, as for mpic_assemble_kv
  *   next_k_ctx, next_v_ctx   device, n_ctx_slots rows each, written; must not overlap
  *                            k_ctx / v_ctx
- * The fused launch needs bf16, device-resident sources and at most 128 chunk instances
- * in the plan; otherwise (and when the recompute set is empty) the call does the same
- * work with a launch of its own after the attention.  The fresh rows of the next layer
- * are not touched: link them (MPIC_PART_FRESH) before that layer's attention.
+ * The fused launch needs bf16, device-resident sources, at most 128 chunk instances in
+ * the plan and Hkv * D / 16 dividing 512; otherwise (and when the recompute set is empty)
+ * the call does the same work with a launch of its own after the attention.  Whether
+ * fusing pays depends on how much of the chip the attention tiles leave idle at the end:
+ * MPIC_PLAN_LAUNCH_ESTIMATE holds the planner's prediction (a batch whose tiles fill the
+ * chip evenly is better served by MPIC_PART_CACHED | MPIC_PART_BACKGROUND on a second
+ * stream).  The fresh rows of the next layer are not touched: link them
+ * (MPIC_PART_FRESH) before that layer's attention.
  * Errors: as mpic_selective_attn and mpic_assemble_kv; INVALID if the buffers overlap.
  */
 int mpic_selective_attn_link_next(mpic_ctx* ctx, mpic_plan* plan, const void* fresh_q, int64_t n_fresh_rows,
