@@ -145,7 +145,7 @@ class LayeredProblem:
     oracle.store.ChunkStore on the oracle side, both filled with the same seeded bytes)."""
 
     def __init__(self, cfg_id, n_layers, tiers, disk_dir, *, k=None, paged=None, io_threads=0, id_base=1000,
-                 custom=None, **layout_kw):
+                 custom=None, interleaved=False, pre_rope=False, **layout_kw):
         from oracle.store import ChunkStore
         self.sh = sh = workloads.shape(cfg_id)
         self.n_layers = n_layers
@@ -162,7 +162,9 @@ class LayeredProblem:
             self.n_slots = max(1, sum(lens))
         self.ids = [id_base + s for s in range(self.n_src)]
         dt = mpic.MPIC_F32 if sh.dtype == "f32" else mpic.MPIC_BF16
-        self.ctx = mpic.Context(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, dt, sh.rope_theta, 0, self.page_size, 0)
+        self.interleaved, self.pre_rope = interleaved, pre_rope
+        self.ctx = mpic.Context(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, dt, sh.rope_theta, int(interleaved),
+                                self.page_size, int(pre_rope))
         self.store = mpic.Store(self.ctx, n_layers, None if disk_dir is None else str(disk_dir), io_threads)
         self.model = ChunkStore()
         self.raw = {}
@@ -216,7 +218,7 @@ class LayeredProblem:
         f64 = lambda t: t.to(torch.float64).numpy()
         return prefill_layers(self.oplan, self.ids, self.model, self.n_layers,
                               lambda l: tuple(f64(t) for t in self.fresh[l]), self.sh.rope_theta,
-                              self.sh.softmax_scale, rows=rows, layers=layers)
+                              self.sh.softmax_scale, self.interleaved, self.pre_rope, rows=rows, layers=layers)
 
     def check(self, ref, layers=None, kv_layers=None):
         """Outputs of `layers` and linked contexts of `kv_layers` against the oracle's."""

@@ -48,6 +48,21 @@ def test_layers_from_hbm_are_linked_by_the_attention_launch(tmp_path):
     p.close()
 
 
+def test_other_rotary_pairing_and_unpositioned_fresh_rows_through_the_pipeline(tmp_path):
+    print("pipeline: interleaved rotary pairs, fresh rows before positional embedding; HBM (fused launch) and mixed tiers", flush=True)
+    for tiers, d in (((HBM,), None), ((DISK, HOST, HBM), tmp_path)):
+        p = LayeredProblem(3, 3, tiers, d, interleaved=True, pre_rope=True, **SMALL3)
+        p.plan_for()
+        assert p.gpu_run() is None
+        p.check(p.oracle_run())
+        p.close()
+    p = LayeredProblem(3, 2, (HBM,), None, interleaved=False, pre_rope=True, **SMALL3)
+    p.plan_for()
+    assert p.gpu_run() is None
+    p.check(p.oracle_run())
+    p.close()
+
+
 def test_attention_with_the_next_layer_linked_equals_separate_calls(tmp_path):
     print("mpic_selective_attn_link_next against mpic_selective_attn + mpic_assemble_kv_parts", flush=True)
     from helpers import Problem
