@@ -406,7 +406,7 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import attend as o_attend, build_plan, link_kv, position_fresh
-        n_req = min(2, len(requests))
+        n_req = min(3, len(requests))
         sub = requests[:n_req]
         oplan = build_plan(sub, sh.default_k)
         f64 = lambda t: t.to(torch.float64).numpy()
@@ -416,16 +416,21 @@ def main():
         fq = np.concatenate([f64(f[0]) for f in fresh])
         fk = np.concatenate([f64(f[1]) for f in fresh])
         fv = np.concatenate([f64(f[2]) for f in fresh])
+        # bounded sample: at most about 1.2 TFLOP of attention (every m-th fresh row of the sample)
+        opos = oplan["q_pos"].astype(np.int64)
+        every = max(1, int(np.ceil(4.0 * sh.head_dim * sh.n_q_heads * int((opos + 1).sum()) / 1.2e12)))
+        rows = np.arange(0, len(opos), every)
         t0 = time.perf_counter()
         K, V = link_kv(oplan, ck, cv, fk, fv, sh.rope_theta, False, args.fresh_pre_rope)
         if args.fresh_pre_rope:
             fq = position_fresh(fq, oplan, sh.rope_theta)
-        o_attend(fq, K, V, oplan, sh.softmax_scale)
+        o_attend(fq, K, V, oplan, sh.softmax_scale, rows=None if every == 1 else rows)
         dt = time.perf_counter() - t0
-        fl = 4.0 * sh.head_dim * sh.n_q_heads * int((oplan["q_pos"].astype(np.int64) + 1).sum())
+        fl = 4.0 * sh.head_dim * sh.n_q_heads * int((opos[rows] + 1).sum())
         cpu = dict(value=round(fl / dt / 1e12, 6), unit="TFLOP/s", cores=int(torch.get_num_threads()),
                    kind="oracle", seconds=round(dt, 2),
-                   sample=f"requests 0..{n_req - 1} of the batch: float64 link of all rows + attention of every fresh row, all heads")
+                   sample=f"requests 0..{n_req - 1} of the batch: float64 link of all rows + attention of "
+                          f"{'every' if every == 1 else f'every {every}th'} fresh row, all heads")
 
     traffic = None
     tfile = os.path.join(ROOT, "profiles", "attn_traffic.json")
