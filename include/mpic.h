@@ -142,6 +142,19 @@ enum {
  */
 int mpic_create(mpic_ctx** out, const mpic_config* config);
 
+/*
+ * Options of a context.
+ *   MPIC_OPT_ATTN_BLOCK_KEYS  keys per LDS block of the bf16 attention kernel: 64, 96, or 0 =
+ *     the library chooses (default).  96 is the faster shape when the launch has the chip to
+ *     itself; 64 uses fewer registers and leaves room on every SIMD for a wave of another
+ *     kernel, which is what linking on a second stream (MPIC_PART_BACKGROUND,
+ *     MPIC_SRC_HOST_MAPPED) needs to overlap with the attention.  With 0 a context uses 96 until
+ *     it has linked that way once, then 64; mpic_prefill_layers picks per call.
+ * Errors: INVALID (unknown option or value).
+ */
+enum { MPIC_OPT_ATTN_BLOCK_KEYS = 1 };
+int mpic_set_option(mpic_ctx* ctx, int32_t option, int64_t value);
+
 /* Destroy a context after all of its plans.  Waits for the side stream.  NULL is allowed. */
 void mpic_destroy(mpic_ctx* ctx);
 

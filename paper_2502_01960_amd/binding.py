@@ -55,6 +55,8 @@ def load_library():
     vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
     lib.mpic_create.argtypes = [C.POINTER(vp), C.POINTER(_Config)]
     lib.mpic_create.restype = C.c_int
+    lib.mpic_set_option.argtypes = [vp, i32, i64]
+    lib.mpic_set_option.restype = C.c_int
     lib.mpic_destroy.argtypes = [vp]
     lib.mpic_destroy.restype = None
     lib.mpic_plan_create.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(_Segment), i32,
@@ -143,6 +145,13 @@ def mpic_create(n_q_heads, n_kv_heads, head_dim, dtype, rope_theta, rope_interle
 
 def mpic_destroy(ctx):
     load_library().mpic_destroy(ctx)
+
+
+MPIC_OPT_ATTN_BLOCK_KEYS = 1
+
+
+def mpic_set_option(ctx, option, value):
+    _check(load_library().mpic_set_option(ctx, int(option), int(value)), ctx)
 
 
 def _i32_array(values):
@@ -420,6 +429,9 @@ class Context:
                                   fresh_pre_rope)
         self.n_q_heads, self.n_kv_heads, self.head_dim = n_q_heads, n_kv_heads, head_dim
         self.dtype, self.page_size = dtype, page_size
+
+    def set_option(self, option, value):
+        mpic_set_option(self.handle, option, value)
 
     def close(self):
         if self.handle is not None:

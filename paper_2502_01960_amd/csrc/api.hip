@@ -171,6 +171,7 @@ int mpic::assemble_parts(mpic_ctx* ctx, mpic_plan* plan, const mpic_chunk_src* s
                                   int64_t n_ctx_slots, uint32_t parts, void* stream_) {
   if (!ctx) return MPIC_ERR_INVALID;
   const bool background = parts & MPIC_PART_BACKGROUND;
+  if (background) ctx->background_seen = true;
   parts &= ~static_cast<uint32_t>(MPIC_PART_BACKGROUND);
   if (parts == 0 || (parts & ~static_cast<uint32_t>(MPIC_PART_CACHED | MPIC_PART_FRESH)))
     return fail(ctx, MPIC_ERR_INVALID, "assemble_kv: parts must be MPIC_PART_CACHED, MPIC_PART_FRESH or both");
@@ -197,6 +198,7 @@ int mpic::assemble_parts(mpic_ctx* ctx, mpic_plan* plan, const mpic_chunk_src* s
       any_mapped = any_mapped || s.on_host == MPIC_SRC_HOST_MAPPED;
     }
   }
+  if (any_mapped) ctx->background_seen = true;  // a launch that lasts as long as the transfer runs beside others
   int rc = mpic::bind_device(ctx);
   if (rc != MPIC_OK) return rc;
   rc = mpic::upload_plan(ctx, plan);
@@ -388,7 +390,7 @@ int mpic::assemble_parts(mpic_ctx* ctx, mpic_plan* plan, const mpic_chunk_src* s
 int mpic::attend(mpic_ctx* ctx, mpic_plan* plan, const void* fresh_q,
                                int64_t n_fresh_rows, const void* k_ctx, const void* v_ctx,
                                int64_t n_ctx_slots, double softmax_scale, void* out, float* lse,
-                               void* stream_, const mpic::NextLink* next) {
+                               void* stream_, const mpic::NextLink* next, int32_t block_keys) {
   if (!ctx) return MPIC_ERR_INVALID;
   if (!plan || plan->ctx != ctx) return fail(ctx, MPIC_ERR_INVALID, "selective_attn: plan does not belong to this context");
   if (n_fresh_rows != plan->n_q) return fail(ctx, MPIC_ERR_INVALID, "selective_attn: n_fresh_rows differs from the plan's recompute set");
@@ -474,6 +476,7 @@ int mpic::attend(mpic_ctx* ctx, mpic_plan* plan, const void* fresh_q,
     a.merges = plan->dev.merges;
     a.n_merges = static_cast<int32_t>(plan->merges.size());
   }
+  a.block_keys = block_keys ? block_keys : ctx->attn_block_keys ? ctx->attn_block_keys : ctx->background_seen ? 64 : 96;
   a.q_rot = plan->dev.fresh_rot;
   a.q_cos = plan->dev.fresh_cos;
   a.q_sin = plan->dev.fresh_sin;
@@ -615,6 +618,18 @@ extern "C" int mpic_selective_attn(mpic_ctx* ctx, mpic_plan* plan, const void* f
                                    void* stream) {
   MPIC_GUARDED(ctx, mpic::attend(ctx, plan, fresh_q, n_fresh_rows, k_ctx, v_ctx, n_ctx_slots, softmax_scale,
                                         out, lse, stream, nullptr))
+}
+
+extern "C" int mpic_set_option(mpic_ctx* ctx, int32_t option, int64_t value) {
+  if (!ctx) return MPIC_ERR_INVALID;
+  switch (option) {
+    case MPIC_OPT_ATTN_BLOCK_KEYS:
+      if (value != 0 && value != 64 && value != 96) return fail(ctx, MPIC_ERR_INVALID, "set_option: attention block must be 0, 64 or 96 keys");
+      ctx->attn_block_keys = static_cast<int32_t>(value);
+      return MPIC_OK;
+    default:
+      return fail(ctx, MPIC_ERR_INVALID, "set_option: unknown option");
+  }
 }
 
 extern "C" int mpic_selective_attn_link_next(mpic_ctx* ctx, mpic_plan* plan, const void* fresh_q,

@@ -42,18 +42,35 @@ typedef float f32x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x8_a4 __attribute__((ext_vector_type(8), aligned(4)));  // eight table entries, dword aligned
+typedef uint32_t u32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));
 
 constexpr int D = 128;   // head dim
-constexpr int BN = 64;   // keys per LDS stage
 constexpr int WAVES = 8;
 constexpr int ROWS_PER_WAVE = 32;
 constexpr int THREADS = WAVES * 64;
-constexpr int ROW_BYTES = D * 2;                 // one staged key or value row
-constexpr int TILE_BYTES = BN * ROW_BYTES;       // one staged K (or V) block: 16 KB
-constexpr int STAGE_BYTES = 2 * TILE_BYTES;      // K block followed by V block
-constexpr int STAGES = 4;                        // ring depth: loads run 3 blocks ahead
-constexpr int LDS_BYTES = STAGES * STAGE_BYTES;  // 128 KB of the CU's 160 KB
-constexpr int LOADS_PER_STAGE = 4;               // direct loads each wave issues per block
+constexpr int ROW_BYTES = D * 2;  // one staged key or value row
+
+// Keys per LDS block and what follows from it.  Two shapes are built:
+//   64 keys: K and V rings of four slots (128 KB), loads two blocks ahead, 204 registers -- leaves
+//            room on every SIMD for a wave of another kernel (linking on a second stream);
+//   96 keys: K ring of two slots, V ring of three (120 KB), loads one block ahead, 238 registers --
+//            a third fewer barriers and phase changes per key, 1 to 2.6 % faster alone, but nothing
+//            fits beside it (two-stream step of 8 requests x 16 chunks: 2.19 -> 2.32 ms).
+template <int kBlockKeys>
+struct Geo {
+  static_assert(kBlockKeys == 64 || kBlockKeys == 96, "block shapes with a ring layout");
+  static constexpr int BN = kBlockKeys;
+  static constexpr int KB = BN / 32;                 // 32-key matrix tiles per block
+  static constexpr int TILE_BYTES = BN * ROW_BYTES;  // one staged K (or V) block
+  static constexpr int K_SLOTS = BN == 64 ? 4 : 2;
+  static constexpr int V_SLOTS = BN == 64 ? 4 : 3;
+  static constexpr int AHEAD = BN == 64 ? 2 : 1;     // blocks the loads run ahead of their first use
+  static constexpr int LDS_BYTES = (K_SLOTS + V_SLOTS) * TILE_BYTES;
+  static constexpr int ROWS_LOADED_PER_WAVE = BN / WAVES;               // rows of K (and of V) a wave stages per block
+  static constexpr int LOADS_PER_STAGE = 2 * ROWS_LOADED_PER_WAVE / 4;  // direct loads each wave issues per block
+  __device__ static int k_slot_off(int t) { return (t % K_SLOTS) * TILE_BYTES; }
+  __device__ static int v_slot_off(int t) { return K_SLOTS * TILE_BYTES + (t % V_SLOTS) * TILE_BYTES; }
+};
 #ifndef MPIC_LINK_ROUNDS
 #define MPIC_LINK_ROUNDS 2
 #endif
@@ -98,6 +115,20 @@ __device__ inline void load4_to_lds_16B(const void* g0, const void* g1, const vo
       "s_mov_b32 m0, %7\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %3, off"
       :
       : "v"(g0), "v"(g1), "v"(g2), "v"(g3), "s"(l0), "s"(l1), "s"(l2), "s"(l3)
+      : "memory", "m0");
+}
+__device__ inline void load6_to_lds_16B(const void* g0, const void* g1, const void* g2, const void* g3, const void* g4,
+                                        const void* g5, uint32_t l0, uint32_t l1, uint32_t l2, uint32_t l3, uint32_t l4,
+                                        uint32_t l5) {
+  asm volatile(
+      "s_mov_b32 m0, %6\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off\n\t"
+      "s_mov_b32 m0, %7\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\t"
+      "s_mov_b32 m0, %8\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\t"
+      "s_mov_b32 m0, %9\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %3, off\n\t"
+      "s_mov_b32 m0, %10\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %4, off\n\t"
+      "s_mov_b32 m0, %11\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %5, off"
+      :
+      : "v"(g0), "v"(g1), "v"(g2), "v"(g3), "v"(g4), "v"(g5), "s"(l0), "s"(l1), "s"(l2), "s"(l3), "s"(l4), "s"(l5)
       : "memory", "m0");
 }
 // s_waitcnt vmcnt(n) only (expcnt / lgkmcnt fields left at "no wait")
@@ -185,9 +216,14 @@ __device__ inline void link_share(const LinkNext& ln, int j) {
   }
 }
 
-template <typename Extra>
+template <int kBlockKeys, typename Extra>
 __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra extra) {
-  extern __shared__ __attribute__((aligned(1024))) char lds[];  // LDS_BYTES: ring of K|V blocks
+  using G = Geo<kBlockKeys>;
+  constexpr int BN = G::BN, KB = G::KB, TILE_BYTES = G::TILE_BYTES, AHEAD = G::AHEAD;
+  constexpr int ROWS_LOADED_PER_WAVE = G::ROWS_LOADED_PER_WAVE, LOADS_PER_STAGE = G::LOADS_PER_STAGE;
+  auto k_slot_off = [](int t) { return G::k_slot_off(t); };
+  auto v_slot_off = [](int t) { return G::v_slot_off(t); };
+  extern __shared__ __attribute__((aligned(1024))) char lds[];  // G::LDS_BYTES: rings of K and V blocks
 
   if constexpr (std::is_same<Extra, LinkNext>::value) {
     if (static_cast<int>(blockIdx.x) >= a.n_tiles) {
@@ -220,8 +256,10 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
   const int flat = tile.row0 + (valid ? local : 0);
   const int64_t fresh_row = a.q_off[b] + flat / group;
   const int head = g * group + flat % group;
-  // padding columns see every key; a row below key0 (negative here) sees none of this piece
-  const int my_pos = valid ? a.q_pos[fresh_row] - key0 : 0x7fffffff;
+  // Last key of this tile (or piece) the row may see.  Padding columns see every key; a row
+  // below key0 (negative here) sees none of this piece; a row beyond the end of a piece sees the
+  // piece up to its last key (blocks need not end where pieces do).
+  const int my_pos = min(valid ? a.q_pos[fresh_row] - key0 : 0x7fffffff, n_keys - 1);
   const __bf16* qp = static_cast<const __bf16*>(a.q) + (fresh_row * a.n_q_heads + head) * D;
   bf16x8 qf[8];
 #pragma unroll
@@ -276,32 +314,54 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
   // each; lane i of load p owns LDS column i&15 of row 8w + 4p + (i>>4) ----
   const int ld_sub = lane >> 4;
   const uint32_t ld_col = lane & 15;
-  const uint32_t ld_k16 = ld_col ^ ld_sub ^ ((wave & 1) << 3);  // ^ (4p): K swizzle = row & 15
   const uint32_t ld_v16 = ld_col ^ (ld_sub << 2);               //          V swizzle = (row & 3) << 2
   const uint32_t sel0 = ld_sub == 0 ? ~0u : 0u, sel1 = ld_sub == 1 ? ~0u : 0u;
   const uint32_t sel2 = ld_sub == 2 ? ~0u : 0u, sel3 = ld_sub == 3 ? ~0u : 0u;
-  // row offsets of this wave's eight rows of a block: one scalar load, issued one block
-  // ahead of its use so that its latency is never waited for
   const int n_iter = (n_keys + BN - 1) / BN;
+  // BN / 8 rows per wave and block: kLoadPairs loads of four rows for K and as many for V
+  constexpr int kLoadPairs = ROWS_LOADED_PER_WAVE / 4;
+  struct RowOffs {
+    u32x4_a4 q[kLoadPairs];
+  };
   auto fetch_rows = [&](int blk) {
     blk = blk < n_iter ? blk : n_iter - 1;
-    return *reinterpret_cast<const __attribute__((address_space(4))) u32x8_a4*>(off_of + blk * BN + wave * 8);
+    const __attribute__((address_space(4))) u32x4_a4* src =
+        reinterpret_cast<const __attribute__((address_space(4))) u32x4_a4*>(off_of + blk * BN + wave * ROWS_LOADED_PER_WAVE);
+    RowOffs r;
+#pragma unroll
+    for (int p = 0; p < kLoadPairs; ++p) r.q[p] = src[p];
+    return r;
   };
   // `ro` holds the offsets of the block whose loads go out next.  It is refilled at the start
   // of the wave's softmax phase, which touches neither LDS nor scalar memory: the scalar load
   // shares its counter with the LDS reads and returns out of order, so whatever waits on
   // that counter next (the first fragment reads of a matrix part, a barrier) waits for it.
-  u32x8_a4 ro = fetch_rows(0);
+  RowOffs ro = fetch_rows(0);
   auto issue_loads = [&](int blk) {
-    const u32x8_a4 cur = ro;
-    const uint32_t dst = lds_base + (blk % STAGES) * STAGE_BYTES + wave * 8 * ROW_BYTES;
-    // the four loads go out back to back, each from its own address registers
-    // this lane's row of each group of four, picked with per-lane masks (branch-free)
-    const uint32_t ra = (cur[0] & sel0) | (cur[1] & sel1) | (cur[2] & sel2) | (cur[3] & sel3);
-    const uint32_t rb = (cur[4] & sel0) | (cur[5] & sel1) | (cur[6] & sel2) | (cur[7] & sel3);
-    load4_to_lds_16B(kbase + (static_cast<uint64_t>(ra + ld_k16) << 4), vbase + (static_cast<uint64_t>(ra + ld_v16) << 4),
-                     kbase + (static_cast<uint64_t>(rb + (ld_k16 ^ 4)) << 4), vbase + (static_cast<uint64_t>(rb + ld_v16) << 4),
-                     dst, dst + TILE_BYTES, dst + 4 * ROW_BYTES, dst + TILE_BYTES + 4 * ROW_BYTES);
+    const RowOffs cur = ro;
+    // the loads go out back to back, each from its own address registers; this lane's row of
+    // each group of four is picked with per-lane masks (branch-free)
+    const uint32_t row0 = wave * ROWS_LOADED_PER_WAVE;
+    const uint32_t dk = lds_base + k_slot_off(blk) + row0 * ROW_BYTES;
+    const uint32_t dv = lds_base + v_slot_off(blk) + row0 * ROW_BYTES;
+    const void* gk[kLoadPairs];
+    const void* gv[kLoadPairs];
+#pragma unroll
+    for (int p = 0; p < kLoadPairs; ++p) {
+      const uint32_t r = (cur.q[p][0] & sel0) | (cur.q[p][1] & sel1) | (cur.q[p][2] & sel2) | (cur.q[p][3] & sel3);
+      const uint32_t kx = ld_col ^ ((row0 + 4 * p + ld_sub) & 15);  // K swizzle = row & 15
+      gk[p] = kbase + (static_cast<uint64_t>(r + kx) << 4);
+      gv[p] = vbase + (static_cast<uint64_t>(r + ld_v16) << 4);
+    }
+    if constexpr (kLoadPairs == 3) {
+      load6_to_lds_16B(gk[0], gv[0], gk[1], gv[1], gk[2], gv[2], dk, dv, dk + 4 * ROW_BYTES, dv + 4 * ROW_BYTES,
+                       dk + 8 * ROW_BYTES, dv + 8 * ROW_BYTES);
+    } else {
+#pragma unroll
+      for (int p = 0; p < kLoadPairs; p += 2)
+        load4_to_lds_16B(gk[p], gv[p], gk[p + 1], gv[p + 1], dk + 4 * p * ROW_BYTES, dv + 4 * p * ROW_BYTES,
+                         dk + 4 * (p + 1) * ROW_BYTES, dv + 4 * (p + 1) * ROW_BYTES);
+    }
   };
 
   // ---- LDS byte offsets of this lane's operand fragments ----
@@ -314,17 +374,18 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
   const int i16 = lane & 15;
   const int v_row = hi * 4 + (i16 >> 2);                                                   // + kh*16 (+8)
   const int v_col_x = ((((lane >> 4) & 1) << 1) | ((i16 & 3) >> 1)) ^ ((v_row & 3) << 2);  // ^ (db << 2)
-  const int v_off = TILE_BYTES + v_row * ROW_BYTES + (i16 & 1) * 8;
+  const int v_off = v_row * ROW_BYTES + (i16 & 1) * 8;
 
   PHASE_DECL
   // every ordinary load (query fragments, positions) is complete before the first direct
   // load is issued: from here on the outstanding-load counter only counts ring traffic
   WAIT_VMCNT(0);
   __builtin_amdgcn_sched_barrier(0);
-  issue_loads(0);
-  ro = fetch_rows(1);
-  if (n_iter > 1) issue_loads(1);
-  ro = fetch_rows(2);
+#pragma unroll
+  for (int i = 0; i < AHEAD; ++i) {
+    if (i < n_iter) issue_loads(i);
+    ro = fetch_rows(i + 1);
+  }
 
   // Ping-pong schedule.  The two wavefronts that share a SIMD (w and w+4) belong to
   // different groups and run half a block apart: while one group keeps the matrix
@@ -336,8 +397,10 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
   //   so its ring slot is refilled with block t+4... the loads of block t+2 are issued
   //   at half step 2t, into the slot block t-2 left free after half step 2t - 1.
   const int gp = wave >> 2;
-  f32x16 acc_s[2] = {f32x16{0}, f32x16{0}};
-  bf16x8 pf[4] = {};
+  f32x16 acc_s[KB];
+#pragma unroll
+  for (int i = 0; i < KB; ++i) acc_s[i] = f32x16{0};
+  bf16x8 pf[2 * KB] = {};
 
   auto k_frag = [&](const char* stage, int kb, int ks) {
     return *reinterpret_cast<const bf16x8*>(stage + k_row_off + kb * 32 * ROW_BYTES + ((k_col_x ^ (ks << 1)) << 4));
@@ -352,17 +415,17 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
   // O^T += V^T . P^T of block t: 16 keys per step, each fragment register refilled for the
   // next step right behind the MFMA that read it; the scheduling barriers pin that order
   auto pv_block = [&](int t) {
-    const char* stage = lds + (t % STAGES) * STAGE_BYTES;
+    const char* stage = lds + v_slot_off(t);
     bf16x8 vf[4];
 #pragma unroll
     for (int db = 0; db < 4; ++db) vf[db] = v_frag(stage, 0, db);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int kh = 0; kh < 4; ++kh) {  // kb = kh/2, half = kh%2
+    for (int kh = 0; kh < 2 * KB; ++kh) {  // kb = kh/2, half = kh%2
 #pragma unroll
       for (int db = 0; db < 4; ++db) {
         acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[db], pf[kh], acc_o[db], 0, 0, 0);
-        if (kh + 1 < 4) vf[db] = v_frag(stage, kh + 1, db);  // refill behind the MFMA that consumed it
+        if (kh + 1 < 2 * KB) vf[db] = v_frag(stage, kh + 1, db);  // refill behind the MFMA that consumed it
         __builtin_amdgcn_sched_barrier(0);
       }
     }
@@ -371,25 +434,25 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
   // S^T = K . Q^T of block t for 64 keys x 32 queries; LDS reads run kPre steps ahead of
   // the MFMAs and the two key sub-blocks alternate
   auto qk_block = [&](int t) {
-    const char* stage = lds + (t % STAGES) * STAGE_BYTES;
+    const char* stage = lds + k_slot_off(t);
     constexpr int kPre = 2;
-    acc_s[0] = f32x16{0};
-    acc_s[1] = f32x16{0};
-    bf16x8 kf[2][8];
+    bf16x8 kf[KB][8];
 #pragma unroll
-    for (int ks = 0; ks < kPre; ++ks) {
-      kf[0][ks] = k_frag(stage, 0, ks);
-      kf[1][ks] = k_frag(stage, 1, ks);
-    }
+    for (int kb = 0; kb < KB; ++kb) acc_s[kb] = f32x16{0};
+#pragma unroll
+    for (int ks = 0; ks < kPre; ++ks)
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb) kf[kb][ks] = k_frag(stage, kb, ks);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
       if (ks + kPre < 8) {
-        kf[0][ks + kPre] = k_frag(stage, 0, ks + kPre);
-        kf[1][ks + kPre] = k_frag(stage, 1, ks + kPre);
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) kf[kb][ks + kPre] = k_frag(stage, kb, ks + kPre);
       }
-      acc_s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0][ks], qf[ks], acc_s[0], 0, 0, 0);
-      acc_s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[1][ks], qf[ks], acc_s[1], 0, 0, 0);
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb)
+        acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb][ks], qf[ks], acc_s[kb], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
@@ -400,7 +463,7 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
     // causal mask by position, on the diagonal blocks only
     if (j0 + BN - 1 > wave_lo_pos) {
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+      for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int key = j0 + kb * 32 + (v >> 2) * 8 + hi * 4 + (v & 3);
@@ -409,7 +472,7 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
     }
     float m_blk = -INFINITY;
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
       for (int v = 0; v < 16; ++v) m_blk = fmaxf(m_blk, acc_s[kb][v]);
     m_blk = max_across_halves(m_blk);
@@ -429,7 +492,7 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
     const float m_scaled = m_run * scale_log2;
     float l_blk = 0.f;
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
       for (int half = 0; half < 2; ++half) {
         f32x8 p;
@@ -447,9 +510,9 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
   auto even_sync = [&](int t) {
     PHASE_MARK(0)
     if (t < n_iter) {
-      // this wave's share of block t has landed when at most the loads of block t+1 are
-      // still outstanding
-      if (t + 1 < n_iter) {
+      // this wave's share of block t has landed when at most the loads of the blocks issued
+      // after it are still outstanding
+      if (AHEAD == 2 && t + 1 < n_iter) {
         WAIT_VMCNT(LOADS_PER_STAGE);
       } else {
         WAIT_VMCNT(0);
@@ -458,7 +521,7 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
     PHASE_MARK(1)
     __syncthreads();
     PHASE_MARK(2)
-    if (t + 2 < n_iter) issue_loads(t + 2);
+    if (t + AHEAD < n_iter) issue_loads(t + AHEAD);
     PHASE_MARK(3)
   };
   // matrix half step of block t: finish block t-1, start block t (blocks past the last key
@@ -481,14 +544,14 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
       even_sync(t);
       matrix_part(t);
       __syncthreads();  // odd half step 2t+1
-      ro = fetch_rows(t + 3);
+      ro = fetch_rows(t + AHEAD + 1);
       if (t < n_iter && t * BN <= wave_hi_pos) softmax_block(t);
       PHASE_MARK(6)
     }
   } else {
     for (int t = 0; t <= n_iter; ++t) {
       even_sync(t);
-      ro = fetch_rows(t + 3);
+      ro = fetch_rows(t + AHEAD + 1);
       if (t >= 1 && (t - 1) * BN <= wave_hi_pos) softmax_block(t - 1);
       PHASE_MARK(6)
       __syncthreads();  // odd half step 2t+1
@@ -589,20 +652,20 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
 
 }  // namespace
 
-hipError_t launch_attn_bf16(const AttnArgs& a, const AssembleArgs* next, const AssembleSrcTable* next_tab,
-                            hipStream_t stream) {
-  if (a.n_tiles <= 0) return hipSuccess;
-  // 128 KB of dynamic LDS needs an explicit opt-in, once per device
+namespace {
+
+template <int kBlockKeys>
+hipError_t launch_shape(const AttnArgs& a, const AssembleArgs* next, const AssembleSrcTable* next_tab, int dev,
+                        hipStream_t stream) {
+  using G = Geo<kBlockKeys>;
+  // more than 64 KB of dynamic LDS needs an explicit opt-in, once per device
   static bool opted_in[64] = {};
-  int dev = 0;
-  hipError_t e = hipGetDevice(&dev);
-  if (e != hipSuccess) return e;
   if (dev >= 0 && dev < 64 && !opted_in[dev]) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bf16_kernel<NoLink>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bf16_kernel<kBlockKeys, NoLink>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES);
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bf16_kernel<LinkNext>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bf16_kernel<kBlockKeys, LinkNext>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES);
     if (e != hipSuccess) return e;
     opted_in[dev] = true;
   }
@@ -616,10 +679,25 @@ hipError_t launch_attn_bf16(const AttnArgs& a, const AssembleArgs* next, const A
     const int64_t rows_per_pass = THREADS / (next->n_kv_heads * (next->head_dim / 2 / 8));
     const int64_t rows_per_wg = kLinkRounds * kLinkDepth * rows_per_pass;
     ln.n_wgs = static_cast<int32_t>(std::max<int64_t>(1, (n_pos + rows_per_wg - 1) / rows_per_wg));
-    hipLaunchKernelGGL(attn_bf16_kernel<LinkNext>, dim3(a.n_tiles + ln.n_wgs), dim3(THREADS), LDS_BYTES, stream, a, ln);
+    hipLaunchKernelGGL((attn_bf16_kernel<kBlockKeys, LinkNext>), dim3(a.n_tiles + ln.n_wgs), dim3(THREADS), G::LDS_BYTES,
+                       stream, a, ln);
   } else {
-    hipLaunchKernelGGL(attn_bf16_kernel<NoLink>, dim3(a.n_tiles), dim3(THREADS), LDS_BYTES, stream, a, NoLink{});
+    hipLaunchKernelGGL((attn_bf16_kernel<kBlockKeys, NoLink>), dim3(a.n_tiles), dim3(THREADS), G::LDS_BYTES, stream, a,
+                       NoLink{});
   }
+  return hipSuccess;
+}
+
+}  // namespace
+
+hipError_t launch_attn_bf16(const AttnArgs& a, const AssembleArgs* next, const AssembleSrcTable* next_tab,
+                            hipStream_t stream) {
+  if (a.n_tiles <= 0) return hipSuccess;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  e = a.block_keys == 96 ? launch_shape<96>(a, next, next_tab, dev, stream) : launch_shape<64>(a, next, next_tab, dev, stream);
+  if (e != hipSuccess) return e;
   if (a.n_merges > 0)
     hipLaunchKernelGGL(attn_merge_kernel, dim3(a.n_merges, kAttnTileRows / 8), dim3(256), 0, stream, a);
   return hipGetLastError();

@@ -75,6 +75,11 @@ struct mpic_ctx {
   // events that order it against the caller's stream (two per layer in flight)
   hipStream_t link_stream = nullptr;
   std::vector<hipEvent_t> ev_layer;
+  // shape of the bf16 attention kernel: 0 = the library chooses (96 keys per block, 64 once the
+  // context has linked in the background: only that shape leaves registers for a wave of the
+  // linking kernel beside it); 64 / 96 = fixed by mpic_set_option
+  int32_t attn_block_keys = 0;
+  bool background_seen = false;
   // partial results of the decode step (one per key split), grown on demand
   void* decode_ws = nullptr;
   size_t decode_ws_bytes = 0;
@@ -134,7 +139,7 @@ struct NextLink {
 };
 int attend(mpic_ctx* ctx, mpic_plan* plan, const void* fresh_q, int64_t n_fresh_rows,
            const void* k_ctx, const void* v_ctx, int64_t n_ctx_slots, double softmax_scale, void* out,
-           float* lse, void* stream, const NextLink* next);
+           float* lse, void* stream, const NextLink* next, int32_t block_keys = 0);
 
 // Rows of the attention tile handled by one workgroup of the bf16 kernel.
 constexpr int kAttnTileRows = 256;
@@ -190,6 +195,7 @@ struct AttnArgs {
   float* ws_lse;  // [n_parts][kAttnTileRows] their log-sum-exp (-inf: the row saw no key of the piece)
   const AttnMerge* merges;
   int32_t n_merges;
+  int32_t block_keys;    // keys per LDS block of the bf16 kernel: 64 or 96
   const int32_t* q_rot;  // non-null: queries are rotated with row q_rot[r] of q_cos / q_sin on load
   const float* q_cos;
   const float* q_sin;

@@ -669,7 +669,7 @@ int prefill_layers(mpic_ctx* ctx, mpic_plan* plan, mpic_store* st, const uint64_
         next.v_ctx = v_ctx[l + 1];
       }
       rc = mpic::attend(ctx, plan, fresh_q[l], n_fresh_rows, k_ctx[l], v_ctx[l], n_ctx_slots, softmax_scale, out[l],
-                        lse ? lse[l] : nullptr, stream, linked ? &next : nullptr);
+                        lse ? lse[l] : nullptr, stream, linked ? &next : nullptr, ctx->attn_block_keys ? 0 : 96);
       if (rc != MPIC_OK) return rc;
     }
     return MPIC_OK;
@@ -718,7 +718,7 @@ int prefill_layers(mpic_ctx* ctx, mpic_plan* plan, mpic_store* st, const uint64_
     if (rc != MPIC_OK) return rc;
     MPIC_HIP(ctx, hipStreamWaitEvent(stream, ctx->ev_layer[2 * l], 0));
     rc = mpic::attend(ctx, plan, fresh_q[l], n_fresh_rows, k_ctx[l], v_ctx[l], n_ctx_slots, softmax_scale, out[l],
-                      lse ? lse[l] : nullptr, stream, nullptr);
+                      lse ? lse[l] : nullptr, stream, nullptr, ctx->attn_block_keys ? 0 : 64);
     if (rc != MPIC_OK) return rc;
     MPIC_HIP(ctx, hipEventRecord(ctx->ev_layer[2 * l + 1], stream));
     last_reader[k_ctx[l]] = l;

@@ -13,6 +13,7 @@ class Problem:
     """Inputs of one layer of one batch, as host tensors in the storage dtype."""
     interleaved = False
     pre_rope = False
+    block_keys = 0        # shape of the bf16 attention kernel: 0 = the library's choice, 64 or 96
 
     def __init__(self, cfg_id, *, k=None, layer=0, paged=None, interleaved=False, pre_rope=False, **layout_kw):
         self.sh = sh = workloads.shape(cfg_id)
@@ -60,6 +61,8 @@ class Problem:
         dt = mpic.MPIC_F32 if sh.dtype == "f32" else mpic.MPIC_BF16
         self.ctx = mpic.Context(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, dt, sh.rope_theta,
                                 int(self.interleaved), self.page_size, int(self.pre_rope))
+        if self.block_keys:
+            self.ctx.set_option(mpic.MPIC_OPT_ATTN_BLOCK_KEYS, self.block_keys)
         self.plan = mpic.Plan(self.ctx, self.requests, self.k, self.page_tables, self.n_pool_pages)
         host = sh.host_sourced if host_sourced is None else host_sourced
         self.srcs = []

@@ -91,6 +91,21 @@ def test_config5_reduced_paged():
     _run_full(Problem(5, n_chunks=5, chunk_len=203, text_len=21), host_sourced=True)
 
 
+@pytest.mark.parametrize("block_keys", [64, 96])
+def test_both_shapes_of_the_attention_kernel(block_keys):
+    """The bf16 kernel exists with 64 and with 96 keys per LDS block: full config 2 (tiles cut along
+    the keys, pieces that end inside a block), ragged GQA batch, paged layout with N % 16 != 0,
+    listed recompute sets."""
+    for p in (Problem(2), Problem(3, n_chunks=3, chunk_len=301, text_len=37, batch=2),
+              Problem(5, n_chunks=5, chunk_len=203, text_len=21), Problem(4, k=16, n_chunks=4, chunk_len=160, text_len=70, batch=3)):
+        p.block_keys = block_keys
+        _run_full(p, host_sourced=False)
+    with pytest.raises(mpic.MpicError):
+        p.ctx.set_option(mpic.MPIC_OPT_ATTN_BLOCK_KEYS, 80)
+    with pytest.raises(mpic.MpicError):
+        p.ctx.set_option(99, 1)
+
+
 def test_paged_and_contiguous_agree_bitwise():
     a = Problem(5, n_chunks=4, chunk_len=128, text_len=32, paged=16)
     b = Problem(5, n_chunks=4, chunk_len=128, text_len=32, paged=0)
@@ -557,6 +572,7 @@ def test_random_feature_combinations():
         p.sh = dataclasses.replace(p.sh, n_q_heads=hq, n_kv_heads=hkv)
         p.pre_rope, p.interleaved = bool(case % 2), bool((case // 2) % 2)
         p.host_mode = mpic.MPIC_SRC_HOST_MAPPED if case % 3 == 0 else mpic.MPIC_SRC_HOST_STAGED
+        p.block_keys = [0, 64, 96][(case // 2) % 3]
         p.chunks = {s_: workloads.gen_chunk(p.sh, 100 + case, s_, src_len[s_]) for s_ in p.chunks}
         q_off = p.oplan["q_off"]
         fresh = [workloads.gen_fresh(p.sh, 100 + case, b, int(q_off[b + 1] - q_off[b])) for b in range(len(reqs))]
