@@ -7,9 +7,10 @@
 // Work decomposition.  A workgroup (8 wavefronts) owns one tile of the plan: up to
 // 256 "flattened rows" (fresh row x query head of one kv group) of one request and
 // kv head, all of which read the same K/V.  Each wavefront owns 32 of those rows and
-// walks the keys 0..n_keys-1 in blocks of 64 that the workgroup stages through a
-// four-deep LDS ring with direct global->LDS loads (no register round trip): three
-// blocks are in flight while one is consumed, and one barrier per block suffices.
+// walks the keys 0..n_keys-1 in blocks of 96 (or 64, see Geo below) that the workgroup
+// stages through LDS rings with direct global->LDS loads (no register round trip): the
+// next blocks are in flight while one is consumed, and two barriers per block keep the
+// rings safe and the two wavefronts of a SIMD in anti-phase.
 // The kernel is bound by the L2->LDS stream of K/V blocks as much as by the matrix
 // cores, which is why a tile is as tall as the register file allows.
 //
@@ -51,7 +52,7 @@ constexpr int THREADS = WAVES * 64;
 constexpr int ROW_BYTES = D * 2;  // one staged key or value row
 
 // Keys per LDS block and what follows from it.  Two shapes are built:
-//   64 keys: K and V rings of four slots (128 KB), loads two blocks ahead, 204 registers -- leaves
+//   64 keys: K and V rings of four slots (128 KB), loads two blocks ahead, 202 registers -- leaves
 //            room on every SIMD for a wave of another kernel (linking on a second stream);
 //   96 keys: K ring of two slots, V ring of three (120 KB), loads one block ahead, 238 registers --
 //            a third fewer barriers and phase changes per key, 1 to 2.6 % faster alone, but nothing
@@ -104,8 +105,8 @@ static_assert(WAVES * ROWS_PER_WAVE == kAttnTileRows, "tile size and kernel shap
 // Direct global->LDS loads of 16 bytes per lane: LDS[m0 + 16*lane] = *gptr.  Written as
 // inline assembly so that the outstanding-load counter is managed by hand below: the
 // compiler would otherwise wait for *all* direct loads before any LDS read, which
-// defeats a ring that keeps three blocks in flight.  The four loads a wavefront issues per
-// block go out back to back, each from its own address registers.
+// defeats a ring that keeps blocks in flight.  The loads a wavefront issues per block go
+// out back to back, each from its own address registers.
 __device__ inline void load4_to_lds_16B(const void* g0, const void* g1, const void* g2, const void* g3,
                                         uint32_t l0, uint32_t l1, uint32_t l2, uint32_t l3) {
   asm volatile(
@@ -310,8 +311,8 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
 #pragma unroll
   for (int i = 0; i < 4; ++i) acc_o[i] = f32x16{0};
 
-  // ---- loader: wave w stages rows 8w..8w+7 of K and of V with two 1 KB direct loads
-  // each; lane i of load p owns LDS column i&15 of row 8w + 4p + (i>>4) ----
+  // ---- loader: wave w stages rows (BN/8)w .. (BN/8)(w+1)-1 of K and of V, four rows per 1 KB
+  // direct load; lane i of load p owns LDS column i&15 of row (BN/8)w + 4p + (i>>4) ----
   const int ld_sub = lane >> 4;
   const uint32_t ld_col = lane & 15;
   const uint32_t ld_v16 = ld_col ^ (ld_sub << 2);               //          V swizzle = (row & 3) << 2
@@ -393,9 +394,11 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
   // does the softmax of its block on the vector ALU; a workgroup barrier at every
   // half step keeps them in anti-phase.  Group gp runs its matrix part of block t in
   // half step 2t + gp and its softmax of block t in half step 2t + gp + 1.
-  //   stage t (K and V of block t) is first read in half step 2t and last in 2t + 3,
-  //   so its ring slot is refilled with block t+4... the loads of block t+2 are issued
-  //   at half step 2t, into the slot block t-2 left free after half step 2t - 1.
+  //   K of block t is read in half steps 2t and 2t + 1, V of block t in 2t + 2 and 2t + 3.
+  //   The loads of block t + AHEAD are issued at half step 2t (behind its barrier) into the
+  //   slots of the blocks whose last reads were in half step 2t - 1: with 64 keys per block K
+  //   and V of block t - 2 (rings of four, AHEAD = 2), with 96 keys K of block t - 1 (ring of
+  //   two) and V of block t - 2 (ring of three), AHEAD = 1.
   const int gp = wave >> 2;
   f32x16 acc_s[KB];
 #pragma unroll
