@@ -513,9 +513,13 @@ def test_calls_can_be_captured_in_a_graph():
     dq, dk, dv = (t.to(p.k_ctx.device) for t in p.decode_inputs())
     dec_out = torch.empty_like(dq)
 
+    nk, nv = torch.full_like(p.k_ctx, float("nan")), torch.full_like(p.v_ctx, float("nan"))   # the next layer's context
+
     def run():
         p.gpu_assemble()
-        p.gpu_attend()
+        # attention with the next layer's stored rows linked by the same launch
+        mpic.mpic_selective_attn_link_next(p.ctx.handle, p.plan.handle, p.d_q, p.k_ctx, p.v_ctx, p.sh.softmax_scale,
+                                           p.out, p.srcs, nk, nv, p.lse)
         mpic.mpic_decode_attn(p.ctx.handle, p.plan.handle, dq, dk, dv, p.k_ctx, p.v_ctx, p.sh.softmax_scale, dec_out)
 
     run()                                                       # eager warm-up: uploads, workspaces
@@ -529,12 +533,12 @@ def test_calls_can_be_captured_in_a_graph():
             t.copy_(torch.randn(t.shape, generator=gen).to(t.dtype))
         run()                                                   # eager reference on the new inputs
         torch.cuda.synchronize()
-        want = [x.clone() for x in (p.k_ctx, p.v_ctx, p.out, p.lse, dec_out)]
-        for x in (p.k_ctx, p.v_ctx, p.out, dec_out):
+        want = [x.clone() for x in (p.k_ctx, p.v_ctx, p.out, p.lse, dec_out, nk, nv)]
+        for x in (p.k_ctx, p.v_ctx, p.out, dec_out, nk, nv):
             x.fill_(float("nan"))
         graph.replay()
         torch.cuda.synchronize()
-        for got, ref in zip((p.k_ctx, p.v_ctx, p.out, p.lse, dec_out), want):
+        for got, ref in zip((p.k_ctx, p.v_ctx, p.out, p.lse, dec_out, nk, nv), want):
             assert torch.equal(got.view(torch.int16 if got.dtype == torch.bfloat16 else torch.int32),
                                ref.view(torch.int16 if ref.dtype == torch.bfloat16 else torch.int32))
 
