@@ -254,14 +254,22 @@ def main():
     attn_ms = timed(attend if fuse or L < 2 else (lambda s: attend(s, ctx_bg, plan_bg)), args.steps)
     asm_ms = timed(assemble, args.steps)
 
-    # ---- one layer (link + attention) captured in a HIP graph and replayed: what a
-    # launch-bound serving loop would do for small batches (extra figure) ----------
+    # ---- one step captured in a HIP graph and replayed: what a launch-bound serving loop would
+    # do for small batches (extra figure).  The step as above when it is the fused one: fresh rows,
+    # then the attention launch that also links the next layer's stored rows; else link + attention.
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
-        mpic.mpic_assemble_kv(ctx.handle, plan.handle, sets[0]["srcs"], sets[0]["fk"], sets[0]["fv"],
-                              sets[0]["k_ctx"], sets[0]["v_ctx"], None)
-        mpic.mpic_selective_attn(ctx.handle, plan.handle, sets[0]["q"], sets[0]["k_ctx"], sets[0]["v_ctx"],
-                                 sh.softmax_scale, sets[0]["out"], None, None)
+        s0, s1 = sets[0], sets[1 % L]
+        if fuse and L >= 2:
+            mpic.mpic_assemble_kv_parts(ctx.handle, plan.handle, None, s0["fk"], s0["fv"], s0["k_ctx"], s0["v_ctx"],
+                                        mpic.MPIC_PART_FRESH, None)
+            mpic.mpic_selective_attn_link_next(ctx.handle, plan.handle, s0["q"], s0["k_ctx"], s0["v_ctx"],
+                                               sh.softmax_scale, s0["out"], s1["srcs"], s1["k_ctx"], s1["v_ctx"],
+                                               None, None)
+        else:
+            mpic.mpic_assemble_kv(ctx.handle, plan.handle, s0["srcs"], s0["fk"], s0["fv"], s0["k_ctx"], s0["v_ctx"], None)
+            mpic.mpic_selective_attn(ctx.handle, plan.handle, s0["q"], s0["k_ctx"], s0["v_ctx"], sh.softmax_scale,
+                                     s0["out"], None, None)
     graph.replay()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
