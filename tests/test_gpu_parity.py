@@ -106,6 +106,28 @@ def test_both_shapes_of_the_attention_kernel(block_keys):
         p.ctx.set_option(99, 1)
 
 
+@pytest.mark.parametrize("block_keys", [64, 96])
+def test_logits_that_grow_fall_and_jump_along_the_keys(block_keys):
+    """The reference point of the lazily rescaled softmax: logits that rise by many powers of two
+    from block to block (a new reference point in every block), that fall (never a new one, late
+    keys underflow), and that jump at random; rows whose first keys are their largest."""
+    n = 1500
+    base = _custom([[("text", n)], [("text", 40)]], 0, [], 0)
+    hq, hkv, d = base.sh.n_q_heads, base.sh.n_kv_heads, base.sh.head_dim
+    u = torch.zeros(d)
+    u[:64] = 0.5                                             # |u|^2 = 16
+    j = torch.arange(n + 40, dtype=torch.float32)
+    rng = np.random.default_rng(77)
+    walk = torch.from_numpy(np.cumsum(rng.choice([-30.0, 0.0, 0.0, 25.0], size=n + 40)).astype(np.float32))
+    for name, level in (("rising", 0.106 * j), ("falling", 0.106 * (n + 40 - j)), ("jumping", 0.05 * walk)):
+        p = _custom([[("text", n)], [("text", 40)]], 0, [], 0)
+        p.block_keys = block_keys
+        p.q = u.expand(n + 40, hq, d).clone().to(torch.bfloat16)
+        p.fresh_k = (level[:, None, None] * u[None, None, :]).expand(n + 40, hkv, d).clone().to(torch.bfloat16)
+        print(name, "logit range", float((level * 16 / np.sqrt(128)).min()), float((level * 16 / np.sqrt(128)).max()), flush=True)
+        _run_full(p, host_sourced=False)
+
+
 def test_paged_and_contiguous_agree_bitwise():
     a = Problem(5, n_chunks=4, chunk_len=128, text_len=32, paged=16)
     b = Problem(5, n_chunks=4, chunk_len=128, text_len=32, paged=0)
