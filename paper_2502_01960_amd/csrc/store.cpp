@@ -637,10 +637,11 @@ int prefill_layers(mpic_ctx* ctx, mpic_plan* plan, mpic_store* st, const uint64_
   // Every cache the plan reads is in GPU memory: nothing to fetch ahead.  When the planner's
   // simulation of the attention launch leaves enough idle time at its end, the stored rows of
   // layer l+1 are linked by the attention launch of layer l itself, in workgroups that run as
-  // that attention drains: one stream, no events.  (A batch whose tiles fill the chip evenly
-  // has no such room; there the two-stream schedule below is faster: 2.17 ms against 2.22 ms per
-  // layer for 8 requests x 16 chunks, where a 75K-token request gains 3.56 ms against 3.60 ms.)  (A context buffer shared by consecutive
-  // layers cannot be written while it is read: those layers are linked by a launch of their own.)
+  // that attention drains: one stream, no events.  A batch whose tiles fill the chip evenly has
+  // no such room, and the two-stream schedule below is the faster one there: 2.17 ms against
+  // 2.22 ms per layer for 8 requests x 16 chunks, while a 75K-token request gains from the fused
+  // launch, 3.56 ms against 3.60 ms.  A context buffer shared by consecutive layers cannot be
+  // written while it is read: those layers are linked by a launch of their own.
   if (rows_stored == 0 && mpic::can_link_in_attention(ctx, plan) && mpic::link_fits_attention_tail(ctx, plan)) {
     std::vector<mpic_chunk_src> next_srcs(std::max(n_srcs, 0));
     const size_t ctx_bytes = static_cast<size_t>(n_ctx_slots) * st->row_bytes;
