@@ -15,6 +15,7 @@ work of a step divided by the time of the whole step.
 import argparse
 import json
 import os
+import subprocess
 import sys
 import time
 
@@ -42,6 +43,7 @@ def parse():
                          "over many layer sets, where only the timing matters")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-host-sourced", action="store_true")
+    ap.add_argument("--no-device-state", action="store_true", help="skip the clock sample under load (3 s)")
     ap.add_argument("--attn-block-keys", type=int, default=0,
                     help="keys per LDS block of the attention kernel in the main context: 64, 96 or 0 = the library's choice")
     ap.add_argument("--pipeline-layers", type=int, default=8,
@@ -54,6 +56,43 @@ def parse():
                     help="also launch a plain elementwise copy of 512 MiB (reads and writes 512 MiB per "
                          "launch): the reference dispatch for scaling hardware traffic counters")
     return ap.parse_args()
+
+
+def sample_clocks_under_load(run, seconds=3.0):
+    """Run `run()` in a loop for about `seconds`; meanwhile ask rocm-smi (a child process) for
+    the clocks and the power cap.  Returns None when the tool is missing or prints nothing usable."""
+    import re
+    import shutil
+    import threading
+    tool = shutil.which("rocm-smi") or "/opt/rocm/bin/rocm-smi"
+    if not os.path.exists(tool):
+        return None
+    out = {}
+
+    def ask():
+        time.sleep(seconds / 3)
+        try:
+            r = subprocess.run([tool, "--showclocks", "--showmaxpower"], capture_output=True, text=True, timeout=30)
+            out["text"] = r.stdout
+        except Exception:
+            pass
+    th = threading.Thread(target=ask)
+    th.start()
+    t0 = time.time()
+    while time.time() - t0 < seconds or th.is_alive():
+        run()
+        if time.time() - t0 > 40:
+            break
+    th.join()
+    text = out.get("text", "")
+    sclk = re.search(r"sclk clock level: *\d+: *\((\d+)Mhz\)", text)
+    mclk = re.search(r"mclk clock level: *\d+: *\((\d+)Mhz\)", text)
+    cap = re.search(r"Max Graphics Package Power \(W\): *([0-9.]+)", text)
+    if not sclk:
+        return None
+    return {"sclk_mhz_under_attention": int(sclk.group(1)), "mclk_mhz": int(mclk.group(1)) if mclk else None,
+            "power_cap_w": float(cap.group(1)) if cap else None, "sclk_mhz_of_the_peak_figure": 2400,
+            "source": "rocm-smi --showclocks --showmaxpower, sampled while the attention kernel ran back to back"}
 
 
 def main():
@@ -253,6 +292,12 @@ def main():
     # the attention launch of the schedule that is the step (its kernel shape included)
     attn_ms = timed(attend if fuse or L < 2 else (lambda s: attend(s, ctx_bg, plan_bg)), args.steps)
     asm_ms = timed(assemble, args.steps)
+
+    # ---- clocks while the attention kernel runs back to back (the 2.5 PFLOP/s peak is a 2.4 GHz
+    # figure; what the part holds under this load says how much of the gap is clock) ----
+    device_state = None
+    if not args.no_device_state:
+        device_state = sample_clocks_under_load(lambda: timed(attend, 50))
 
     # ---- one step captured in a HIP graph and replayed: what a launch-bound serving loop would
     # do for small batches (extra figure).  The step as above when it is the fused one: fresh rows,
@@ -500,6 +545,7 @@ def main():
         "first_layer_ms_warm_process": round(warm_first_layer_ms, 4),
         "host_sourced": host,
         "layer_pipeline": pipe,
+        "device_state": device_state,
     }
     print(json.dumps(rec))
     return 0

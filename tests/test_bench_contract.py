@@ -42,3 +42,6 @@ def test_bench_prints_one_json_line_with_the_contract_keys():
     assert abs(rec["value"] - rec["attention"]["flops"] / (rec["ms_per_step"] * 1e-3) / 1e12) < 0.5
     for tier in ("disk", "host", "hbm"):
         assert rec["layer_pipeline"][tier]["ms_per_layer"] > 0
+    # the clock sample is there when the box has the tool, and then below the peak's 2.4 GHz
+    state = rec["device_state"]
+    assert state is None or 100 < state["sclk_mhz_under_attention"] <= 2400
