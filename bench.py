@@ -290,7 +290,20 @@ def main():
         return e0.elapsed_time(e1) / n
 
     # the attention launch of the schedule that is the step (its kernel shape included)
-    attn_ms = timed(attend if fuse or L < 2 else (lambda s: attend(s, ctx_bg, plan_bg)), args.steps)
+    attend_of_step = attend if fuse or L < 2 else (lambda s: attend(s, ctx_bg, plan_bg))
+    attn_ms = timed(attend_of_step, args.steps)
+
+    def each(fn, n):
+        """Durations of n back-to-back launches one by one (an event between neighbours)."""
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+        torch.cuda.synchronize()
+        evs[0].record(stream)
+        for i in range(n):
+            fn(sets[i % L])
+            evs[i + 1].record(stream)
+        evs[-1].synchronize()
+        return np.array([evs[i].elapsed_time(evs[i + 1]) for i in range(n)])
+    attn_each = each(attend_of_step, max(args.steps, 20))
     asm_ms = timed(assemble, args.steps)
 
     # ---- clocks while the attention kernel runs back to back (the 2.5 PFLOP/s peak is a 2.4 GHz
@@ -531,7 +544,8 @@ def main():
                      "kernel": "attn_bf16_kernel<%d keys per block>" % (64 if not (fuse or L < 2) else args.attn_block_keys or 96),
                      "avg_launch_ms": round(attn_ms, 5)},
         "cpu_baseline": cpu,
-        "attention": {"ms": round(attn_ms, 5), "TFLOPs": round(attn_tflops, 3),
+        "attention": {"ms": round(attn_ms, 5), "ms_median": round(float(np.median(attn_each)), 5),
+                      "ms_min": round(float(attn_each.min()), 5), "TFLOPs": round(attn_tflops, 3),
                       "pct_mfma_peak": round(100 * attn_tflops / PEAK_BF16_TFLOPS, 3), "flops": attn_flops},
         "assembly": {"ms": round(asm_ms, 5), "GBps": round(asm_gbs, 2), "pct_hbm_peak": round(100 * asm_gbs / PEAK_HBM_GBS, 3),
                      "bytes": asm_bytes},
