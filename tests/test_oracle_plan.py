@@ -176,6 +176,8 @@ def test_missing_chunk_equals_text():
     assert pa["runs"].tolist() == pb["runs"].tolist()
     big = build_plan([[("text", 5), ("chunk", 0, 7, 100), ("text", 2), ("chunk", 1, 6, None)]], 2)
     assert big["q_pos"].tolist() == pa["q_pos"].tolist()
+    # the effective k of a chunk is clipped to its length: min(k, L) tokens are recomputed
+    assert pa["inst_k"].tolist() == [7, 2] and big["inst_k"].tolist() == [7, 2]
 
 
 def test_k_zero_and_no_text_gives_empty_set():
