@@ -73,6 +73,20 @@ def _chosen(seg, default_k):
 
 def _check_invariants(reqs, default_k, p, page_size=0, tables=None):
     B = len(reqs)
+    # chunk instances are numbered in prompt order over the batch; their shift is the offset of
+    # their first token and their effective k the length of the leading run 0, 1, 2, ... of their set
+    inst = 0
+    for b in range(B):
+        off = 0
+        for s in reqs[b]:
+            if s[0] == "chunk":
+                pick = _chosen(s, default_k)
+                lead = next(t for t in range(s[2] + 1) if t not in pick)
+                assert (p["inst_src"][inst], p["inst_delta"][inst], p["inst_len"][inst], p["inst_k"][inst],
+                        p["inst_req"][inst]) == (s[1], off, s[2], lead, b)
+                inst += 1
+            off += s[1] if s[0] == "text" else s[2]
+    assert inst == len(p["inst_src"])
     for b in range(B):
         segs = reqs[b]
         # independent construction: label every position, then filter

@@ -166,7 +166,14 @@ PLAN_MISTAKES = [
     ("stored row by position, not by chunk-local index", "owner[off + t] = (inst, t)", "owner[off + t] = (inst, off + t)"),
     ("runs never merged", "if i > 0 and order[i - 1] == p - 1:", "if False:"),
     ("fresh rows numbered per request", "row_of = {p: q_off[-1] + i for i, p in enumerate(order)}", "row_of = {p: i for i, p in enumerate(order)}"),
+    ("page offset dropped", "* page_size + p % page_size", "* page_size"),
+    ("page table of the first request for all", "int(page_tables[b][p // page_size])", "int(page_tables[0][p // page_size])"),
+    ("effective k counts the set, not its leading run", "k_eff = 0\n                while k_eff in chosen:\n                    k_eff += 1",
+     "k_eff = len(chosen)"),
+    ("slot of a fresh row taken from the first request", "slot_map.append(dst_slot[ctx_off[-1] + p])", "slot_map.append(dst_slot[p])"),
 ]
+BATCH_OR_PAGED = {"fresh rows numbered per request", "page offset dropped", "page table of the first request for all",
+                  "effective k counts the set, not its leading run", "slot of a fresh row taken from the first request"}
 
 
 @pytest.mark.parametrize("what,old,new", PLAN_MISTAKES, ids=[m[0] for m in PLAN_MISTAKES])
@@ -174,8 +181,8 @@ def test_plan_pins(monkeypatch, what, old, new):
     bad = _mutant(oracle.plan, old, new)
     monkeypatch.setattr(P, "build_plan", bad.build_plan)
     pins = list(PLAN_PINS)
-    if what == "fresh rows numbered per request":   # needs a batch: the brute-force construction on random batches
-        pins.append(P.test_random_layouts)
+    if what in BATCH_OR_PAGED:   # needs a batch, pages or an explicit token set: the brute-force construction on random layouts
+        pins += [P.test_random_layouts, P.test_random_layouts_paged]
     assert _bites(pins) >= 1, what
 
 
