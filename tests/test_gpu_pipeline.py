@@ -262,6 +262,46 @@ def test_degenerate_batches(tmp_path):
     p.close()
 
 
+def test_more_chunk_instances_than_one_linking_launch_carries(tmp_path):
+    """A linking launch takes the source pointers of at most 128 chunk instances as arguments; a
+    batch with more is linked by several launches over consecutive position ranges (and its next
+    layer never rides in the attention launch).  180 short chunks drawn from 40 sources."""
+    print("pipeline: 180 chunk instances (more than one linking launch carries), HBM and mixed tiers", flush=True)
+    rng = np.random.default_rng(180)
+    n_src = 40
+    src_len = {s: int(rng.integers(5, 13)) for s in range(n_src)}
+    reqs = []
+    for b in range(2):
+        segs = []
+        for i in range(90):
+            s = int(rng.integers(0, n_src))
+            segs.append(("text", int(rng.integers(0, 4))))
+            segs.append(("chunk", s, src_len[s], None if i % 3 else int(rng.integers(0, 4))))
+        segs.append(("text", 7))
+        reqs.append(segs)
+    for tiers, d in (((HBM,), None), ((HBM, HOST, DISK), tmp_path)):
+        p = LayeredProblem(3, 2, tiers, d, k=2, custom=(reqs, n_src, src_len))
+        p.plan_for()
+        assert len(p.oplan["inst_src"]) == 180
+        assert p.gpu_run() is None
+        ref = p.oracle_run()
+        p.check(ref)
+        # the single-layer entry points on the same plan: linking in one call, attention with the next layer's rows
+        srcs = [p.store.layer(p.ids[s], 1) if tiers == (HBM,) else None for s in range(n_src)]
+        if tiers == (HBM,):
+            k2 = torch.full_like(p.k_ctx[1], float("nan")); v2 = torch.full_like(p.v_ctx[1], float("nan"))
+            out = torch.full_like(p.out[0], float("nan"))
+            mpic.mpic_selective_attn_link_next(p.ctx.handle, p.plan.handle, p.d_fresh[0][0], p.k_ctx[0], p.v_ctx[0],
+                                               p.sh.softmax_scale, out, srcs, k2, v2)
+            mpic.mpic_assemble_kv_parts(p.ctx.handle, p.plan.handle, None, p.d_fresh[1][1], p.d_fresh[1][2], k2, v2,
+                                        mpic.MPIC_PART_FRESH)
+            torch.cuda.synchronize()
+            assert torch.equal(out.view(torch.int16), p.out[0].view(torch.int16))
+            assert torch.equal(k2.view(torch.int16), p.k_ctx[1].view(torch.int16))
+            assert torch.equal(v2.view(torch.int16), p.v_ctx[1].view(torch.int16))
+        p.close()
+
+
 def test_rejected_calls_enqueue_nothing(tmp_path):
     print("pipeline: argument checks", flush=True)
     p = LayeredProblem(3, 2, (HBM,), tmp_path, **SMALL3)
