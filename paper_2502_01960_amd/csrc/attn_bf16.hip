@@ -69,8 +69,10 @@ struct Geo {
   static constexpr int LDS_BYTES = (K_SLOTS + V_SLOTS) * TILE_BYTES;
   static constexpr int ROWS_LOADED_PER_WAVE = BN / WAVES;               // rows of K (and of V) a wave stages per block
   static constexpr int LOADS_PER_STAGE = 2 * ROWS_LOADED_PER_WAVE / 4;  // direct loads each wave issues per block
-  __device__ static int k_slot_off(int t) { return (t % K_SLOTS) * TILE_BYTES; }
-  __device__ static int v_slot_off(int t) { return K_SLOTS * TILE_BYTES + (t % V_SLOTS) * TILE_BYTES; }
+  // the V ring comes first: its fragment reads step through a block with immediate offsets (16 keys =
+  // 4 KB apart) that must stay below 64 KB, which a ring base of its own would use up
+  __device__ static int v_slot_off(int t) { return (t % V_SLOTS) * TILE_BYTES; }
+  __device__ static int k_slot_off(int t) { return V_SLOTS * TILE_BYTES + (t % K_SLOTS) * TILE_BYTES; }
 };
 #ifndef MPIC_LINK_ROUNDS
 #define MPIC_LINK_ROUNDS 2
