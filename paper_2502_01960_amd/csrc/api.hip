@@ -545,10 +545,7 @@ static int decode_attn_impl(mpic_ctx* ctx, mpic_plan* plan, const void* q, const
   // is a multiple of 128 keys.
   int32_t n_splits = 1, keys_per_split = std::max(max_ctx, 1);
   if (c.dtype == MPIC_BF16 && max_ctx > 0) {
-#ifndef MPIC_DECODE_TARGET
-#define MPIC_DECODE_TARGET 256
-#endif
-    constexpr int64_t kTargetWorkgroups = MPIC_DECODE_TARGET;
+    constexpr int64_t kTargetWorkgroups = 256;  // one round over the compute units
     const int64_t lanes = static_cast<int64_t>(plan->n_requests) * c.n_kv_heads * ((ctx->group + 31) / 32);
     const int64_t want = std::max<int64_t>(1, kTargetWorkgroups / lanes);
     int64_t kps = (max_ctx + want - 1) / want;

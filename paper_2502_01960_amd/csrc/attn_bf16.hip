@@ -30,20 +30,10 @@
 
 #include "common.h"
 #include "link_rows.h"
+#include "wave_ops.h"
 
 namespace mpic {
 namespace {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef short s16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x8_a4 __attribute__((ext_vector_type(8), aligned(4)));  // eight table entries, dword aligned
-typedef uint32_t u32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));
 
 constexpr int D = 128;   // head dim
 constexpr int WAVES = 8;
@@ -74,28 +64,10 @@ struct Geo {
   __device__ static int v_slot_off(int t) { return (t % V_SLOTS) * TILE_BYTES; }
   __device__ static int k_slot_off(int t) { return V_SLOTS * TILE_BYTES + (t % K_SLOTS) * TILE_BYTES; }
 };
-#ifndef MPIC_LINK_ROUNDS
-#define MPIC_LINK_ROUNDS 2
-#endif
-constexpr int kLinkRounds = MPIC_LINK_ROUNDS;
-#ifndef MPIC_LINK_DEPTH
-#define MPIC_LINK_DEPTH 2
-#endif
-constexpr int kLinkDepth = MPIC_LINK_DEPTH;  // items a thread of a trailing workgroup keeps in flight
+constexpr int kLinkRounds = 2;  // trips of the linking loop per trailing workgroup
+constexpr int kLinkDepth = 2;   // items a thread of a trailing workgroup keeps in flight
 constexpr float kSumLimit = 4096.0f;  // lazy rescale: a lane's share of a block's row sum may reach this
 static_assert(WAVES * ROWS_PER_WAVE == kAttnTileRows, "tile size and kernel shape must agree");
-
-// Phase timing (development builds only, -DMPIC_PHASE_TIMING): per-wave sums of shader
-// clock ticks between marks, written to the lse buffer as [tile][wave][8] floats.
-#ifdef MPIC_PHASE_TIMING
-#define PHASE_DECL unsigned long long ph_t = __builtin_amdgcn_s_memtime(); float ph_sum[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-#define PHASE_MARK(i) { const unsigned long long n_ = __builtin_amdgcn_s_memtime(); ph_sum[i] += static_cast<float>(n_ - ph_t); ph_t = n_; }
-#else
-#define PHASE_DECL
-#define PHASE_MARK(i)
-#endif
-
-#define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
 
 // Staged rows are 256 bytes = 16 columns of 16 bytes, unpadded (a direct global->LDS
 // load writes 64 lanes x 16 bytes contiguously).  Bank conflicts are avoided by
@@ -103,74 +75,6 @@ static_assert(WAVES * ROWS_PER_WAVE == kAttnTileRows, "tile size and kernel shap
 // *global* addresses accordingly.
 //   K, read 16 bytes per lane by 16+ consecutive rows:      swizzle = row & 15
 //   V, transpose-read as 4 rows x 64 bytes per 32 lanes:    swizzle = (row & 3) << 2
-
-// Direct global->LDS loads of 16 bytes per lane: LDS[m0 + 16*lane] = *gptr.  Written as
-// inline assembly so that the outstanding-load counter is managed by hand below: the
-// compiler would otherwise wait for *all* direct loads before any LDS read, which
-// defeats a ring that keeps blocks in flight.  The loads a wavefront issues per block go
-// out back to back, each from its own address registers.
-__device__ inline void load4_to_lds_16B(const void* g0, const void* g1, const void* g2, const void* g3,
-                                        uint32_t l0, uint32_t l1, uint32_t l2, uint32_t l3) {
-  asm volatile(
-      "s_mov_b32 m0, %4\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off\n\t"
-      "s_mov_b32 m0, %5\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\t"
-      "s_mov_b32 m0, %6\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\t"
-      "s_mov_b32 m0, %7\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %3, off"
-      :
-      : "v"(g0), "v"(g1), "v"(g2), "v"(g3), "s"(l0), "s"(l1), "s"(l2), "s"(l3)
-      : "memory", "m0");
-}
-__device__ inline void load6_to_lds_16B(const void* g0, const void* g1, const void* g2, const void* g3, const void* g4,
-                                        const void* g5, uint32_t l0, uint32_t l1, uint32_t l2, uint32_t l3, uint32_t l4,
-                                        uint32_t l5) {
-  asm volatile(
-      "s_mov_b32 m0, %6\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off\n\t"
-      "s_mov_b32 m0, %7\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\t"
-      "s_mov_b32 m0, %8\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\t"
-      "s_mov_b32 m0, %9\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %3, off\n\t"
-      "s_mov_b32 m0, %10\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %4, off\n\t"
-      "s_mov_b32 m0, %11\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %5, off"
-      :
-      : "v"(g0), "v"(g1), "v"(g2), "v"(g3), "v"(g4), "v"(g5), "s"(l0), "s"(l1), "s"(l2), "s"(l3), "s"(l4), "s"(l5)
-      : "memory", "m0");
-}
-// s_waitcnt vmcnt(n) only (expcnt / lgkmcnt fields left at "no wait")
-#define WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
-
-// Combine a value with the one held by lane ^ 32 (the other half of a query column) with
-// v_permlane32_swap (verified: swapping two copies of a register leaves the low half's values
-// in one result and the high half's in the other, in both halves).  A plain cross-lane shuffle
-// would go through the LDS pipeline, whose command queue the fragment reads keep full.
-// (The two results are copied into scalars before they are reinterpreted: a bit cast applied
-// directly to an element of the returned vector reads element 0 for both.)
-struct Halves {
-  float lo, hi;
-};
-__device__ inline Halves split_halves(float x) {
-  const unsigned a = __builtin_bit_cast(unsigned, x);
-  const auto r = __builtin_amdgcn_permlane32_swap(a, a, false, false);
-  const unsigned r0 = r[0], r1 = r[1];
-  return Halves{__builtin_bit_cast(float, r0), __builtin_bit_cast(float, r1)};
-}
-__device__ inline float max_across_halves(float x) {
-  const Halves h = split_halves(x);
-  return fmaxf(h.lo, h.hi);
-}
-__device__ inline float sum_across_halves(float x) {
-  const Halves h = split_halves(x);
-  return h.lo + h.hi;
-}
-
-__device__ inline float wave_min(float x) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) x = fminf(x, __shfl_xor(x, off));
-  return x;
-}
-__device__ inline float wave_max(float x) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) x = fmaxf(x, __shfl_xor(x, off));
-  return x;
-}
 
 // Second job a launch may carry: the stored rows of the *next* layer's context, linked by
 // workgroups that come after the attention tiles in the grid.  The dispatcher hands out
@@ -251,7 +155,7 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
       (const __attribute__((address_space(4))) uint32_t*)(a.kv_off16 + a.ctx_off[b] + key0);
   const char* kbase = static_cast<const char*>(a.k_ctx) + g * ROW_BYTES;
   const char* vbase = static_cast<const char*>(a.v_ctx) + g * ROW_BYTES;
-  const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(LDS_PTR(char, lds)));
+  const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(MPIC_LDS_PTR(char, lds)));
 
   // ---- this lane's query ----
   const int local = wave * ROWS_PER_WAVE + col;
@@ -302,9 +206,8 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
     }
   }
 
-  const float posf = static_cast<float>(valid ? my_pos : -1);
-  const int wave_hi_pos = static_cast<int>(wave_max(posf));  // negative: idle wave
-  const int wave_lo_pos = static_cast<int>(wave_min(valid ? posf : 3.0e9f));
+  const int wave_hi_pos = wave_max_i32(valid ? my_pos : -1);  // negative: idle wave
+  const int wave_lo_pos = wave_min_i32(valid ? my_pos : 0x7fffffff);
 
   const float scale_log2 = a.scale * 1.4426950408889634f;
   float m_run = -INFINITY;  // running reference maximum of the raw logits (scale > 0 keeps the order)
@@ -379,10 +282,9 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
   const int v_col_x = ((((lane >> 4) & 1) << 1) | ((i16 & 3) >> 1)) ^ ((v_row & 3) << 2);  // ^ (db << 2)
   const int v_off = v_row * ROW_BYTES + (i16 & 1) * 8;
 
-  PHASE_DECL
   // every ordinary load (query fragments, positions) is complete before the first direct
   // load is issued: from here on the outstanding-load counter only counts ring traffic
-  WAIT_VMCNT(0);
+  MPIC_WAIT_VMCNT(0);
   __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int i = 0; i < AHEAD; ++i) {
@@ -412,8 +314,8 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
   };
   auto v_frag = [&](const char* stage, int kh, int db) {
     const char* vp = stage + v_off + kh * 16 * ROW_BYTES + ((v_col_x ^ (db << 2)) << 4);
-    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, vp));
-    const s16x4 up = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, vp + 8 * ROW_BYTES));
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(MPIC_LDS_PTR(s16x4, vp));
+    const s16x4 up = __builtin_amdgcn_ds_read_tr16_b64_v4i16(MPIC_LDS_PTR(s16x4, vp + 8 * ROW_BYTES));
     return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, up, 0, 1, 2, 3, 4, 5, 6, 7));
   };
 
@@ -535,21 +437,17 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
 
   // even half step 2t: block t must be complete in LDS, then the loads of block t+2 go out
   auto even_sync = [&](int t) {
-    PHASE_MARK(0)
     if (t < n_iter) {
       // this wave's share of block t has landed when at most the loads of the blocks issued
       // after it are still outstanding
       if (AHEAD == 2 && t + 1 < n_iter) {
-        WAIT_VMCNT(LOADS_PER_STAGE);
+        MPIC_WAIT_VMCNT(LOADS_PER_STAGE);
       } else {
-        WAIT_VMCNT(0);
+        MPIC_WAIT_VMCNT(0);
       }
     }
-    PHASE_MARK(1)
     __syncthreads();
-    PHASE_MARK(2)
     if (t + AHEAD < n_iter) issue_loads(t + AHEAD);
-    PHASE_MARK(3)
   };
   // matrix half step of block t: finish block t-1, start block t (blocks past the last key
   // this wave can see are skipped; the barriers stay aligned)
@@ -558,9 +456,7 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
     __builtin_amdgcn_s_setprio(1);  // the wave that feeds the matrix core is issued first
     if (t < n_iter && t * BN <= wave_hi_pos) {
       if (do_pv) pv_block(t - 1);
-      PHASE_MARK(4)
       qk_block(t);
-      PHASE_MARK(5)
     } else if (do_pv) {
       pv_block(t - 1);
     }
@@ -573,25 +469,17 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
       __syncthreads();  // odd half step 2t+1
       ro = fetch_rows(t + AHEAD + 1);
       if (t < n_iter && t * BN <= wave_hi_pos) softmax_block(t);
-      PHASE_MARK(6)
     }
   } else {
     for (int t = 0; t <= n_iter; ++t) {
       even_sync(t);
       ro = fetch_rows(t + AHEAD + 1);
       if (t >= 1 && (t - 1) * BN <= wave_hi_pos) softmax_block(t - 1);
-      PHASE_MARK(6)
       __syncthreads();  // odd half step 2t+1
       matrix_part(t);
     }
   }
 
-#ifdef MPIC_PHASE_TIMING
-  if (lane == 0 && a.lse) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) a.lse[(static_cast<int64_t>(blockIdx.x) * WAVES + wave) * 8 + i] = ph_sum[i];
-  }
-#endif
   // ---- epilogue: normalise and store this lane's query column ----
   if (!valid) return;
   const float l_tot = sum_across_halves(l_run);
@@ -626,10 +514,7 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
       for (int e = 0; e < 4; ++e) o[e] = acc_o[db][q4 * 4 + e] * inv;
       *reinterpret_cast<bf16x4*>(op + db * 32 + q4 * 8 + hi * 4) = __builtin_convertvector(o, bf16x4);
     }
-#ifndef MPIC_PHASE_TIMING
-  if (a.lse && hi == 0)
-    a.lse[fresh_row * a.n_q_heads + head] = m_run * a.scale + logf(l_tot);
-#endif
+  if (a.lse && hi == 0) a.lse[fresh_row * a.n_q_heads + head] = m_run * a.scale + logf(l_tot);
 }
 
 
@@ -685,17 +570,15 @@ template <int kBlockKeys>
 hipError_t launch_shape(const AttnArgs& a, const AssembleArgs* next, const AssembleSrcTable* next_tab, int dev,
                         hipStream_t stream) {
   using G = Geo<kBlockKeys>;
-  // more than 64 KB of dynamic LDS needs an explicit opt-in, once per device
-  static bool opted_in[64] = {};
-  if (dev >= 0 && dev < 64 && !opted_in[dev]) {
+  static LdsOptIn opt_in;  // one per kernel shape
+  const hipError_t eo = opt_in.ensure(dev, [] {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bf16_kernel<kBlockKeys, NoLink>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES);
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bf16_kernel<kBlockKeys, LinkNext>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    opted_in[dev] = true;
-  }
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bf16_kernel<kBlockKeys, LinkNext>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES);
+  });
+  if (eo != hipSuccess) return eo;
   const int64_t n_pos = next ? next->pos_end - next->pos_begin : 0;
   if (n_pos > 0) {
     LinkNext ln;

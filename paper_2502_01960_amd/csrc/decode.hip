@@ -18,31 +18,19 @@
 // (O, log-sum-exp) partial per split; a second small kernel merges the splits and adds
 // the new token itself.
 #include "common.h"
+#include "wave_ops.h"
 
 namespace mpic {
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef uint32_t u32x8_a4 __attribute__((ext_vector_type(8), aligned(4)));
-
-#ifndef MPIC_DECODE_WAVES
-#define MPIC_DECODE_WAVES 4
-#endif
-#ifndef MPIC_DECODE_STAGES
-#define MPIC_DECODE_STAGES 2
-#endif
 constexpr int D = 128;
-constexpr int WAVES = MPIC_DECODE_WAVES;
+constexpr int WAVES = 4;
 constexpr int THREADS = WAVES * 64;
 constexpr int BN = 32;                           // keys per wavefront block
 constexpr int ROW_BYTES = D * 2;
 constexpr int TILE_BYTES = BN * ROW_BYTES;       // one staged K (or V) block: 8 KB
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;      // K block followed by V block
-constexpr int STAGES = MPIC_DECODE_STAGES;       // blocks in flight per wavefront: STAGES - 1
+constexpr int STAGES = 2;                        // blocks in flight per wavefront: STAGES - 1
 constexpr int WAVE_LDS = STAGES * STAGE_BYTES;
 constexpr int LDS_BYTES = WAVES * WAVE_LDS;
 constexpr int LOADS_PER_BLOCK = 16;              // direct loads per wavefront and block
@@ -51,59 +39,21 @@ static_assert(kDecodeBlockKeys % BN == 0, "a split is a whole number of key bloc
 static_assert(LDS_BYTES <= 160 * 1024 && LOADS_PER_BLOCK * (STAGES - 1) <= 63, "LDS size / load counter range");
 static_assert(WAVES * 32 * D * 4 + 2 * WAVES * 32 * 4 <= LDS_BYTES, "merge area must fit the staging area");
 
-#define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
-
-// LDS[m0 + 16*lane] = 16 bytes at gptr (direct global->LDS load; the outstanding-load
-// counter is managed by hand, see wait_loads).  Every context row is read exactly once per
-// step, hence the non-temporal hint (worth 11 %: the stream no longer evicts itself from L2).
-__device__ inline void load_to_lds_16B(const void* gptr, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off nt"
-               :
-               : "v"(gptr), "s"(lds_addr)
-               : "memory", "m0");
-}
-// s_waitcnt vmcnt(n) only (expcnt / lgkmcnt fields left at "no wait").  The builtin rather
-// than inline assembly: the compiler's own wait insertion sees it and adds nothing on top.
-#define WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
 // wait until at most `blocks` blocks of loads are outstanding; the empty asm keeps the
 // compiler from moving an LDS read above the wait
 __device__ inline void wait_loads(int blocks) {
   if (blocks >= 3) {
-    WAIT_VMCNT(48);
+    MPIC_WAIT_VMCNT(48);
   } else if (blocks == 2) {
-    WAIT_VMCNT(32);
+    MPIC_WAIT_VMCNT(32);
   } else if (blocks == 1) {
-    WAIT_VMCNT(16);
+    MPIC_WAIT_VMCNT(16);
   } else {
-    WAIT_VMCNT(0);
+    MPIC_WAIT_VMCNT(0);
   }
   asm volatile("" ::: "memory");
 }
 static_assert(LOADS_PER_BLOCK == 16, "wait_loads spells the count out");
-
-// Combine a value with the one held by lane ^ 32 (the other half of a query column) with
-// v_permlane32_swap (verified: swapping two copies of a register leaves the low half's values
-// in one result and the high half's in the other, in both halves).  A plain cross-lane shuffle
-// would go through the LDS pipeline, whose command queue the fragment reads keep full.
-// (The two results are copied into scalars before they are reinterpreted: a bit cast applied
-// directly to an element of the returned vector reads element 0 for both.)
-struct Halves {
-  float lo, hi;
-};
-__device__ inline Halves split_halves(float x) {
-  const unsigned a = __builtin_bit_cast(unsigned, x);
-  const auto r = __builtin_amdgcn_permlane32_swap(a, a, false, false);
-  const unsigned r0 = r[0], r1 = r[1];
-  return Halves{__builtin_bit_cast(float, r0), __builtin_bit_cast(float, r1)};
-}
-__device__ inline float max_across_halves(float x) {
-  const Halves h = split_halves(x);
-  return fmaxf(h.lo, h.hi);
-}
-__device__ inline float sum_across_halves(float x) {
-  const Halves h = split_halves(x);
-  return h.lo + h.hi;
-}
 
 __global__ __launch_bounds__(THREADS) void decode_bf16_kernel(DecodeArgs a) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
@@ -129,7 +79,7 @@ __global__ __launch_bounds__(THREADS) void decode_bf16_kernel(DecodeArgs a) {
   const char* kbase = static_cast<const char*>(a.k_ctx) + g * ROW_BYTES;
   const char* vbase = static_cast<const char*>(a.v_ctx) + g * ROW_BYTES;
   char* my_lds = lds + wave * WAVE_LDS;
-  const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(LDS_PTR(char, my_lds)));
+  const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(MPIC_LDS_PTR(char, my_lds)));
 
   // ---- this lane's query column: head cb*32 + col of the kv group (columns past the group
   // repeat its first head and are never written) ----
@@ -171,8 +121,8 @@ __global__ __launch_bounds__(THREADS) void decode_bf16_kernel(DecodeArgs a) {
       const u32x8_a4 q8 = cur.r[p >> 1];
       const int o = (p & 1) * 4;
       const uint32_t r16 = ld_sub == 0 ? q8[o] : ld_sub == 1 ? q8[o + 1] : ld_sub == 2 ? q8[o + 2] : q8[o + 3];
-      load_to_lds_16B(kbase + (static_cast<uint64_t>(r16 + (ld_k16 ^ ((p & 3) << 2))) << 4), dst + p * 4 * ROW_BYTES);
-      load_to_lds_16B(vbase + (static_cast<uint64_t>(r16 + ld_v16) << 4), dst + TILE_BYTES + p * 4 * ROW_BYTES);
+      load_to_lds_16B_nt(kbase + (static_cast<uint64_t>(r16 + (ld_k16 ^ ((p & 3) << 2))) << 4), dst + p * 4 * ROW_BYTES);
+      load_to_lds_16B_nt(vbase + (static_cast<uint64_t>(r16 + ld_v16) << 4), dst + TILE_BYTES + p * 4 * ROW_BYTES);
     }
   };
 
@@ -188,7 +138,7 @@ __global__ __launch_bounds__(THREADS) void decode_bf16_kernel(DecodeArgs a) {
 
   // every ordinary load is complete before the first direct load: from here on the
   // outstanding-load counter only counts staging traffic
-  WAIT_VMCNT(0);
+  MPIC_WAIT_VMCNT(0);
   __builtin_amdgcn_sched_barrier(0);
 
   // Software pipeline: the loads of the next STAGES-1 blocks of this wavefront are in
@@ -264,8 +214,8 @@ __global__ __launch_bounds__(THREADS) void decode_bf16_kernel(DecodeArgs a) {
 #pragma unroll
       for (int db = 0; db < 4; ++db) {
         const char* vp = st + v_off + kh * 16 * ROW_BYTES + ((v_col_x ^ (db << 2)) << 4);
-        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, vp));
-        const s16x4 up = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, vp + 8 * ROW_BYTES));
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(MPIC_LDS_PTR(s16x4, vp));
+        const s16x4 up = __builtin_amdgcn_ds_read_tr16_b64_v4i16(MPIC_LDS_PTR(s16x4, vp + 8 * ROW_BYTES));
         const bf16x8 vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, up, 0, 1, 2, 3, 4, 5, 6, 7));
         acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kh], acc_o[db], 0, 0, 0);
       }
@@ -492,16 +442,15 @@ hipError_t launch_decode(int dtype, const DecodeArgs& a, hipStream_t stream) {
     }
     return hipGetLastError();
   }
-  static bool opted_in[64] = {};
+  static LdsOptIn opt_in;
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
-  if (dev >= 0 && dev < 64 && !opted_in[dev]) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_bf16_kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-    if (e != hipSuccess) return e;
-    opted_in[dev] = true;
-  }
+  e = opt_in.ensure(dev, [] {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(decode_bf16_kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+  });
+  if (e != hipSuccess) return e;
   const int group = a.n_q_heads / a.n_kv_heads;
   const dim3 grid(a.n_splits, a.n_kv_heads * ((group + 31) / 32), a.n_requests);
   if (a.max_ctx > 0) hipLaunchKernelGGL(decode_bf16_kernel, grid, dim3(THREADS), LDS_BYTES, stream, a);

@@ -29,9 +29,6 @@ int fail_hip(mpic_ctx* ctx, hipError_t e, const char* what) {
 
 namespace {
 
-#ifndef MPIC_SPLIT_ROUNDS
-#define MPIC_SPLIT_ROUNDS 2
-#endif
 constexpr int kXcds = 8;  // L2 domains of the chip; workgroup i is dispatched to domain i % 8
 constexpr int kComputeUnits = 256;
 
@@ -63,7 +60,7 @@ void build_tiles(mpic_plan& p, int group, int n_kv_heads) {
   };
   constexpr int64_t kBlock = 64;          // keys per block of the attention kernel
   constexpr int64_t kMinPieceBlocks = 4;
-  constexpr int64_t kSplitRounds = MPIC_SPLIT_ROUNDS;
+  constexpr int64_t kSplitRounds = 2;
   const int B = p.n_requests;
   const int n_combo = B * n_kv_heads;
   auto last_pos = [&](int b, int64_t row_end) {  // position of the last fresh row below flattened row `row_end`
@@ -90,7 +87,6 @@ void build_tiles(mpic_plan& p, int group, int n_kv_heads) {
   count_pieces(tile_rows, &total_blocks);
   const int64_t per_cu = (total_blocks + kComputeUnits - 1) / kComputeUnits;
   const int64_t rounds = std::max<int64_t>(1, std::min<int64_t>(kSplitRounds, per_cu / 16));
-  const bool no_cut = kSplitRounds == 0;
   int64_t cap = std::max<int64_t>(kMinPieceBlocks, (total_blocks + kComputeUnits * rounds - 1) / (kComputeUnits * rounds));
   // rounding up per tile makes more pieces than total / cap: grow the cap until they fit the rounds
   auto count_at_cap = [&](int64_t c) {
@@ -122,7 +118,7 @@ void build_tiles(mpic_plan& p, int group, int n_kv_heads) {
         const int64_t n = std::min<int64_t>(tile_rows, rows - row);
         const int64_t n_keys = last_pos(b, row + n) + 1;
         const int64_t blocks = (n_keys + kBlock - 1) / kBlock;
-        int64_t parts = (blocks > cap_blocks && !no_cut) ? (blocks + cap_blocks - 1) / cap_blocks : 1;
+        int64_t parts = (blocks > cap_blocks) ? (blocks + cap_blocks - 1) / cap_blocks : 1;
         const int64_t per = (blocks + parts - 1) / parts;  // blocks per piece
         parts = (blocks + per - 1) / per;
         for (int64_t i = 0; i < parts; ++i) {
@@ -217,7 +213,7 @@ void build_tiles(mpic_plan& p, int group, int n_kv_heads) {
   // two thirds of a compute unit's whole share).  Whether cutting those pays is decided by
   // simulating the launch for a few piece sizes; the uncut launch is kept unless a cut one
   // is predicted to finish at least 3 % earlier.
-  if (!no_cut && chosen.n_parts == 0) {
+  if (chosen.n_parts == 0) {
     int64_t longest = 0;
     for (int b = 0; b < B; ++b) {
       const int64_t rows = static_cast<int64_t>(p.q_off[b + 1] - p.q_off[b]) * group;
