@@ -362,6 +362,28 @@ int mpic_decode_attn(mpic_ctx* ctx, mpic_plan* plan, const void* q, const void* 
                      double softmax_scale, void* out, float* lse, void* stream);
 
 /*
+ * mpic_decode_attn for callers that cannot allocate: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the same
+ * result, but the partial results of the key splits live in a file-scope device array of the
+ * library (8 MiB per GPU, held until the process ends) instead of the context's workspace,
+ * and the call makes no hipMalloc, hipFree or other allocating call:
+ *   - the context must be bound to the current GPU and the plan already uploaded to it, which
+ *     any earlier GPU call with this plan does (mpic_assemble_kv, mpic_selective_attn,
+ *     mpic_decode_attn); otherwise MPIC_ERR_INVALID;
+ *   - a batch whose partial results ([B][Hq][splits][D+1] floats; splits is chosen so that
+ *     B * Hkv * splits is about 256, and is 1 for larger batches) exceed 8 MiB is rejected
+ *     with MPIC_ERR_UNSUPPORTED before anything is enqueued;
+ *   - the first call on a GPU looks the array's device address up (no allocation).
+ * All calls on one GPU share the array, whatever their context: calls that may overlap (on
+ * different streams, or from different host threads) race.  The kernels write every partial
+ * they later read, so nothing needs clearing between calls.
+ * Errors: as mpic_decode_attn without OOM; INVALID / UNSUPPORTED as above.
+ */
+int mpic_decode_attn_static(mpic_ctx* ctx, mpic_plan* plan, const void* q, const void* new_k,
+                            const void* new_v, const void* k_ctx, const void* v_ctx, int64_t n_ctx_slots,
+                            double softmax_scale, void* out, float* lse, void* stream);
+
+/*
  * K distance of every token of a chunk (Sec. 4.2: the L1 distance between the token's K
  * tensors in two caches of the same image computed at different positions):
  *   dist[t] = sum over kv heads and coordinates of |k_a[t] - k_b[t]|, fp32 accumulation.

@@ -87,6 +87,8 @@ def load_library():
     lib.mpic_selective_attn_link_next.restype = C.c_int
     lib.mpic_decode_attn.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, C.c_double, vp, vp, vp]
     lib.mpic_decode_attn.restype = C.c_int
+    lib.mpic_decode_attn_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, C.c_double, vp, vp, vp]
+    lib.mpic_decode_attn_static.restype = C.c_int
     lib.mpic_k_distance.argtypes = [vp, vp, vp, i64, vp, vp]
     lib.mpic_k_distance.restype = C.c_int
     lib.mpic_rank_tokens.argtypes = [C.POINTER(C.c_float), i64, i64, C.POINTER(i32)]
@@ -319,6 +321,14 @@ def mpic_decode_attn(ctx, plan, q, new_k, new_v, k_ctx, v_ctx, softmax_scale, ou
     rc = load_library().mpic_decode_attn(ctx, plan, _ptr(q), _ptr(new_k), _ptr(new_v), _ptr(k_ctx), _ptr(v_ctx),
                                          0 if k_ctx is None else k_ctx.shape[0], float(softmax_scale),
                                          _ptr(out), _ptr(lse), _stream(stream))
+    _check(rc, ctx)
+
+
+def mpic_decode_attn_static(ctx, plan, q, new_k, new_v, k_ctx, v_ctx, softmax_scale, out, lse=None, stream=None):
+    """mpic_decode_attn with its partial results in the library's static device array (no allocation)."""
+    rc = load_library().mpic_decode_attn_static(ctx, plan, _ptr(q), _ptr(new_k), _ptr(new_v), _ptr(k_ctx),
+                                                _ptr(v_ctx), 0 if k_ctx is None else k_ctx.shape[0],
+                                                float(softmax_scale), _ptr(out), _ptr(lse), _stream(stream))
     _check(rc, ctx)
 
 

@@ -518,10 +518,13 @@ int mpic::attend(mpic_ctx* ctx, mpic_plan* plan, const void* fresh_q,
   return MPIC_OK;
 }
 
+// static_scratch: the partial results go to the library's file-scope device array instead of
+// the context's workspace, and the call allocates nothing (it then needs a context and a plan
+// that an earlier call has already brought to the GPU).
 static int decode_attn_impl(mpic_ctx* ctx, mpic_plan* plan, const void* q, const void* new_k,
                             const void* new_v, const void* k_ctx, const void* v_ctx,
                             int64_t n_ctx_slots, double softmax_scale, void* out, float* lse,
-                            void* stream_) {
+                            void* stream_, bool static_scratch) {
   if (!ctx) return MPIC_ERR_INVALID;
   if (!plan || plan->ctx != ctx) return fail(ctx, MPIC_ERR_INVALID, "decode_attn: plan does not belong to this context");
   if (!(softmax_scale > 0.0) || !std::isfinite(softmax_scale)) return fail(ctx, MPIC_ERR_INVALID, "decode_attn: softmax_scale must be finite and positive");
@@ -532,10 +535,21 @@ static int decode_attn_impl(mpic_ctx* ctx, mpic_plan* plan, const void* q, const
   if (!mpic::aligned16(q) || !mpic::aligned16(out) || !mpic::aligned16(k_ctx) || !mpic::aligned16(v_ctx) ||
       !mpic::aligned16(new_k) || !mpic::aligned16(new_v))
     return fail(ctx, MPIC_ERR_INVALID, "decode_attn: buffers must be 16-byte aligned");
-  int rc = mpic::bind_device(ctx);
-  if (rc != MPIC_OK) return rc;
-  rc = mpic::upload_plan(ctx, plan);
-  if (rc != MPIC_OK) return rc;
+  int rc = MPIC_OK;
+  if (static_scratch) {
+    int dev = -1;
+    MPIC_HIP(ctx, hipGetDevice(&dev));
+    if (ctx->device < 0 || !plan->dev.block)
+      return fail(ctx, MPIC_ERR_INVALID, "decode_attn_static: the plan is not on the GPU yet (an earlier call with this plan, "
+                                         "e.g. mpic_assemble_kv, uploads it)");
+    if (ctx->device != dev || plan->dev.device != dev)
+      return fail(ctx, MPIC_ERR_INVALID, "decode_attn_static: context and plan live on another GPU than the current one");
+  } else {
+    rc = mpic::bind_device(ctx);
+    if (rc != MPIC_OK) return rc;
+    rc = mpic::upload_plan(ctx, plan);
+    if (rc != MPIC_OK) return rc;
+  }
   const mpic_config& c = ctx->cfg;
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   int32_t max_ctx = 0;
@@ -555,7 +569,14 @@ static int decode_attn_impl(mpic_ctx* ctx, mpic_plan* plan, const void* q, const
   }
   const size_t rows = static_cast<size_t>(plan->n_requests) * c.n_q_heads;
   const size_t need = rows * n_splits * (c.head_dim + 1) * sizeof(float);
-  if (need > ctx->decode_ws_bytes) {
+  float* ws = nullptr;
+  if (static_scratch) {
+    size_t have = 0;
+    MPIC_HIP(ctx, mpic::decode_static_scratch(&ws, &have));
+    if (need > have)
+      return fail(ctx, MPIC_ERR_UNSUPPORTED, "decode_attn_static: the partial results of this batch (" + std::to_string(need) +
+                                             " bytes) exceed the static scratch array (" + std::to_string(have) + " bytes)");
+  } else if (need > ctx->decode_ws_bytes) {
     // growing the workspace is rare (first call / larger batch): drain what may still read it
     MPIC_HIP(ctx, hipDeviceSynchronize());
     if (ctx->decode_ws) MPIC_HIP(ctx, hipFree(ctx->decode_ws));
@@ -578,7 +599,8 @@ static int decode_attn_impl(mpic_ctx* ctx, mpic_plan* plan, const void* q, const
   a.v_ctx = v_ctx;
   a.out = out;
   a.lse = lse;
-  a.ws_o = static_cast<float*>(ctx->decode_ws);
+  if (!static_scratch) ws = static_cast<float*>(ctx->decode_ws);
+  a.ws_o = ws;
   a.ws_lse = a.ws_o + rows * n_splits * c.head_dim;
   a.scale = static_cast<float>(softmax_scale);
   a.n_q_heads = c.n_q_heads;
@@ -644,5 +666,13 @@ extern "C" int mpic_decode_attn(mpic_ctx* ctx, mpic_plan* plan, const void* q, c
                                 int64_t n_ctx_slots, double softmax_scale, void* out, float* lse,
                                 void* stream) {
   MPIC_GUARDED(ctx, decode_attn_impl(ctx, plan, q, new_k, new_v, k_ctx, v_ctx, n_ctx_slots, softmax_scale, out, lse,
-                                     stream))
+                                     stream, false))
+}
+
+extern "C" int mpic_decode_attn_static(mpic_ctx* ctx, mpic_plan* plan, const void* q, const void* new_k,
+                                       const void* new_v, const void* k_ctx, const void* v_ctx,
+                                       int64_t n_ctx_slots, double softmax_scale, void* out, float* lse,
+                                       void* stream) {
+  MPIC_GUARDED(ctx, decode_attn_impl(ctx, plan, q, new_k, new_v, k_ctx, v_ctx, n_ctx_slots, softmax_scale, out, lse,
+                                     stream, true))
 }

@@ -227,6 +227,9 @@ struct DecodeArgs {
   int32_t max_ctx;  // longest context of the batch
 };
 hipError_t launch_decode(int dtype, const DecodeArgs& a, hipStream_t stream);
+// Device address and size of the file-scope scratch array of the decode kernels on the
+// current GPU (looked up once per device; allocates nothing).
+hipError_t decode_static_scratch(float** ptr, size_t* bytes);
 hipError_t launch_attn_f32(const AttnArgs& a, int64_t n_q, hipStream_t stream);
 
 

@@ -428,6 +428,33 @@ __global__ __launch_bounds__(256) void decode_f32_kernel(DecodeArgs a) {
 
 }  // namespace
 
+// Scratch of mpic_decode_attn_static: partial results of the key splits for callers that must
+// not allocate.  The array exists once per GPU for the life of the process.  In host code its
+// name is only a handle: the device address comes from hipGetSymbolAddress, looked up once per
+// device with that device current, and only that address is handed to kernels.
+constexpr size_t kStaticScratchBytes = size_t{8} << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+hipError_t decode_static_scratch(float** ptr, size_t* bytes) {
+  static std::mutex mu;
+  static void* addr[64] = {};
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!addr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    addr[dev] = p;
+  }
+  *ptr = static_cast<float*>(addr[dev]);
+  *bytes = kStaticScratchBytes;
+  return hipSuccess;
+}
+
 hipError_t launch_decode(int dtype, const DecodeArgs& a, hipStream_t stream) {
   const int64_t rows = static_cast<int64_t>(a.n_requests) * a.n_q_heads;
   if (rows <= 0) return hipSuccess;

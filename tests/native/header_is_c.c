@@ -7,7 +7,7 @@ static void* use[] = {
     (void*)mpic_create,          (void*)mpic_destroy,        (void*)mpic_plan_create,  (void*)mpic_plan_create_selected,
     (void*)mpic_plan_get,        (void*)mpic_plan_get_rope,  (void*)mpic_plan_get_fresh_rope,
     (void*)mpic_plan_destroy,    (void*)mpic_assemble_kv,    (void*)mpic_assemble_kv_parts,
-    (void*)mpic_selective_attn,  (void*)mpic_decode_attn,    (void*)mpic_k_distance,   (void*)mpic_rank_tokens,
+    (void*)mpic_selective_attn,  (void*)mpic_decode_attn,  (void*)mpic_decode_attn_static,  (void*)mpic_k_distance,   (void*)mpic_rank_tokens,
     (void*)mpic_store_create,    (void*)mpic_store_destroy,  (void*)mpic_store_put,    (void*)mpic_store_move,
     (void*)mpic_store_expire,    (void*)mpic_store_drop,     (void*)mpic_store_lookup, (void*)mpic_store_layer,
     (void*)mpic_prefill_layers,  (void*)mpic_selective_attn_link_next, (void*)mpic_set_option,  (void*)mpic_strerror,       (void*)mpic_last_error};
