@@ -17,6 +17,10 @@ Pin status of every function (see tests/test_oracle_*.py):
   link.position_fresh    pinned: row-by-row complex form of RoPE at per-request position
                          ids, full prefill reproduced from unpositioned fresh rows,
                          logits depend on the signed distance only
+  link.link_kv_unshifted / attend.attend_unshifted   pinned: <Rot(-D) q, k> = <q, Rot(D) k> per
+                         chunk instance (also against the complex form), and the pair gives
+                         the outputs of link_kv + attend on random layouts, both pairings,
+                         rotated and unrotated fresh rows
   attend.attend          pinned: loop transcription of App. A, library SDPA in the
                          recompute-all case, closed forms (zero queries, one-hot V)
   decode.decode_attend   pinned: the last row of causal prefill over context + new token
@@ -38,8 +42,8 @@ values are unpinned by the paper itself.
 """
 from .plan import build_plan            # noqa: F401
 from .rope import rotate                # noqa: F401
-from .link import link_kv, position_fresh, to_slots     # noqa: F401
-from .attend import attend, attend_loops  # noqa: F401
+from .link import link_kv, link_kv_unshifted, position_fresh, to_slots     # noqa: F401
+from .attend import attend, attend_loops, attend_unshifted  # noqa: F401
 from .decode import decode_attend       # noqa: F401
 from .select import k_distance, top_tokens, top_counts  # noqa: F401
 from .store import ChunkStore            # noqa: F401

@@ -40,6 +40,41 @@ def attend(q, k_ctx, v_ctx, plan, scale, rows=None):
     return out, lse
 
 
+def attend_unshifted(q, k_ctx, v_ctx, shift, plan, theta, scale, interleaved=False, rows=None):
+    """Selective attention over a context whose stored keys were linked without their position
+    shift (link.link_kv_unshifted).  The rotation is orthogonal, so the logit of query q and a
+    key that still lacks the shift D is <q, Rot(D) k> = <Rot(-D) q, k>: the query is turned
+    back by the shift of the key's chunk instead of the key being turned forward.  Same
+    softmax and same sums as attend (App. A); written key by key."""
+    from .rope import rotate
+    q = np.asarray(q, dtype=np.float64)
+    k_ctx = np.asarray(k_ctx, dtype=np.float64)
+    v_ctx = np.asarray(v_ctx, dtype=np.float64)
+    nq, hq, d = q.shape
+    group = hq // k_ctx.shape[1]
+    out = np.full((nq, hq, d), np.nan)
+    lse = np.full((nq, hq), np.nan)
+    todo = np.arange(nq) if rows is None else np.asarray(rows, dtype=np.int64)
+    for r in todo:
+        b = int(plan["q_req"][r])
+        base = int(plan["ctx_off"][b])
+        n_keys = int(plan["q_pos"][r]) + 1
+        sh = np.asarray(shift[base:base + n_keys])
+        s = np.empty((hq, n_keys))
+        for dlt in np.unique(sh):                      # one turned-back query per distinct shift
+            qt = rotate(q[r], -float(dlt), theta, interleaved)      # [Hq][D]
+            at = np.nonzero(sh == dlt)[0]
+            for h in range(hq):
+                s[h, at] = scale * (k_ctx[base + at, h // group, :] @ qt[h])
+        for h in range(hq):
+            m = s[h].max()
+            w = np.exp(s[h] - m)
+            z = w.sum()
+            out[r, h] = (w @ v_ctx[base:base + n_keys, h // group, :]) / z
+            lse[r, h] = m + np.log(z)
+    return out, lse
+
+
 def attend_loops(q, k_ctx, v_ctx, plan, scale):
     """The same definition with every sum written as a Python loop (tiny inputs)."""
     import math

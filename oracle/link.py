@@ -47,6 +47,31 @@ def link_kv(plan, chunk_k, chunk_v, fresh_k, fresh_v, theta, interleaved=False, 
     return K, V
 
 
+def link_kv_unshifted(plan, chunk_k, chunk_v, fresh_k, fresh_v, theta, interleaved=False, fresh_pre_rope=False):
+    """The linked context with the stored keys left as they are stored (Sec. 4.1: the linker
+    only joins caches; Fig. 7 step 2 replaces rows and touches nothing else).  Returns
+    (K, V, shift): K and V as link_kv but stored keys unrotated, and shift [N] = the position
+    shift each key still lacks (its chunk's offset; 0 for fresh rows, which carry their
+    global position).  attend.attend_unshifted consumes the triple."""
+    n = int(plan["ctx_off"][-1])
+    fresh_k = np.asarray(fresh_k, dtype=np.float64)
+    if fresh_pre_rope:
+        fresh_k = position_fresh(fresh_k, plan, theta, interleaved)
+    fresh_v = np.asarray(fresh_v, dtype=np.float64)
+    K = np.empty((n,) + fresh_k.shape[1:], dtype=np.float64)
+    V = np.empty_like(K)
+    shift = np.zeros(n, dtype=np.int64)
+    for pos in range(n):
+        i, r = int(plan["src_inst"][pos]), int(plan["src_row"][pos])
+        if i < 0:
+            K[pos], V[pos] = fresh_k[r], fresh_v[r]
+        else:
+            cache = int(plan["inst_src"][i])
+            K[pos], V[pos] = chunk_k[cache][r], chunk_v[cache][r]
+            shift[pos] = int(plan["inst_delta"][i])
+    return K, V, shift
+
+
 def to_slots(x_logical, dst_slot, n_slots, fill=np.nan):
     """Place logical rows at their physical slots (paged layout); unused slots = fill."""
     out = np.full((n_slots,) + x_logical.shape[1:], fill, dtype=x_logical.dtype)

@@ -10,7 +10,8 @@ import pytest
 import torch
 
 import workloads
-from oracle import attend, attend_loops, build_plan, decode_attend, link_kv, position_fresh, rotate, to_slots
+from oracle import (attend, attend_loops, attend_unshifted, build_plan, decode_attend, link_kv, link_kv_unshifted,
+                    position_fresh, rotate, to_slots)
 
 RNG = np.random.default_rng(1234)
 
@@ -352,3 +353,50 @@ def test_decode_step_closed_forms():
     big = K.copy(); big[9] = 50.0 * q[2] / np.linalg.norm(q[2], axis=-1, keepdims=True)
     o3, _ = decode_attend(q, big, V, plan, 1.0)
     np.testing.assert_allclose(o3[2], V[9], atol=1e-6)
+
+
+# ----------------------------------------------------------------- keys linked without their shift
+@pytest.mark.parametrize("interleaved", [False, True])
+def test_turning_the_query_back_equals_turning_the_key_forward(interleaved):
+    """<Rot(-D) q, k> = <q, Rot(D) k>, per head, for the shifts of real layouts; the left side
+    also against the complex-number form of RoPE (conjugate phase on the query)."""
+    theta, D = 1e6, 128
+    q = RNG.standard_normal((6, D))
+    k = RNG.standard_normal((6, D))
+    for delta in (0, 1, 128, 2560, 19584, 75776):
+        lhs = np.einsum("id,id->i", rotate(q, -delta, theta, interleaved), k)
+        rhs = np.einsum("id,id->i", q, rotate(k, delta, theta, interleaved))
+        assert np.abs(lhs - rhs).max() < 1e-10
+        ref = np.einsum("id,id->i", _rope_complex(q, -delta, theta, interleaved), k)
+        assert np.abs(lhs - ref).max() < 1e-10
+    # the sign matters: turning the query forward instead is a different number
+    wrong = np.einsum("id,id->i", rotate(q, 2560, theta, interleaved), k)
+    assert np.abs(wrong - np.einsum("id,id->i", q, rotate(k, 2560, theta, interleaved))).max() > 1e-3
+
+
+@pytest.mark.parametrize("interleaved,pre_rope", [(False, False), (True, False), (False, True)])
+def test_unshifted_link_and_attend_equal_shifted_link_and_attend(interleaved, pre_rope):
+    """Leaving stored keys as stored and turning each query back per chunk instance gives the
+    outputs of the linked-and-shifted context: same chunk twice, adjacent chunks, k = 0 and
+    k beyond the chunk, two requests."""
+    theta, hq, hkv, d = 5e5, 4, 2, 16
+    reqs = [[("text", 3), ("chunk", 0, 9, None), ("chunk", 1, 5, 0), ("text", 2), ("chunk", 0, 9, 4), ("text", 1)],
+            [("chunk", 1, 5, 9), ("chunk", 0, 9, None), ("text", 4)]]
+    plan = build_plan(reqs, 2)
+    ck = {0: RNG.standard_normal((9, hkv, d)), 1: RNG.standard_normal((5, hkv, d))}
+    cv = {0: RNG.standard_normal((9, hkv, d)), 1: RNG.standard_normal((5, hkv, d))}
+    nq = int(plan["q_off"][-1])
+    q, fk, fv = (RNG.standard_normal((nq, h, d)) for h in (hq, hkv, hkv))
+    K, V = link_kv(plan, ck, cv, fk, fv, theta, interleaved, pre_rope)
+    qq = position_fresh(q, plan, theta, interleaved) if pre_rope else q
+    O, L = attend(qq, K, V, plan, 0.25)
+    K0, V0, shift = link_kv_unshifted(plan, ck, cv, fk, fv, theta, interleaved, pre_rope)
+    assert np.array_equal(V0, V)
+    stored = plan["src_inst"] >= 0
+    assert np.array_equal(K0[~stored], K[~stored])                       # fresh rows are the same rows
+    assert np.array_equal(shift[stored], plan["inst_delta"][plan["src_inst"][stored]]) and not shift[~stored].any()
+    for g in np.nonzero(stored)[0]:                                      # stored rows: exactly as stored
+        i = int(plan["src_inst"][g])
+        assert np.array_equal(K0[g], ck[int(plan["inst_src"][i])][int(plan["src_row"][g])])
+    O0, L0 = attend_unshifted(qq, K0, V0, shift, plan, theta, 0.25, interleaved)
+    assert np.abs(O0 - O).max() < 1e-11 and np.abs(L0 - L).max() < 1e-11

@@ -119,6 +119,38 @@ def test_linking_pins(monkeypatch, what, old, new):
     assert _bites(LINK_PINS) >= 1, what
 
 
+UNSHIFTED_PINS = [lambda: M.test_unshifted_link_and_attend_equal_shifted_link_and_attend(False, False),
+                  lambda: M.test_unshifted_link_and_attend_equal_shifted_link_and_attend(True, False),
+                  lambda: M.test_unshifted_link_and_attend_equal_shifted_link_and_attend(False, True)]
+UNSHIFTED_LINK_MISTAKES = [
+    ("the shift a key lacks is its chunk's index", "shift[pos] = int(plan[\"inst_delta\"][i])", "shift[pos] = i"),
+    ("fresh rows marked as lacking a shift", "shift = np.zeros(n, dtype=np.int64)", "shift = np.full(n, 5, dtype=np.int64)"),
+    ("stored value taken from the key cache", "K[pos], V[pos] = chunk_k[cache][r], chunk_v[cache][r]",
+     "K[pos], V[pos] = chunk_k[cache][r], chunk_k[cache][r]"),
+]
+UNSHIFTED_ATTEND_MISTAKES = [
+    ("query turned forward instead of back", "qt = rotate(q[r], -float(dlt), theta, interleaved)", "qt = rotate(q[r], float(dlt), theta, interleaved)"),
+    ("query never turned", "qt = rotate(q[r], -float(dlt), theta, interleaved)", "qt = q[r]"),
+    ("one key too few", "n_keys = int(plan[\"q_pos\"][r]) + 1", "n_keys = max(1, int(plan[\"q_pos\"][r]))"),
+    ("kv head by remainder", "k_ctx[base + at, h // group, :] @ qt[h]", "k_ctx[base + at, h % k_ctx.shape[1], :] @ qt[h]"),
+    ("scale dropped", "s[h, at] = scale * (", "s[h, at] = 1.0 * ("),
+]
+
+
+@pytest.mark.parametrize("what,old,new", UNSHIFTED_LINK_MISTAKES, ids=[m[0] for m in UNSHIFTED_LINK_MISTAKES])
+def test_unshifted_linking_pins(monkeypatch, what, old, new):
+    bad = _mutant(oracle.link, old, new)
+    monkeypatch.setattr(M, "link_kv_unshifted", bad.link_kv_unshifted)
+    assert _bites(UNSHIFTED_PINS) >= 1, what
+
+
+@pytest.mark.parametrize("what,old,new", UNSHIFTED_ATTEND_MISTAKES, ids=[m[0] for m in UNSHIFTED_ATTEND_MISTAKES])
+def test_unshifted_attention_pins(monkeypatch, what, old, new):
+    bad = _mutant(ATTEND, old, new)
+    monkeypatch.setattr(M, "attend_unshifted", bad.attend_unshifted)
+    assert _bites(UNSHIFTED_PINS) >= 1, what
+
+
 ATTEND_MISTAKES = [
     ("a token does not see itself", "> pos[:, None]", ">= pos[:, None]"),
     ("a token sees one key too many", "np.arange(n_keys)[None, :] > pos[:, None]", "np.arange(n_keys)[None, :] > pos[:, None] + 1"),
