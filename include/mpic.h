@@ -67,6 +67,16 @@ typedef struct mpic_config {
                             /*    library rotates them (K while linking, Q while     */
                             /*    attending) by the position id of their token, the  */
                             /*    positional step that Fig. 7 leaves out             */
+  int32_t lazy_rope;        /* 0: stored keys are rotated to their global position   */
+                            /*    while they are linked (the context holds final     */
+                            /*    keys);                                             */
+                            /* 1: stored keys are never rewritten: linking copies    */
+                            /*    them as stored (or does not touch them at all, see */
+                            /*    mpic_selective_attn_in_place) and the attention    */
+                            /*    kernels turn the query back by the shift of each   */
+                            /*    chunk instance instead, <Rot(-s) q, k> =           */
+                            /*    <q, Rot(s) k> (Sec. 4.1: single-step linking that  */
+                            /*    only joins caches; Fig. 7 step 2)                  */
 } mpic_config;
 
 /* One segment of a request, in prompt order. */
@@ -123,6 +133,15 @@ enum {
                              /* (mpic_selective_attn_link_next); 1 if that is also predicted   */
                              /* to pay (the linking fits into the idle time, or the launch is  */
                              /* too short for a second stream to help)                         */
+  MPIC_PLAN_KEY_BLOCKS_32 = 16, /* lazy_rope contexts: [n_blocks][4] (first position, keys,    */
+  MPIC_PLAN_KEY_BLOCKS_64 = 17, /* chunk instance or -1 = fresh rows, request): the keys of    */
+  MPIC_PLAN_KEY_BLOCKS_96 = 18, /* every request cut into blocks of at most 32 / 64 / 96 keys  */
+                             /* that never straddle a change of source, request after request; */
+                             /* the decode kernel walks the first list, the two shapes of the  */
+                             /* attention kernel the others                                    */
+  MPIC_PLAN_LAZY_TILES_64 = 19, /* lazy_rope contexts: MPIC_PLAN_ATTN_TILES with (end key,     */
+  MPIC_PLAN_LAZY_TILES_96 = 20, /* first key) replaced by (end block, first block) counted     */
+                             /* from the request's first block of that list                    */
   MPIC_PLAN_ATTN_TILES = 14  /* [n_tiles][8] launch order of the attention kernel: (request,   */
                              /* kv head, first flattened row, rows, end key, first key, slot   */
                              /* of the partial result or -1, 0); flattened row = (fresh row -  */
@@ -236,7 +255,9 @@ void mpic_plan_destroy(mpic_plan* plan);
  *     (pair (x, y) -> (x cos - y sin, x sin + y cos)), computed in fp32 and rounded
  *     once to the storage type.
  * Slots that belong to no position (tail of a last page, unused pool pages) are not
- * touched.
+ * touched.  On a context with lazy_rope = 1 stored keys are copied as stored, bit for bit
+ * (K_ctx[slot] = K_c[t]); mpic_selective_attn and mpic_decode_attn then apply the shift on
+ * the query side.
  *
  *   srcs [n_srcs]     host array; every chunk index used by the plan must be < n_srcs
  *                     and srcs[i].len must match.  k / v: device, or pinned host memory
@@ -307,6 +328,29 @@ int mpic_selective_attn(mpic_ctx* ctx, mpic_plan* plan, const void* fresh_q, int
                         double softmax_scale, void* out, float* lse, void* stream);
 
 /*
+ * Selective attention over caches that are linked by reference (contexts created with
+ * lazy_rope = 1; Sec. 4.1: the linker joins the stored caches in a single step; Fig. 7 steps
+ * 2-3).  Same result as mpic_assemble_kv followed by mpic_selective_attn, but no stored row is
+ * copied or rewritten: the kernel reads the rows of every chunk instance where its cache is
+ * stored (srcs, device memory) and turns the query back by the instance's shift; only the rows
+ * of the recompute set are read from k_ctx / v_ctx, where mpic_assemble_kv_parts with
+ * MPIC_PART_FRESH has put them (the other slots of the context are never touched and may hold
+ * anything).  Per layer the linking traffic drops from 4 * N * Hkv * D * elem bytes to
+ * 4 * Nq * Hkv * D * elem, and caches of chunks shared by several requests exist once.
+ *   srcs [n_srcs]     as for mpic_assemble_kv; every source the plan reads must be
+ *                     MPIC_SRC_DEVICE (copy host-resident caches to the GPU first, or use
+ *                     mpic_assemble_kv + mpic_selective_attn, which on these contexts copies
+ *                     stored keys unrotated)
+ * BF16: at most 128 chunk instances per plan (their addresses travel as kernel arguments).
+ * Errors: as mpic_selective_attn; INVALID on a context without lazy_rope or for a source that
+ * is not in device memory; UNSUPPORTED beyond 128 instances.
+ */
+int mpic_selective_attn_in_place(mpic_ctx* ctx, mpic_plan* plan, const void* fresh_q, int64_t n_fresh_rows,
+                                 const mpic_chunk_src* srcs, int32_t n_srcs, const void* k_ctx,
+                                 const void* v_ctx, int64_t n_ctx_slots, double softmax_scale, void* out,
+                                 float* lse, void* stream);
+
+/*
  * mpic_selective_attn of one layer and, in the same launch, the stored rows of the next
  * layer's context (what mpic_assemble_kv_parts with MPIC_PART_CACHED writes): workgroups
  * that follow the attention tiles in the grid link them while the attention drains, on
@@ -360,6 +404,17 @@ int mpic_selective_attn_link_next(mpic_ctx* ctx, mpic_plan* plan, const void* fr
 int mpic_decode_attn(mpic_ctx* ctx, mpic_plan* plan, const void* q, const void* new_k,
                      const void* new_v, const void* k_ctx, const void* v_ctx, int64_t n_ctx_slots,
                      double softmax_scale, void* out, float* lse, void* stream);
+
+/*
+ * mpic_decode_attn over caches linked by reference (lazy_rope contexts): stored rows are read
+ * in their caches (srcs: device memory, as for mpic_selective_attn_in_place), rows of the
+ * recompute set in k_ctx / v_ctx.  Same arguments otherwise, same result.
+ * Errors: as mpic_decode_attn and mpic_selective_attn_in_place.
+ */
+int mpic_decode_attn_in_place(mpic_ctx* ctx, mpic_plan* plan, const void* q, const void* new_k,
+                              const void* new_v, const mpic_chunk_src* srcs, int32_t n_srcs,
+                              const void* k_ctx, const void* v_ctx, int64_t n_ctx_slots,
+                              double softmax_scale, void* out, float* lse, void* stream);
 
 /*
  * mpic_decode_attn for callers that cannot allocate: code under HIP graph capture, tight

@@ -13,7 +13,8 @@ MPIC_F32, MPIC_BF16 = 0, 1
 
 PLAN_FIELDS = dict(ctx_off=0, q_off=1, q_pos=2, q_req=3, slot_map=4, src_inst=5, src_row=6,
                    dst_slot=7, inst_src=8, inst_delta=9, inst_len=10, inst_k=11, inst_req=12,
-                   runs=13, attn_tiles=14, launch_estimate=15)
+                   runs=13, attn_tiles=14, launch_estimate=15, key_blocks_32=16, key_blocks_64=17,
+                   key_blocks_96=18, lazy_tiles_64=19, lazy_tiles_96=20)
 
 
 class MpicError(RuntimeError):
@@ -25,7 +26,7 @@ class MpicError(RuntimeError):
 class _Config(C.Structure):
     _fields_ = [("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("dtype", C.c_int32), ("rope_theta", C.c_double), ("rope_interleaved", C.c_int32),
-                ("page_size", C.c_int32), ("fresh_pre_rope", C.c_int32)]
+                ("page_size", C.c_int32), ("fresh_pre_rope", C.c_int32), ("lazy_rope", C.c_int32)]
 
 
 class _Segment(C.Structure):
@@ -87,6 +88,12 @@ def load_library():
     lib.mpic_selective_attn_link_next.restype = C.c_int
     lib.mpic_decode_attn.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, C.c_double, vp, vp, vp]
     lib.mpic_decode_attn.restype = C.c_int
+    lib.mpic_selective_attn_in_place.argtypes = [vp, vp, vp, i64, C.POINTER(_ChunkSrc), i32, vp, vp, i64, C.c_double,
+                                                 vp, vp, vp]
+    lib.mpic_selective_attn_in_place.restype = C.c_int
+    lib.mpic_decode_attn_in_place.argtypes = [vp, vp, vp, vp, vp, C.POINTER(_ChunkSrc), i32, vp, vp, i64, C.c_double,
+                                              vp, vp, vp]
+    lib.mpic_decode_attn_in_place.restype = C.c_int
     lib.mpic_decode_attn_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, C.c_double, vp, vp, vp]
     lib.mpic_decode_attn_static.restype = C.c_int
     lib.mpic_k_distance.argtypes = [vp, vp, vp, i64, vp, vp]
@@ -137,9 +144,9 @@ def _check(rc, ctx=None):
 
 
 def mpic_create(n_q_heads, n_kv_heads, head_dim, dtype, rope_theta, rope_interleaved=0, page_size=0,
-                fresh_pre_rope=0):
+                fresh_pre_rope=0, lazy_rope=0):
     cfg = _Config(n_q_heads, n_kv_heads, head_dim, dtype, rope_theta, rope_interleaved, page_size,
-                  fresh_pre_rope)
+                  fresh_pre_rope, lazy_rope)
     h = C.c_void_p()
     _check(load_library().mpic_create(C.byref(h), C.byref(cfg)))
     return h
@@ -216,8 +223,10 @@ def mpic_plan_get(plan, what):
     out = np.ctypeslib.as_array(p, shape=(n.value,)).copy() if n.value else np.zeros(0, np.int32)
     if code == PLAN_FIELDS["runs"]:
         out = out.reshape(-1, 4)
-    elif code == PLAN_FIELDS["attn_tiles"]:
+    elif code in (PLAN_FIELDS["attn_tiles"], PLAN_FIELDS["lazy_tiles_64"], PLAN_FIELDS["lazy_tiles_96"]):
         out = out.reshape(-1, 8)
+    elif code in (PLAN_FIELDS["key_blocks_32"], PLAN_FIELDS["key_blocks_64"], PLAN_FIELDS["key_blocks_96"]):
+        out = out.reshape(-1, 4)
     return out
 
 
@@ -302,6 +311,24 @@ def mpic_selective_attn(ctx, plan, fresh_q, k_ctx, v_ctx, softmax_scale, out, ls
     rc = load_library().mpic_selective_attn(ctx, plan, _ptr(fresh_q), n_fresh, _ptr(k_ctx), _ptr(v_ctx),
                                             k_ctx.shape[0], float(softmax_scale), _ptr(out), _ptr(lse),
                                             _stream(stream))
+    _check(rc, ctx)
+
+
+def mpic_selective_attn_in_place(ctx, plan, fresh_q, srcs, k_ctx, v_ctx, softmax_scale, out, lse=None, stream=None):
+    """Attention over caches linked by reference (lazy_rope contexts): stored rows are read in `srcs`."""
+    arr, n_srcs = _src_array(srcs, MPIC_SRC_HOST_STAGED)
+    n_fresh = 0 if fresh_q is None else fresh_q.shape[0]
+    rc = load_library().mpic_selective_attn_in_place(ctx, plan, _ptr(fresh_q), n_fresh, arr, n_srcs, _ptr(k_ctx),
+                                                     _ptr(v_ctx), k_ctx.shape[0], float(softmax_scale), _ptr(out),
+                                                     _ptr(lse), _stream(stream))
+    _check(rc, ctx)
+
+
+def mpic_decode_attn_in_place(ctx, plan, q, new_k, new_v, srcs, k_ctx, v_ctx, softmax_scale, out, lse=None, stream=None):
+    arr, n_srcs = _src_array(srcs, MPIC_SRC_HOST_STAGED)
+    rc = load_library().mpic_decode_attn_in_place(ctx, plan, _ptr(q), _ptr(new_k), _ptr(new_v), arr, n_srcs,
+                                                  _ptr(k_ctx), _ptr(v_ctx), 0 if k_ctx is None else k_ctx.shape[0],
+                                                  float(softmax_scale), _ptr(out), _ptr(lse), _stream(stream))
     _check(rc, ctx)
 
 
@@ -434,9 +461,9 @@ def mpic_prefill_layers(ctx, plan, store, ids, fresh_q, fresh_k, fresh_v, k_ctx,
 # ---------------------------------------------------------------- handle owners
 class Context:
     def __init__(self, n_q_heads, n_kv_heads, head_dim, dtype, rope_theta, rope_interleaved=0, page_size=0,
-                 fresh_pre_rope=0):
+                 fresh_pre_rope=0, lazy_rope=0):
         self.handle = mpic_create(n_q_heads, n_kv_heads, head_dim, dtype, rope_theta, rope_interleaved, page_size,
-                                  fresh_pre_rope)
+                                  fresh_pre_rope, lazy_rope)
         self.n_q_heads, self.n_kv_heads, self.head_dim = n_q_heads, n_kv_heads, head_dim
         self.dtype, self.page_size = dtype, page_size
 

@@ -5,6 +5,7 @@
 #include <cmath>
 #include <cstring>
 #include <new>
+#include <string>
 
 #include "common.h"
 
@@ -75,6 +76,33 @@ int upload_plan(mpic_ctx* ctx, mpic_plan* p) {
   const size_t o_fresh_sin = put(p->fresh_sin.data(), p->fresh_sin.size() * 4);
   const size_t o_tiles = put(p->tiles.data(), p->tiles.size() * sizeof(AttnTile));
   const size_t o_merges = put(p->merges.data(), p->merges.size() * sizeof(AttnMerge));
+  // lazy_rope contexts: key blocks, their row-offset tables in both views, tiles in block indices
+  size_t o_kblk[kNumBlockSizes] = {}, o_first[kNumBlockSizes] = {}, o_vctx[kNumBlockSizes] = {},
+         o_vref[kNumBlockSizes] = {}, o_ltiles[kNumBlockSizes] = {};
+  const bool lazy = ctx->cfg.lazy_rope != 0;
+  if (lazy) {
+    for (int s = 0; s < kNumBlockSizes; ++s) {
+      const size_t bn = kBlockSizes[s];
+      const std::vector<KeyBlock>& blocks = p->kblk[s];
+      // slots past n_valid repeat the block's last row: what is staged there is masked, but it
+      // must be a row that exists (in-place reads must stay inside their source)
+      std::vector<uint32_t> vctx(blocks.size() * bn + kTablePad, 0u), vref(vctx.size(), 0u);
+      for (size_t t = 0; t < blocks.size(); ++t) {
+        const KeyBlock& kb = blocks[t];
+        const size_t ctx0 = p->ctx_off[kb.req];
+        for (size_t i = 0; i < bn; ++i) {
+          const size_t pos = ctx0 + kb.pos0 + std::min<size_t>(i, kb.n_valid - 1);
+          vctx[t * bn + i] = off[pos];
+          vref[t * bn + i] = kb.inst < 0 ? off[pos] : static_cast<uint32_t>(static_cast<uint64_t>(p->src_row[pos]) * units);
+        }
+      }
+      o_kblk[s] = put(blocks.data(), blocks.size() * sizeof(KeyBlock));
+      o_first[s] = put(p->kblk_first[s].data(), p->kblk_first[s].size() * 4);
+      o_vctx[s] = put(vctx.data(), vctx.size() * 4);
+      o_vref[s] = put(vref.data(), vref.size() * 4);
+      o_ltiles[s] = put(p->lazy_tiles[s].data(), p->lazy_tiles[s].size() * sizeof(AttnTile));
+    }
+  }
   image.resize(image.size() + 256, 0);
 
   char* base = nullptr;
@@ -105,6 +133,15 @@ int upload_plan(mpic_ctx* ctx, mpic_plan* p) {
   }
   d.tiles = reinterpret_cast<AttnTile*>(base + o_tiles);
   d.merges = reinterpret_cast<AttnMerge*>(base + o_merges);
+  if (lazy) {
+    for (int s = 0; s < kNumBlockSizes; ++s) {
+      d.kblk[s] = reinterpret_cast<KeyBlock*>(base + o_kblk[s]);
+      d.kblk_first[s] = reinterpret_cast<int32_t*>(base + o_first[s]);
+      d.voff_ctx[s] = reinterpret_cast<uint32_t*>(base + o_vctx[s]);
+      d.voff_ref[s] = reinterpret_cast<uint32_t*>(base + o_vref[s]);
+      d.lazy_tiles[s] = reinterpret_cast<AttnTile*>(base + o_ltiles[s]);
+    }
+  }
   d.block = base;
   d.device = ctx->device;
   p->dev = d;
@@ -112,6 +149,40 @@ int upload_plan(mpic_ctx* ctx, mpic_plan* p) {
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+// lazy_rope contexts: what the kernels need to walk the plan's key blocks of `bn` keys.  With
+// `refs` the stored rows are read in place in the chunk caches (validated here), else in the
+// context buffers, where mpic_assemble_kv copied them unrotated.
+int fill_lazy_refs(mpic_ctx* ctx, const mpic_plan* plan, int bn, const SrcRefs* refs, const char* who, LazyRefs* out) {
+  const int s = block_size_index(bn);
+  LazyRefs r{};
+  r.blocks = plan->dev.kblk[s];
+  r.first = plan->dev.kblk_first[s];
+  r.voff = refs ? plan->dev.voff_ref[s] : plan->dev.voff_ctx[s];
+  r.rope_cos = plan->dev.rope_cos;
+  r.rope_sin = plan->dev.rope_sin;
+  r.by_ref = refs ? 1 : 0;
+  if (refs) {
+    const size_t n_inst = plan->inst_src.size();
+    if (n_inst > static_cast<size_t>(kMaxInstPerLaunch))
+      return fail(ctx, MPIC_ERR_UNSUPPORTED, std::string(who) + ": more than 128 chunk instances cannot be read in place");
+    if (n_inst > 0 && (!refs->srcs || refs->n_srcs <= plan->max_src))
+      return fail(ctx, MPIC_ERR_INVALID, std::string(who) + ": srcs does not cover every chunk index of the plan");
+    for (size_t i = 0; i < n_inst; ++i) {
+      const mpic_chunk_src& sc = refs->srcs[plan->inst_src[i]];
+      if (sc.len != plan->inst_len[i]) return fail(ctx, MPIC_ERR_INVALID, std::string(who) + ": chunk source length differs from its segment");
+      if (plan->inst_cached[i] > 0) {
+        if (sc.on_host != MPIC_SRC_DEVICE) return fail(ctx, MPIC_ERR_INVALID, std::string(who) + ": a cache that is read in place must be in device memory");
+        if (!sc.k || !sc.v || !aligned16(sc.k) || !aligned16(sc.v))
+          return fail(ctx, MPIC_ERR_INVALID, std::string(who) + ": chunk source pointer missing or not 16-byte aligned");
+      }
+      r.k[i] = sc.k;
+      r.v[i] = sc.v;
+    }
+  }
+  *out = r;
+  return MPIC_OK;
+}
 
 }  // namespace
 }  // namespace mpic
@@ -284,8 +355,9 @@ int mpic::assemble_parts(mpic_ctx* ctx, mpic_plan* plan, const mpic_chunk_src* s
   a.src_inst = plan->dev.src_inst;
   a.src_row = plan->dev.src_row;
   a.dst_slot = plan->dev.dst_slot;
-  a.rope_cos = plan->dev.rope_cos;
-  a.rope_sin = plan->dev.rope_sin;
+  // (lazy_rope: stored keys are copied as stored, the shift is applied on the query side)
+  a.rope_cos = ctx->cfg.lazy_rope ? nullptr : plan->dev.rope_cos;
+  a.rope_sin = ctx->cfg.lazy_rope ? nullptr : plan->dev.rope_sin;
   a.fresh_rot = plan->dev.fresh_rot;
   a.fresh_cos = plan->dev.fresh_cos;
   a.fresh_sin = plan->dev.fresh_sin;
@@ -390,8 +462,10 @@ int mpic::assemble_parts(mpic_ctx* ctx, mpic_plan* plan, const mpic_chunk_src* s
 int mpic::attend(mpic_ctx* ctx, mpic_plan* plan, const void* fresh_q,
                                int64_t n_fresh_rows, const void* k_ctx, const void* v_ctx,
                                int64_t n_ctx_slots, double softmax_scale, void* out, float* lse,
-                               void* stream_, const mpic::NextLink* next, int32_t block_keys) {
+                               void* stream_, const mpic::NextLink* next, int32_t block_keys, const mpic::SrcRefs* refs) {
   if (!ctx) return MPIC_ERR_INVALID;
+  const bool lazy = ctx->cfg.lazy_rope != 0;
+  if (refs && !lazy) return fail(ctx, MPIC_ERR_INVALID, "selective_attn_in_place: the context was not created with lazy_rope");
   if (!plan || plan->ctx != ctx) return fail(ctx, MPIC_ERR_INVALID, "selective_attn: plan does not belong to this context");
   if (n_fresh_rows != plan->n_q) return fail(ctx, MPIC_ERR_INVALID, "selective_attn: n_fresh_rows differs from the plan's recompute set");
   if (!(softmax_scale > 0.0) || !std::isfinite(softmax_scale)) return fail(ctx, MPIC_ERR_INVALID, "selective_attn: softmax_scale must be finite and positive");
@@ -421,7 +495,7 @@ int mpic::attend(mpic_ctx* ctx, mpic_plan* plan, const void* fresh_q,
       return fail(ctx, MPIC_ERR_INVALID, "selective_attn: the next layer's context must not overlap the one being read");
     if (n_inst > 0 && (!next->srcs || next->n_srcs <= plan->max_src))
       return fail(ctx, MPIC_ERR_INVALID, "selective_attn: next layer's srcs does not cover every chunk index of the plan");
-    fuse_next = mpic::can_link_in_attention(ctx, plan);
+    fuse_next = mpic::can_link_in_attention(ctx, plan) && !lazy;  // (the lazy kernel carries no linking)
     for (size_t i = 0; i < n_inst; ++i) {
       const mpic_chunk_src& sc = next->srcs[plan->inst_src[i]];
       if (sc.len != plan->inst_len[i]) return fail(ctx, MPIC_ERR_INVALID, "selective_attn: next layer's chunk source length differs from its segment");
@@ -482,6 +556,25 @@ int mpic::attend(mpic_ctx* ctx, mpic_plan* plan, const void* fresh_q,
   a.q_sin = plan->dev.fresh_sin;
   a.interleaved = c.rope_interleaved;
   hipStream_t stream = static_cast<hipStream_t>(stream_);
+  if (lazy) {
+    mpic::LazyRefs lr;
+    rc = mpic::fill_lazy_refs(ctx, plan, c.dtype == MPIC_F32 ? 32 : a.block_keys, refs, "selective_attn", &lr);
+    if (rc != MPIC_OK) return rc;
+    if (c.dtype == MPIC_F32) {
+      a.src_inst = plan->dev.src_inst;
+      a.src_row = plan->dev.src_row;
+      a.rope_cos = plan->dev.rope_cos;
+      a.rope_sin = plan->dev.rope_sin;
+      MPIC_HIP(ctx, mpic::launch_attn_f32(a, plan->n_q, &lr, stream));
+    } else {
+      a.tiles = plan->dev.lazy_tiles[mpic::block_size_index(a.block_keys)];
+      MPIC_HIP(ctx, mpic::launch_attn_bf16(a, nullptr, nullptr, &lr, stream));
+    }
+    if (next)
+      return mpic::assemble_parts(ctx, plan, next->srcs, next->n_srcs, nullptr, nullptr, 0, next->k_ctx, next->v_ctx,
+                                  n_ctx_slots, MPIC_PART_CACHED, stream_);
+    return MPIC_OK;
+  }
   if (fuse_next) {
     mpic::AssembleArgs la{};
     la.src_inst = plan->dev.src_inst;
@@ -504,13 +597,13 @@ int mpic::attend(mpic_ctx* ctx, mpic_plan* plan, const void* fresh_q,
       tab.k[i] = next->srcs[plan->inst_src[i]].k;
       tab.v[i] = next->srcs[plan->inst_src[i]].v;
     }
-    MPIC_HIP(ctx, mpic::launch_attn_bf16(a, &la, &tab, stream));
+    MPIC_HIP(ctx, mpic::launch_attn_bf16(a, &la, &tab, nullptr, stream));
     return MPIC_OK;
   }
   if (c.dtype == MPIC_F32) {
-    MPIC_HIP(ctx, mpic::launch_attn_f32(a, plan->n_q, stream));
+    MPIC_HIP(ctx, mpic::launch_attn_f32(a, plan->n_q, nullptr, stream));
   } else {
-    MPIC_HIP(ctx, mpic::launch_attn_bf16(a, nullptr, nullptr, stream));
+    MPIC_HIP(ctx, mpic::launch_attn_bf16(a, nullptr, nullptr, nullptr, stream));
   }
   if (next)  // same result, one launch more
     return mpic::assemble_parts(ctx, plan, next->srcs, next->n_srcs, nullptr, nullptr, 0, next->k_ctx, next->v_ctx,
@@ -524,8 +617,10 @@ int mpic::attend(mpic_ctx* ctx, mpic_plan* plan, const void* fresh_q,
 static int decode_attn_impl(mpic_ctx* ctx, mpic_plan* plan, const void* q, const void* new_k,
                             const void* new_v, const void* k_ctx, const void* v_ctx,
                             int64_t n_ctx_slots, double softmax_scale, void* out, float* lse,
-                            void* stream_, bool static_scratch) {
+                            void* stream_, bool static_scratch, const mpic::SrcRefs* refs = nullptr) {
   if (!ctx) return MPIC_ERR_INVALID;
+  const bool lazy = ctx->cfg.lazy_rope != 0;
+  if (refs && !lazy) return fail(ctx, MPIC_ERR_INVALID, "decode_attn_in_place: the context was not created with lazy_rope");
   if (!plan || plan->ctx != ctx) return fail(ctx, MPIC_ERR_INVALID, "decode_attn: plan does not belong to this context");
   if (!(softmax_scale > 0.0) || !std::isfinite(softmax_scale)) return fail(ctx, MPIC_ERR_INVALID, "decode_attn: softmax_scale must be finite and positive");
   if (!q || !out) return fail(ctx, MPIC_ERR_INVALID, "decode_attn: null buffer");
@@ -552,8 +647,12 @@ static int decode_attn_impl(mpic_ctx* ctx, mpic_plan* plan, const void* q, const
   }
   const mpic_config& c = ctx->cfg;
   hipStream_t stream = static_cast<hipStream_t>(stream_);
+  // longest context of the batch; lazy_rope (bf16): in slots of the requests' 32-key blocks
+  const bool by_blocks = lazy && c.dtype == MPIC_BF16;
   int32_t max_ctx = 0;
-  for (int b = 0; b < plan->n_requests; ++b) max_ctx = std::max(max_ctx, plan->ctx_off[b + 1] - plan->ctx_off[b]);
+  for (int b = 0; b < plan->n_requests; ++b)
+    max_ctx = std::max(max_ctx, by_blocks ? (plan->kblk_first[0][b + 1] - plan->kblk_first[0][b]) * 32
+                                          : plan->ctx_off[b + 1] - plan->ctx_off[b]);
   // Splits: a workgroup fills a compute unit's LDS, so the keys are cut so that one round of
   // workgroups covers the chip (fewer when the batch alone supplies that many); each split
   // is a multiple of 128 keys.
@@ -610,7 +709,20 @@ static int decode_attn_impl(mpic_ctx* ctx, mpic_plan* plan, const void* q, const
   a.n_splits = n_splits;
   a.keys_per_split = keys_per_split;
   a.max_ctx = max_ctx;
-  MPIC_HIP(ctx, mpic::launch_decode(c.dtype, a, stream));
+  if (lazy) {
+    mpic::LazyRefs lr;
+    rc = mpic::fill_lazy_refs(ctx, plan, 32, refs, "decode_attn", &lr);
+    if (rc != MPIC_OK) return rc;
+    a.interleaved = c.rope_interleaved;
+    a.blk_first = by_blocks ? plan->dev.kblk_first[0] : nullptr;
+    a.src_inst = plan->dev.src_inst;
+    a.src_row = plan->dev.src_row;
+    a.rope_cos = plan->dev.rope_cos;
+    a.rope_sin = plan->dev.rope_sin;
+    MPIC_HIP(ctx, mpic::launch_decode(c.dtype, a, &lr, stream));
+    return MPIC_OK;
+  }
+  MPIC_HIP(ctx, mpic::launch_decode(c.dtype, a, nullptr, stream));
   return MPIC_OK;
 }
 
@@ -637,6 +749,15 @@ extern "C" int mpic_selective_attn(mpic_ctx* ctx, mpic_plan* plan, const void* f
                                    void* stream) {
   MPIC_GUARDED(ctx, mpic::attend(ctx, plan, fresh_q, n_fresh_rows, k_ctx, v_ctx, n_ctx_slots, softmax_scale,
                                         out, lse, stream, nullptr))
+}
+
+extern "C" int mpic_selective_attn_in_place(mpic_ctx* ctx, mpic_plan* plan, const void* fresh_q,
+                                            int64_t n_fresh_rows, const mpic_chunk_src* srcs, int32_t n_srcs,
+                                            const void* k_ctx, const void* v_ctx, int64_t n_ctx_slots,
+                                            double softmax_scale, void* out, float* lse, void* stream) {
+  const mpic::SrcRefs refs{srcs, n_srcs};
+  MPIC_GUARDED(ctx, mpic::attend(ctx, plan, fresh_q, n_fresh_rows, k_ctx, v_ctx, n_ctx_slots, softmax_scale,
+                                 out, lse, stream, nullptr, 0, &refs))
 }
 
 extern "C" int mpic_set_option(mpic_ctx* ctx, int32_t option, int64_t value) {
@@ -667,6 +788,15 @@ extern "C" int mpic_decode_attn(mpic_ctx* ctx, mpic_plan* plan, const void* q, c
                                 void* stream) {
   MPIC_GUARDED(ctx, decode_attn_impl(ctx, plan, q, new_k, new_v, k_ctx, v_ctx, n_ctx_slots, softmax_scale, out, lse,
                                      stream, false))
+}
+
+extern "C" int mpic_decode_attn_in_place(mpic_ctx* ctx, mpic_plan* plan, const void* q, const void* new_k,
+                                         const void* new_v, const mpic_chunk_src* srcs, int32_t n_srcs,
+                                         const void* k_ctx, const void* v_ctx, int64_t n_ctx_slots,
+                                         double softmax_scale, void* out, float* lse, void* stream) {
+  const mpic::SrcRefs refs{srcs, n_srcs};
+  MPIC_GUARDED(ctx, decode_attn_impl(ctx, plan, q, new_k, new_v, k_ctx, v_ctx, n_ctx_slots, softmax_scale, out, lse,
+                                     stream, false, &refs))
 }
 
 extern "C" int mpic_decode_attn_static(mpic_ctx* ctx, mpic_plan* plan, const void* q, const void* new_k,

@@ -87,6 +87,8 @@ struct LinkNext {
   int32_t n_wgs;  // workgroups after the attention tiles
 };
 
+typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+
 __device__ inline void link_share(const LinkNext& ln, int j) {
   const link::Shape sh = link::shape_of<__bf16>(ln.args);
   // workgroup j links rows [lo, hi) of the range; a thread keeps its unit pair and walks down
@@ -146,13 +148,20 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
   const int col = lane & 31;  // query column owned by this lane
   const int hi = lane >> 5;   // which half of the contraction index this lane feeds
   const int group = a.n_q_heads / a.n_kv_heads;
+  constexpr bool kLazy = std::is_same<Extra, LazyRefs>::value;
   const int b = tile.req, g = tile.kv_head;
-  const int key0 = tile.key0;              // pieces of a tile cut along the keys start here;
+  const int key0 = kLazy ? 0 : tile.key0;  // pieces of a tile cut along the keys start here;
   const int n_keys = tile.n_keys - key0;   // from here on keys and positions are relative to it
   // context row offsets in 16-byte units; read with scalar loads (the table is padded so
   // that reading up to 64 entries past the last key of the tile stays in bounds)
-  const __attribute__((address_space(4))) uint32_t* off_of =
-      (const __attribute__((address_space(4))) uint32_t*)(a.kv_off16 + a.ctx_off[b] + key0);
+  const __attribute__((address_space(4))) uint32_t* off_of;
+  int vb0 = 0;  // lazy: this tile's first key block in the batch's list (its tile counts in blocks)
+  if constexpr (kLazy) {
+    vb0 = extra.first[b] + tile.key0;
+    off_of = (const __attribute__((address_space(4))) uint32_t*)(extra.voff + static_cast<int64_t>(vb0) * BN);
+  } else {
+    off_of = (const __attribute__((address_space(4))) uint32_t*)(a.kv_off16 + a.ctx_off[b] + key0);
+  }
   const char* kbase = static_cast<const char*>(a.k_ctx) + g * ROW_BYTES;
   const char* vbase = static_cast<const char*>(a.v_ctx) + g * ROW_BYTES;
   const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(MPIC_LDS_PTR(char, lds)));
@@ -166,42 +175,142 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
   // Last key of this tile (or piece) the row may see.  Padding columns see every key; a row
   // below key0 (negative here) sees none of this piece; a row beyond the end of a piece sees the
   // piece up to its last key (blocks need not end where pieces do).
-  const int my_pos = min(valid ? a.q_pos[fresh_row] - key0 : 0x7fffffff, n_keys - 1);
+  // (lazy: positions stay absolute, the blocks carry theirs; a piece owns whole blocks)
+  const int my_pos = kLazy ? (valid ? a.q_pos[fresh_row] : 0x3fffffff)
+                           : min(valid ? a.q_pos[fresh_row] - key0 : 0x7fffffff, n_keys - 1);
+  const int n_iter = kLazy ? tile.n_keys - tile.key0 : (n_keys + BN - 1) / BN;
+  // descriptor of key block blk of this tile (lazy only; a scalar load)
+  auto desc_of = [&](int blk) __attribute__((always_inline)) {
+    blk = blk < n_iter ? blk : n_iter - 1;
+    KeyBlock d{};
+    if constexpr (kLazy) {
+      const i32x4 raw = *(const __attribute__((address_space(4))) i32x4*)(extra.blocks + vb0 + blk);
+      d.pos0 = raw[0];
+      d.n_valid = raw[1];
+      d.inst = raw[2];
+    }
+    return d;
+  };
+  // does the row see any key of this tile (or piece)?
+  const int piece_pos0 = kLazy ? desc_of(0).pos0 : 0;
+  auto sees = [&]() { return my_pos >= piece_pos0; };
   const __bf16* qp = static_cast<const __bf16*>(a.q) + (fresh_row * a.n_q_heads + head) * D;
   bf16x8 qf[8];
+  // (Re)load this lane's query fragments.  Queries that arrive without positions are turned by
+  // their position id, in fp32; with lazy_rope the query is also turned *back* by the shift of
+  // the chunk instance whose keys come next (inst >= 0); one rounding after both.  This lane
+  // holds coordinates d = 16*ks + 8*hi + e: a rotate-half pair (d, d + 64) is (qf[ks],
+  // qf[ks + 4]) element by element, an interleaved pair (2i, 2i + 1) is two neighbouring
+  // elements of one fragment.
+  auto load_q = [&](int inst) __attribute__((always_inline)) {
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16 + hi * 8);
-  if (a.q_rot) {
-    // Queries that arrive without positions are turned by their position id here, in fp32,
-    // and rounded once.  This lane holds coordinates d = 16*ks + 8*hi + e: a rotate-half
-    // pair (d, d + 64) is (qf[ks], qf[ks + 4]) element by element, an interleaved pair
-    // (2i, 2i + 1) is two neighbouring elements of one fragment.
-    const int64_t u = a.q_rot[fresh_row];
-    const float* ct = a.q_cos + u * (D / 2);
-    const float* st = a.q_sin + u * (D / 2);
+    for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16 + hi * 8);
+    const bool fwd = a.q_rot != nullptr;
+    const bool back = kLazy && inst >= 0;
+    if (!fwd && !back) return;
+    const float* ct = nullptr;
+    const float* st = nullptr;
+    const float* cb = nullptr;
+    const float* sb = nullptr;
+    if (fwd) {
+      const int64_t u = a.q_rot[fresh_row];
+      ct = a.q_cos + u * (D / 2);
+      st = a.q_sin + u * (D / 2);
+    }
+    if constexpr (kLazy) {
+      if (back) {
+        cb = extra.rope_cos + static_cast<int64_t>(inst) * (D / 2);
+        sb = extra.rope_sin + static_cast<int64_t>(inst) * (D / 2);
+      }
+    }
     if (a.interleaved) {
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
-        const f32x4 c = *reinterpret_cast<const f32x4*>(ct + ks * 8 + hi * 4);
-        const f32x4 s = *reinterpret_cast<const f32x4*>(st + ks * 8 + hi * 4);
-        const f32x8 x = __builtin_convertvector(qf[ks], f32x8);
-        f32x8 y;
+        f32x8 x = __builtin_convertvector(qf[ks], f32x8);
+        if (fwd) {
+          const f32x4 c = *reinterpret_cast<const f32x4*>(ct + ks * 8 + hi * 4);
+          const f32x4 s = *reinterpret_cast<const f32x4*>(st + ks * 8 + hi * 4);
+          f32x8 y;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          y[2 * i] = x[2 * i] * c[i] - x[2 * i + 1] * s[i];
-          y[2 * i + 1] = x[2 * i] * s[i] + x[2 * i + 1] * c[i];
+          for (int i = 0; i < 4; ++i) {
+            y[2 * i] = x[2 * i] * c[i] - x[2 * i + 1] * s[i];
+            y[2 * i + 1] = x[2 * i] * s[i] + x[2 * i + 1] * c[i];
+          }
+          x = y;
         }
-        qf[ks] = __builtin_convertvector(y, bf16x8);
+        if (back) {
+          const f32x4 c = *reinterpret_cast<const f32x4*>(cb + ks * 8 + hi * 4);
+          const f32x4 s = *reinterpret_cast<const f32x4*>(sb + ks * 8 + hi * 4);
+          f32x8 y;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            y[2 * i] = x[2 * i] * c[i] + x[2 * i + 1] * s[i];
+            y[2 * i + 1] = x[2 * i + 1] * c[i] - x[2 * i] * s[i];
+          }
+          x = y;
+        }
+        qf[ks] = __builtin_convertvector(x, bf16x8);
+        __builtin_amdgcn_sched_barrier(0);
       }
     } else {
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
-        const f32x8 c = *reinterpret_cast<const f32x8*>(ct + ks * 16 + hi * 8);
-        const f32x8 s = *reinterpret_cast<const f32x8*>(st + ks * 16 + hi * 8);
-        const f32x8 x0 = __builtin_convertvector(qf[ks], f32x8);
-        const f32x8 x1 = __builtin_convertvector(qf[ks + 4], f32x8);
-        qf[ks] = __builtin_convertvector(x0 * c - x1 * s, bf16x8);
-        qf[ks + 4] = __builtin_convertvector(x0 * s + x1 * c, bf16x8);
+        f32x8 x0 = __builtin_convertvector(qf[ks], f32x8);
+        f32x8 x1 = __builtin_convertvector(qf[ks + 4], f32x8);
+        if (fwd) {
+          const f32x8 c = *reinterpret_cast<const f32x8*>(ct + ks * 16 + hi * 8);
+          const f32x8 s = *reinterpret_cast<const f32x8*>(st + ks * 16 + hi * 8);
+          const f32x8 y0 = x0 * c - x1 * s, y1 = x0 * s + x1 * c;
+          x0 = y0;
+          x1 = y1;
+        }
+        if (back) {
+          const f32x8 c = *reinterpret_cast<const f32x8*>(cb + ks * 16 + hi * 8);
+          const f32x8 s = *reinterpret_cast<const f32x8*>(sb + ks * 16 + hi * 8);
+          const f32x8 y0 = x0 * c + x1 * s, y1 = x1 * c - x0 * s;
+          x0 = y0;
+          x1 = y1;
+        }
+        qf[ks] = __builtin_convertvector(x0, bf16x8);
+        qf[ks + 4] = __builtin_convertvector(x1, bf16x8);
+        __builtin_amdgcn_sched_barrier(0);  // one pair of fragments at a time: few registers in flight
+      }
+    }
+  };
+  int q_inst = kLazy ? desc_of(0).inst : -1;  // the instance whose shift qf is turned back by
+  if constexpr (kLazy) {
+    load_q(q_inst);
+  } else {
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16 + hi * 8);
+    if (a.q_rot) {
+      const int64_t u = a.q_rot[fresh_row];
+      const float* ct = a.q_cos + u * (D / 2);
+      const float* st = a.q_sin + u * (D / 2);
+      if (a.interleaved) {
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+          const f32x4 c = *reinterpret_cast<const f32x4*>(ct + ks * 8 + hi * 4);
+          const f32x4 s = *reinterpret_cast<const f32x4*>(st + ks * 8 + hi * 4);
+          const f32x8 x = __builtin_convertvector(qf[ks], f32x8);
+          f32x8 y;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            y[2 * i] = x[2 * i] * c[i] - x[2 * i + 1] * s[i];
+            y[2 * i + 1] = x[2 * i] * s[i] + x[2 * i + 1] * c[i];
+          }
+          qf[ks] = __builtin_convertvector(y, bf16x8);
+        }
+      } else {
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+          const f32x8 c = *reinterpret_cast<const f32x8*>(ct + ks * 16 + hi * 8);
+          const f32x8 s = *reinterpret_cast<const f32x8*>(st + ks * 16 + hi * 8);
+          const f32x8 x0 = __builtin_convertvector(qf[ks], f32x8);
+          const f32x8 x1 = __builtin_convertvector(qf[ks + 4], f32x8);
+          qf[ks] = __builtin_convertvector(x0 * c - x1 * s, bf16x8);
+          qf[ks + 4] = __builtin_convertvector(x0 * s + x1 * c, bf16x8);
+        }
       }
     }
   }
@@ -223,11 +332,12 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
   const uint32_t ld_v16 = ld_col ^ (ld_sub << 2);               //          V swizzle = (row & 3) << 2
   const uint32_t sel0 = ld_sub == 0 ? ~0u : 0u, sel1 = ld_sub == 1 ? ~0u : 0u;
   const uint32_t sel2 = ld_sub == 2 ? ~0u : 0u, sel3 = ld_sub == 3 ? ~0u : 0u;
-  const int n_iter = (n_keys + BN - 1) / BN;
   // BN / 8 rows per wave and block: kLoadPairs loads of four rows for K and as many for V
   constexpr int kLoadPairs = ROWS_LOADED_PER_WAVE / 4;
   struct RowOffs {
     u32x4_a4 q[kLoadPairs];
+    const char* kb;  // lazy: where the block's rows are stored (context or the chunk's cache)
+    const char* vb;
   };
   auto fetch_rows = [&](int blk) {
     blk = blk < n_iter ? blk : n_iter - 1;
@@ -236,6 +346,12 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
     RowOffs r;
 #pragma unroll
     for (int p = 0; p < kLoadPairs; ++p) r.q[p] = src[p];
+    if constexpr (kLazy) {
+      const int inst = desc_of(blk).inst;
+      const bool in_ctx = inst < 0 || !extra.by_ref;
+      r.kb = (in_ctx ? static_cast<const char*>(a.k_ctx) : static_cast<const char*>(extra.k[inst])) + g * ROW_BYTES;
+      r.vb = (in_ctx ? static_cast<const char*>(a.v_ctx) : static_cast<const char*>(extra.v[inst])) + g * ROW_BYTES;
+    }
     return r;
   };
   // `ro` holds the offsets of the block whose loads go out next.  It is refilled at the start
@@ -252,12 +368,18 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
     const uint32_t dv = lds_base + v_slot_off(blk) + row0 * ROW_BYTES;
     const void* gk[kLoadPairs];
     const void* gv[kLoadPairs];
+    const char* kb = kbase;
+    const char* vb = vbase;
+    if constexpr (kLazy) {
+      kb = cur.kb;
+      vb = cur.vb;
+    }
 #pragma unroll
     for (int p = 0; p < kLoadPairs; ++p) {
       const uint32_t r = (cur.q[p][0] & sel0) | (cur.q[p][1] & sel1) | (cur.q[p][2] & sel2) | (cur.q[p][3] & sel3);
       const uint32_t kx = ld_col ^ ((row0 + 4 * p + ld_sub) & 15);  // K swizzle = row & 15
-      gk[p] = kbase + (static_cast<uint64_t>(r + kx) << 4);
-      gv[p] = vbase + (static_cast<uint64_t>(r + ld_v16) << 4);
+      gk[p] = kb + (static_cast<uint64_t>(r + kx) << 4);
+      gv[p] = vb + (static_cast<uint64_t>(r + ld_v16) << 4);
     }
     if constexpr (kLoadPairs == 3) {
       load6_to_lds_16B(gk[0], gv[0], gk[1], gv[1], gk[2], gv[2], dk, dv, dk + 4 * ROW_BYTES, dv + 4 * ROW_BYTES,
@@ -365,7 +487,22 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
   };
 
   // softmax of block t: S^T (acc_s) -> P^T (pf), running sum and reference maximum
+  KeyBlock kd{};  // lazy: descriptor of the block softmax_block works on
   auto softmax_block = [&](int t) {
+    if constexpr (kLazy) {
+      // keys of the block sit at positions pos0 .. pos0 + n_valid - 1; slots behind them are
+      // padding; masked on blocks with padding and on the diagonal blocks
+      if (kd.n_valid < BN || kd.pos0 + BN - 1 > wave_lo_pos) {
+        const int bound = min(my_pos - kd.pos0, kd.n_valid - 1) - hi * 4;  // last visible slot (may be negative)
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int slot = kb * 32 + (v >> 2) * 8 + (v & 3);
+            acc_s[kb][v] = slot <= bound ? acc_s[kb][v] : -INFINITY;
+          }
+      }
+    } else {
     const int j0 = t * BN;
     // causal mask by position, on the diagonal blocks only
     if (j0 + BN - 1 > wave_lo_pos) {
@@ -377,6 +514,7 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
           acc_s[kb][v] = key <= my_pos ? acc_s[kb][v] : -INFINITY;
         }
     }
+    }
     // Lazy rescale without a block maximum.  The probabilities are first computed against the
     // current reference point m_run.  All of them are positive, so if this lane's share of the
     // row sum stays below kSumLimit no single one exceeded it, and the reference point may stay:
@@ -386,7 +524,7 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
     // redone the careful way: block maximum, new reference point, accumulators rescaled.  After
     // the first blocks of a row that is rare, and the fast path saves the maximum over the block
     // (a seventh of the vector instructions of the phase the barriers wait for: +2.1 %).
-    bool careful = m_run == -INFINITY && my_pos >= 0;  // (rows below a piece never see a key: left alone)
+    bool careful = m_run == -INFINITY && sees();  // (rows below a piece never see a key: left alone)
     float l_blk = 0.f;
     if (__builtin_amdgcn_ballot_w64(careful) == 0) {
       const float m_scaled0 = m_run * scale_log2;
@@ -402,7 +540,7 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
           }
           pf[kb * 2 + half] = __builtin_convertvector(p, bf16x8);
         }
-      careful = my_pos >= 0 && !(l_blk <= kSumLimit);  // (also true for NaN)
+      careful = sees() && !(l_blk <= kSumLimit);  // (also true for NaN)
     }
     if (__builtin_amdgcn_ballot_w64(careful) != 0) {
       float m_blk = -INFINITY;
@@ -449,34 +587,91 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
     __syncthreads();
     if (t + AHEAD < n_iter) issue_loads(t + AHEAD);
   };
-  // matrix half step of block t: finish block t-1, start block t (blocks past the last key
-  // this wave can see are skipped; the barriers stay aligned)
-  auto matrix_part = [&](int t) {
-    const bool do_pv = t >= 1 && (t - 1) * BN <= wave_hi_pos;
+  // matrix half step of block t: finish block t-1 (if this wave needed it), start block t (if it
+  // needs it: blocks past the last key the wave can see are skipped; the barriers stay aligned)
+  auto matrix_part = [&](int t, bool do_qk, bool do_pv, int inst) __attribute__((always_inline)) {
     __builtin_amdgcn_s_setprio(1);  // the wave that feeds the matrix core is issued first
-    if (t < n_iter && t * BN <= wave_hi_pos) {
+    if (do_qk) {
       if (do_pv) pv_block(t - 1);
+      if constexpr (kLazy) {
+        if (inst != q_inst) {  // the keys of this block lack another shift than the last one's
+          __builtin_amdgcn_sched_barrier(0);  // (keeps the reload out of the matrix parts around it)
+          load_q(inst);
+          q_inst = inst;
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
       qk_block(t);
     } else if (do_pv) {
       pv_block(t - 1);
     }
     __builtin_amdgcn_s_setprio(0);
   };
-  if (gp == 0) {
-    for (int t = 0; t <= n_iter; ++t) {
-      even_sync(t);
-      matrix_part(t);
-      __syncthreads();  // odd half step 2t+1
-      ro = fetch_rows(t + AHEAD + 1);
-      if (t < n_iter && t * BN <= wave_hi_pos) softmax_block(t);
+  if constexpr (kLazy) {
+    // the same two loops over the tile's key blocks: a block is needed while its first position
+    // is within the wave's reach; its descriptor is fetched one step ahead, at the start of the
+    // softmax phase like the row offsets
+    KeyBlock cur = desc_of(0);
+    bool prev_needed = false;
+    if (gp == 0) {
+      for (int t = 0; t <= n_iter; ++t) {
+        const bool needed = t < n_iter && cur.pos0 <= wave_hi_pos;
+        even_sync(t);
+        matrix_part(t, needed, prev_needed, cur.inst);
+        __syncthreads();  // odd half step 2t+1
+        ro = fetch_rows(t + AHEAD + 1);
+        const KeyBlock nxt = desc_of(t + 1);
+        if (needed) {
+          kd = cur;
+          softmax_block(t);
+        }
+        prev_needed = needed;
+        cur = nxt;
+      }
+    } else {
+      for (int t = 0; t <= n_iter; ++t) {
+        even_sync(t);
+        ro = fetch_rows(t + AHEAD + 1);
+        const KeyBlock nxt = desc_of(t);
+        if (prev_needed) {
+          kd = cur;
+          softmax_block(t - 1);
+        }
+        __syncthreads();  // odd half step 2t+1
+        cur = nxt;
+        const bool needed = t < n_iter && cur.pos0 <= wave_hi_pos;
+        matrix_part(t, needed, prev_needed, cur.inst);
+        prev_needed = needed;
+      }
     }
   } else {
-    for (int t = 0; t <= n_iter; ++t) {
-      even_sync(t);
-      ro = fetch_rows(t + AHEAD + 1);
-      if (t >= 1 && (t - 1) * BN <= wave_hi_pos) softmax_block(t - 1);
-      __syncthreads();  // odd half step 2t+1
-      matrix_part(t);
+    auto matrix_old = [&](int t) {
+      const bool do_pv = t >= 1 && (t - 1) * BN <= wave_hi_pos;
+      __builtin_amdgcn_s_setprio(1);
+      if (t < n_iter && t * BN <= wave_hi_pos) {
+        if (do_pv) pv_block(t - 1);
+        qk_block(t);
+      } else if (do_pv) {
+        pv_block(t - 1);
+      }
+      __builtin_amdgcn_s_setprio(0);
+    };
+    if (gp == 0) {
+      for (int t = 0; t <= n_iter; ++t) {
+        even_sync(t);
+        matrix_old(t);
+        __syncthreads();  // odd half step 2t+1
+        ro = fetch_rows(t + AHEAD + 1);
+        if (t < n_iter && t * BN <= wave_hi_pos) softmax_block(t);
+      }
+    } else {
+      for (int t = 0; t <= n_iter; ++t) {
+        even_sync(t);
+        ro = fetch_rows(t + AHEAD + 1);
+        if (t >= 1 && (t - 1) * BN <= wave_hi_pos) softmax_block(t - 1);
+        __syncthreads();  // odd half step 2t+1
+        matrix_old(t);
+      }
     }
   }
 
@@ -487,7 +682,7 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
     // piece of a tile cut along the keys: normalised fp32 partial + log-sum-exp for the merge
     // kernel.  A row that lies below key0 saw no key (its registers may hold NaN: selected
     // away, never multiplied).
-    const bool seen = my_pos >= 0;
+    const bool seen = sees();
     const float inv_p = seen ? 1.f / l_tot : 0.f;
     const int64_t slot = static_cast<int64_t>(tile.part) * kAttnTileRows + local;
     float* po = a.ws_o + slot * D;
@@ -567,18 +762,26 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
 namespace {
 
 template <int kBlockKeys>
-hipError_t launch_shape(const AttnArgs& a, const AssembleArgs* next, const AssembleSrcTable* next_tab, int dev,
-                        hipStream_t stream) {
+hipError_t launch_shape(const AttnArgs& a, const AssembleArgs* next, const AssembleSrcTable* next_tab,
+                        const LazyRefs* lazy, int dev, hipStream_t stream) {
   using G = Geo<kBlockKeys>;
   static LdsOptIn opt_in;  // one per kernel shape
   const hipError_t eo = opt_in.ensure(dev, [] {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bf16_kernel<kBlockKeys, NoLink>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES);
     if (e != hipSuccess) return e;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bf16_kernel<kBlockKeys, LinkNext>),
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bf16_kernel<kBlockKeys, LinkNext>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bf16_kernel<kBlockKeys, LazyRefs>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES);
   });
   if (eo != hipSuccess) return eo;
+  if (lazy) {
+    hipLaunchKernelGGL((attn_bf16_kernel<kBlockKeys, LazyRefs>), dim3(a.n_tiles), dim3(THREADS), G::LDS_BYTES, stream, a,
+                       *lazy);
+    return hipSuccess;
+  }
   const int64_t n_pos = next ? next->pos_end - next->pos_begin : 0;
   if (n_pos > 0) {
     LinkNext ln;
@@ -601,12 +804,13 @@ hipError_t launch_shape(const AttnArgs& a, const AssembleArgs* next, const Assem
 }  // namespace
 
 hipError_t launch_attn_bf16(const AttnArgs& a, const AssembleArgs* next, const AssembleSrcTable* next_tab,
-                            hipStream_t stream) {
+                            const LazyRefs* lazy, hipStream_t stream) {
   if (a.n_tiles <= 0) return hipSuccess;
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
-  e = a.block_keys == 96 ? launch_shape<96>(a, next, next_tab, dev, stream) : launch_shape<64>(a, next, next_tab, dev, stream);
+  e = a.block_keys == 96 ? launch_shape<96>(a, next, next_tab, lazy, dev, stream)
+                         : launch_shape<64>(a, next, next_tab, lazy, dev, stream);
   if (e != hipSuccess) return e;
   if (a.n_merges > 0)
     hipLaunchKernelGGL(attn_merge_kernel, dim3(a.n_merges, kAttnTileRows / 8), dim3(256), 0, stream, a);

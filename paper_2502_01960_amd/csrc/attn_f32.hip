@@ -12,8 +12,12 @@
 namespace mpic {
 namespace {
 
-template <int D>
-__global__ __launch_bounds__(256) void attn_f32_kernel(AttnArgs a, int64_t n_q) {
+// kLazy (lazy_rope contexts): a stored key still lacks its position shift; it is turned to its
+// global position as it is read (the pair (x, y) of the key becomes (x cos - y sin, x sin + y cos)
+// inside the dot product), in fp32, and never written back.  With refs.by_ref the stored rows
+// are read in their caches instead of the context.
+template <int D, bool kLazy>
+__global__ __launch_bounds__(256) void attn_f32_kernel(AttnArgs a, int64_t n_q, LazyRefs refs) {
   const int lane = threadIdx.x & 63;
   const int64_t item = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
   if (item >= n_q * a.n_q_heads) return;  // whole wave leaves together
@@ -57,8 +61,34 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(AttnArgs a, int64_t n_q) 
     }
   }
 
+  const int32_t* inst_of = kLazy ? a.src_inst + a.ctx_off[b] : nullptr;
+  const int32_t* row_of = kLazy ? a.src_row + a.ctx_off[b] : nullptr;
+  // where the key / value row of position j is stored
+  auto row_ptr = [&](int j, const float* ctx_base, const void* const* tab) {
+    if constexpr (kLazy) {
+      const int inst = inst_of[j];
+      if (inst >= 0 && refs.by_ref)
+        return static_cast<const float*>(tab[inst]) + g * D + static_cast<int64_t>(row_of[j]) * row_elems;
+    }
+    return ctx_base + static_cast<int64_t>(slot_of[j]) * row_elems;
+  };
   auto logit = [&](int j) {
-    const float* kp = K + static_cast<int64_t>(slot_of[j]) * row_elems;
+    const float* kp = row_ptr(j, K, refs.k);
+    if constexpr (kLazy) {
+      const int inst = inst_of[j];
+      if (inst >= 0) {
+        const float* ct = a.rope_cos + static_cast<int64_t>(inst) * (D / 2);
+        const float* st = a.rope_sin + static_cast<int64_t>(inst) * (D / 2);
+        float acc = 0.f;
+        for (int i = 0; i < D / 2; ++i) {
+          const int ix = a.interleaved ? 2 * i : i, iy = a.interleaved ? 2 * i + 1 : i + D / 2;
+          const float x = kp[ix], y = kp[iy], c = ct[i], s = st[i];
+          acc = fmaf(q[ix], x * c - y * s, acc);
+          acc = fmaf(q[iy], x * s + y * c, acc);
+        }
+        return acc * a.scale;
+      }
+    }
     float acc = 0.f;
 #pragma unroll
     for (int d = 0; d < D; d += 4) {
@@ -83,7 +113,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(AttnArgs a, int64_t n_q) 
   for (int j = lane; j < n_keys; j += 64) {
     const float w = expf(logit(j) - m);
     z += w;
-    const float* vp = V + static_cast<int64_t>(slot_of[j]) * row_elems;
+    const float* vp = row_ptr(j, V, refs.v);
 #pragma unroll
     for (int d = 0; d < D; d += 4) {
       const float4 t = *reinterpret_cast<const float4*>(vp + d);
@@ -109,14 +139,21 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(AttnArgs a, int64_t n_q) 
 
 }  // namespace
 
-hipError_t launch_attn_f32(const AttnArgs& a, int64_t n_q, hipStream_t stream) {
+hipError_t launch_attn_f32(const AttnArgs& a, int64_t n_q, const LazyRefs* lazy, hipStream_t stream) {
   const int64_t items = n_q * a.n_q_heads;
   if (items <= 0) return hipSuccess;
   const dim3 grid(static_cast<unsigned>((items + 3) / 4)), block(256);
-  if (a.head_dim == 64)
-    hipLaunchKernelGGL((attn_f32_kernel<64>), grid, block, 0, stream, a, n_q);
-  else
-    hipLaunchKernelGGL((attn_f32_kernel<128>), grid, block, 0, stream, a, n_q);
+  if (lazy) {
+    if (a.head_dim == 64)
+      hipLaunchKernelGGL((attn_f32_kernel<64, true>), grid, block, 0, stream, a, n_q, *lazy);
+    else
+      hipLaunchKernelGGL((attn_f32_kernel<128, true>), grid, block, 0, stream, a, n_q, *lazy);
+  } else {
+    if (a.head_dim == 64)
+      hipLaunchKernelGGL((attn_f32_kernel<64, false>), grid, block, 0, stream, a, n_q, LazyRefs{});
+    else
+      hipLaunchKernelGGL((attn_f32_kernel<128, false>), grid, block, 0, stream, a, n_q, LazyRefs{});
+  }
   return hipGetLastError();
 }
 

@@ -32,6 +32,23 @@ struct AttnMerge {
 };
 static_assert(sizeof(AttnMerge) == 32, "merge item layout");
 
+// Contexts with lazy_rope: the keys of a request, cut into blocks that never straddle a change
+// of source (a chunk instance, or a run of fresh rows).  Inside a block all keys come from
+// consecutive rows of one source and lack the same position shift, so a kernel can turn the
+// query back once per block instead of turning every key forward (Sec. 4.1: the linker joins
+// caches and touches nothing else).  A block holds n_valid <= BN keys at positions pos0 ..
+// pos0 + n_valid - 1; the rest of its BN slots are padding that the kernels mask.
+struct KeyBlock {
+  int32_t pos0;     // position (inside its request) of the block's first key
+  int32_t n_valid;  // keys in the block, 1 .. BN
+  int32_t inst;     // chunk instance that stores the keys (they lack its shift), -1 = fresh rows
+  int32_t req;      // owning request
+};
+static_assert(sizeof(KeyBlock) == 16, "key block layout");
+constexpr int kNumBlockSizes = 3;
+constexpr int kBlockSizes[kNumBlockSizes] = {32, 64, 96};  // decode kernel, attention kernel shapes
+inline int block_size_index(int bn) { return bn == 32 ? 0 : bn == 64 ? 1 : 2; }
+
 // Device-resident copy of a plan.
 struct PlanDevice {
   int32_t* src_inst = nullptr;
@@ -49,6 +66,12 @@ struct PlanDevice {
   float* fresh_sin = nullptr;
   AttnTile* tiles = nullptr;
   AttnMerge* merges = nullptr;
+  // lazy_rope contexts, one set per block size (kBlockSizes)
+  KeyBlock* kblk[kNumBlockSizes] = {};
+  int32_t* kblk_first[kNumBlockSizes] = {};   // [B+1] first block of each request
+  uint32_t* voff_ctx[kNumBlockSizes] = {};    // [n_blocks * BN + pad] row offsets (16-byte units), every row in the context
+  uint32_t* voff_ref[kNumBlockSizes] = {};    // the same with stored rows addressed inside their source
+  AttnTile* lazy_tiles[kNumBlockSizes] = {};  // tiles with (key0, n_keys) replaced by (first block, end block) of the request
   void* block = nullptr;  // the single allocation all of the above point into
   int device = -1;
 };
@@ -107,6 +130,12 @@ struct mpic_plan {
   int64_t est_idle_blocks = 0;
   std::vector<int32_t> launch_est;  // MPIC_PLAN_LAUNCH_ESTIMATE
   std::vector<float> rope_cos, rope_sin;
+  // contexts with lazy_rope only: key blocks per block size, first block of every request,
+  // attention tiles in block indices (empty for the decode block size)
+  std::vector<mpic::KeyBlock> kblk[mpic::kNumBlockSizes];
+  std::vector<int32_t> kblk_first[mpic::kNumBlockSizes];
+  std::vector<mpic::AttnTile> lazy_tiles[mpic::kNumBlockSizes];
+  std::vector<int32_t> kblk_flat[mpic::kNumBlockSizes];  // the blocks as int32 quadruples, for mpic_plan_get
   std::vector<int32_t> fresh_rot;            // contexts with fresh_pre_rope only
   std::vector<float> fresh_cos, fresh_sin;   // one row per distinct position id
   mpic::PlanDevice dev;
@@ -137,9 +166,14 @@ struct NextLink {
   void* k_ctx;
   void* v_ctx;
 };
+// refs non-null (lazy_rope contexts): stored rows are read in place in these chunk caches.
+struct SrcRefs {
+  const mpic_chunk_src* srcs;
+  int32_t n_srcs;
+};
 int attend(mpic_ctx* ctx, mpic_plan* plan, const void* fresh_q, int64_t n_fresh_rows,
            const void* k_ctx, const void* v_ctx, int64_t n_ctx_slots, double softmax_scale, void* out,
-           float* lse, void* stream, const NextLink* next, int32_t block_keys = 0);
+           float* lse, void* stream, const NextLink* next, int32_t block_keys = 0, const SrcRefs* refs = nullptr);
 
 // Rows of the attention tile handled by one workgroup of the bf16 kernel.
 constexpr int kAttnTileRows = 256;
@@ -200,11 +234,35 @@ struct AttnArgs {
   const float* q_cos;
   const float* q_sin;
   int32_t interleaved;
+  // lazy_rope contexts, fp32 kernel: source of every position and the rotary tables of the instances
+  const int32_t* src_inst;
+  const int32_t* src_row;
+  const float* rope_cos;
+  const float* rope_sin;
+};
+// Contexts with lazy_rope: stored keys are never turned to their global position.  The kernel
+// walks the request's key blocks (KeyBlock: all keys of a block come from consecutive rows of
+// one source and lack the same shift) and turns its *queries* back by that shift whenever the
+// source changes, <Rot(-s) q, k> = <q, Rot(s) k>.  Each block is staged from the base address of
+// its source: the context buffers for fresh rows (and for stored rows that were copied there),
+// or the chunk's cache itself when the caches are linked by reference.
+struct LazyRefs {
+  const KeyBlock* blocks;  // key blocks of the batch for this kernel's block size
+  const int32_t* first;    // [B+1] first block of every request
+  const uint32_t* voff;    // [n_blocks][BN] row offsets (16-byte units) from the block's base
+  const float* rope_cos;   // [n_inst][D/2] cos / sin of every instance's shift
+  const float* rope_sin;
+  int32_t by_ref;          // 0: every block is staged from the context buffers (the tables below are unused);
+                           // 1: stored rows are read in their caches, at the addresses below
+  int32_t pad;
+  const void* k[kMaxInstPerLaunch];  // base of the rows of every chunk instance
+  const void* v[kMaxInstPerLaunch];
 };
 // `next` / `next_tab` non-null: workgroups after the attention tiles link those rows (stored
 // rows of the next layer's context; device-resident sources only, at most kMaxInstPerLaunch).
+// `lazy` non-null: the lazy_rope kernel (a.tiles then counts in key blocks); not combined with `next`.
 hipError_t launch_attn_bf16(const AttnArgs& a, const AssembleArgs* next, const AssembleSrcTable* next_tab,
-                            hipStream_t stream);
+                            const LazyRefs* lazy, hipStream_t stream);
 
 // Keys of a decode split are a multiple of this (four wavefronts x 32-key blocks).
 constexpr int kDecodeBlockKeys = 128;
@@ -225,12 +283,22 @@ struct DecodeArgs {
   int32_t n_q_heads, n_kv_heads, head_dim, n_requests;
   int32_t n_splits, keys_per_split;
   int32_t max_ctx;  // longest context of the batch
+  // lazy_rope contexts: keys_per_split and max_ctx then count 32-key slots of the request's key
+  // blocks (KeyBlock list for 32 keys); the fp32 kernel uses the per-position maps instead
+  int32_t interleaved;
+  const int32_t* blk_first;  // [B+1] first 32-key block of each request (bf16), null otherwise
+  const int32_t* src_inst;
+  const int32_t* src_row;
+  const float* rope_cos;
+  const float* rope_sin;
 };
-hipError_t launch_decode(int dtype, const DecodeArgs& a, hipStream_t stream);
+// `lazy` non-null: the lazy_rope kernels.
+hipError_t launch_decode(int dtype, const DecodeArgs& a, const LazyRefs* lazy, hipStream_t stream);
 // Device address and size of the file-scope scratch array of the decode kernels on the
 // current GPU (looked up once per device; allocates nothing).
 hipError_t decode_static_scratch(float** ptr, size_t* bytes);
-hipError_t launch_attn_f32(const AttnArgs& a, int64_t n_q, hipStream_t stream);
+// `lazy` non-null (lazy_rope contexts): stored keys are turned to their position as they are read.
+hipError_t launch_attn_f32(const AttnArgs& a, int64_t n_q, const LazyRefs* lazy, hipStream_t stream);
 
 
 // Can the attention launch of this plan carry the linking of the next layer (device-resident

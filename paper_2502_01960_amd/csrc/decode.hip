@@ -17,6 +17,8 @@
 // scalars).  The four wavefronts merge their partial results through LDS and write one
 // (O, log-sum-exp) partial per split; a second small kernel merges the splits and adds
 // the new token itself.
+#include <type_traits>
+
 #include "common.h"
 #include "wave_ops.h"
 
@@ -55,7 +57,17 @@ __device__ inline void wait_loads(int blocks) {
 }
 static_assert(LOADS_PER_BLOCK == 16, "wait_loads spells the count out");
 
-__global__ __launch_bounds__(THREADS) void decode_bf16_kernel(DecodeArgs a) {
+// Extra = LazyRefs (lazy_rope contexts): the wavefronts walk the request's 32-key blocks of the
+// plan (KeyBlock: one source and one missing shift per block, slots past n_valid are padding),
+// stage each block from its source's base address, and turn the query back by the block's shift
+// whenever it changes, <Rot(-s) q, k> = <q, Rot(s) k>; a.keys_per_split then counts slots of
+// those blocks.
+struct NoLazy {};
+typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+
+template <typename Extra>
+__global__ __launch_bounds__(THREADS) void decode_bf16_kernel(DecodeArgs a, Extra extra) {
+  constexpr bool kLazy = std::is_same<Extra, LazyRefs>::value;
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -68,16 +80,37 @@ __global__ __launch_bounds__(THREADS) void decode_bf16_kernel(DecodeArgs a) {
   const int g = blockIdx.y / col_blocks;
   const int cb = blockIdx.y % col_blocks;
   const int b = blockIdx.z;
-  const int n_ctx = a.ctx_off[b + 1] - a.ctx_off[b];
+  // keys of this request, or (lazy) slots of its key blocks
+  int n_ctx = a.ctx_off[b + 1] - a.ctx_off[b];
+  int vb0 = 0;
+  if constexpr (kLazy) {
+    n_ctx = (extra.first[b + 1] - extra.first[b]) * BN;
+    vb0 = extra.first[b] + split * (a.keys_per_split / BN);
+  }
   const int key0 = split * a.keys_per_split;
   if (key0 >= n_ctx) return;  // this request has fewer splits (the whole workgroup leaves)
   const int n_keys = min(n_ctx, key0 + a.keys_per_split) - key0;
   const int n_blk = (n_keys + BN - 1) / BN;
 
-  const __attribute__((address_space(4))) uint32_t* off_of =
-      (const __attribute__((address_space(4))) uint32_t*)(a.kv_off16 + a.ctx_off[b] + key0);
-  const char* kbase = static_cast<const char*>(a.k_ctx) + g * ROW_BYTES;
-  const char* vbase = static_cast<const char*>(a.v_ctx) + g * ROW_BYTES;
+  const __attribute__((address_space(4))) uint32_t* off_of;
+  if constexpr (kLazy) {
+    off_of = (const __attribute__((address_space(4))) uint32_t*)(extra.voff + static_cast<int64_t>(vb0) * BN);
+  } else {
+    off_of = (const __attribute__((address_space(4))) uint32_t*)(a.kv_off16 + a.ctx_off[b] + key0);
+  }
+  auto desc_of = [&](int blk) __attribute__((always_inline)) {
+    blk = blk < n_blk ? blk : n_blk - 1;
+    KeyBlock d{};
+    if constexpr (kLazy) {
+      const i32x4 raw = *(const __attribute__((address_space(4))) i32x4*)(extra.blocks + vb0 + blk);
+      d.pos0 = raw[0];
+      d.n_valid = raw[1];
+      d.inst = raw[2];
+    }
+    return d;
+  };
+  const char* kbase_ctx = static_cast<const char*>(a.k_ctx) + g * ROW_BYTES;
+  const char* vbase_ctx = static_cast<const char*>(a.v_ctx) + g * ROW_BYTES;
   char* my_lds = lds + wave * WAVE_LDS;
   const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(MPIC_LDS_PTR(char, my_lds)));
 
@@ -90,6 +123,53 @@ __global__ __launch_bounds__(THREADS) void decode_bf16_kernel(DecodeArgs a) {
   bf16x8 qf[8];
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16 + hi * 8);
+  // lazy: the query as handed over, and the query turned back by the shift of instance `inst`
+  // (fp32 arithmetic, one rounding).  This lane holds coordinates d = 16*ks + 8*hi + e: a
+  // rotate-half pair (d, d + 64) is (q[ks], q[ks + 4]), an interleaved pair two neighbours.
+  bf16x8 q0[8];
+  int q_inst = -1;
+  if constexpr (kLazy) {
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) q0[ks] = qf[ks];
+  }
+  auto turn_back = [&](int inst) __attribute__((always_inline)) {
+    if (inst < 0) {
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) qf[ks] = q0[ks];
+      return;
+    }
+    const float* cb = nullptr;
+    const float* sb = nullptr;
+    if constexpr (kLazy) {
+      cb = extra.rope_cos + static_cast<int64_t>(inst) * (D / 2);
+      sb = extra.rope_sin + static_cast<int64_t>(inst) * (D / 2);
+    }
+    if (a.interleaved) {
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        const f32x4 c = *reinterpret_cast<const f32x4*>(cb + ks * 8 + hi * 4);
+        const f32x4 s = *reinterpret_cast<const f32x4*>(sb + ks * 8 + hi * 4);
+        const f32x8 x = __builtin_convertvector(q0[ks], f32x8);
+        f32x8 y;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          y[2 * i] = x[2 * i] * c[i] + x[2 * i + 1] * s[i];
+          y[2 * i + 1] = x[2 * i + 1] * c[i] - x[2 * i] * s[i];
+        }
+        qf[ks] = __builtin_convertvector(y, bf16x8);
+      }
+    } else {
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        const f32x8 c = *reinterpret_cast<const f32x8*>(cb + ks * 16 + hi * 8);
+        const f32x8 s = *reinterpret_cast<const f32x8*>(sb + ks * 16 + hi * 8);
+        const f32x8 x0 = __builtin_convertvector(q0[ks], f32x8);
+        const f32x8 x1 = __builtin_convertvector(q0[ks + 4], f32x8);
+        qf[ks] = __builtin_convertvector(x0 * c + x1 * s, bf16x8);
+        qf[ks + 4] = __builtin_convertvector(x1 * c - x0 * s, bf16x8);
+      }
+    }
+  };
 
   const float scale_log2 = a.scale * 1.4426950408889634f;
   float m_run = -INFINITY;
@@ -105,16 +185,32 @@ __global__ __launch_bounds__(THREADS) void decode_bf16_kernel(DecodeArgs a) {
   const uint32_t ld_col = lane & 15;
   const uint32_t ld_k16 = ld_col ^ ld_sub;        // ^ ((p & 3) << 2)
   const uint32_t ld_v16 = ld_col ^ (ld_sub << 2);
-  struct Rows { u32x8_a4 r[4]; };
+  struct Rows {
+    u32x8_a4 r[4];
+    const char* kb;  // lazy: base of the block's rows (context, or the chunk's cache)
+    const char* vb;
+  };
   auto fetch_rows = [&](int blk) {
     blk = blk < n_blk ? blk : n_blk - 1;
     Rows x;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
       x.r[i] = *reinterpret_cast<const __attribute__((address_space(4))) u32x8_a4*>(off_of + blk * BN + i * 8);
+    if constexpr (kLazy) {
+      const int inst = desc_of(blk).inst;
+      const bool in_ctx = inst < 0 || !extra.by_ref;
+      x.kb = (in_ctx ? static_cast<const char*>(a.k_ctx) : static_cast<const char*>(extra.k[inst])) + g * ROW_BYTES;
+      x.vb = (in_ctx ? static_cast<const char*>(a.v_ctx) : static_cast<const char*>(extra.v[inst])) + g * ROW_BYTES;
+    }
     return x;
   };
   auto issue_loads = [&](const Rows& cur, int stage) {
+    const char* kbase = kbase_ctx;
+    const char* vbase = vbase_ctx;
+    if constexpr (kLazy) {
+      kbase = cur.kb;
+      vbase = cur.vb;
+    }
     const uint32_t dst = lds_base + stage * STAGE_BYTES;
 #pragma unroll
     for (int p = 0; p < 8; ++p) {
@@ -165,6 +261,14 @@ __global__ __launch_bounds__(THREADS) void decode_bf16_kernel(DecodeArgs a) {
     }
     wait_loads(issued - it - 1);
     const char* st = my_lds + stage * STAGE_BYTES;
+    KeyBlock kd{};
+    if constexpr (kLazy) {
+      kd = desc_of(blk);
+      if (kd.inst != q_inst) {  // the keys of this block lack another shift than the last block's
+        turn_back(kd.inst);
+        q_inst = kd.inst;
+      }
+    }
 
     // S^T = K . Q^T for 32 keys x 32 query columns
     f32x16 acc_s = f32x16{0};
@@ -174,6 +278,15 @@ __global__ __launch_bounds__(THREADS) void decode_bf16_kernel(DecodeArgs a) {
       acc_s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], acc_s, 0, 0, 0);
     }
     // keys past the end of the context (ragged last block) take no weight
+    if constexpr (kLazy) {
+      if (kd.n_valid < BN) {  // slots past the block's keys are padding
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int slot = (v >> 2) * 8 + hi * 4 + (v & 3);
+          acc_s[v] = slot < kd.n_valid ? acc_s[v] : -INFINITY;
+        }
+      }
+    } else {
     const int j0 = blk * BN;
     if (j0 + BN > n_keys) {
 #pragma unroll
@@ -181,6 +294,7 @@ __global__ __launch_bounds__(THREADS) void decode_bf16_kernel(DecodeArgs a) {
         const int key = j0 + (v >> 2) * 8 + hi * 4 + (v & 3);
         acc_s[v] = key < n_keys ? acc_s[v] : -INFINITY;
       }
+    }
     }
     float m_blk = -INFINITY;
 #pragma unroll
@@ -288,7 +402,8 @@ __global__ __launch_bounds__(kD) void decode_merge_kernel(DecodeArgs a) {
   const int b = static_cast<int>(row / a.n_q_heads);
   const int h = static_cast<int>(row % a.n_q_heads);
   const int g = h / (a.n_q_heads / a.n_kv_heads);
-  const int n_ctx = a.ctx_off[b + 1] - a.ctx_off[b];
+  // keys of the request, or (lazy_rope, bf16) slots of its 32-key blocks
+  const int n_ctx = a.blk_first ? (a.blk_first[b + 1] - a.blk_first[b]) * 32 : a.ctx_off[b + 1] - a.ctx_off[b];
   const int n_s = (n_ctx + a.keys_per_split - 1) / a.keys_per_split;
   float self = -INFINITY;
   float v_new = 0.f;
@@ -357,8 +472,11 @@ __global__ __launch_bounds__(kD) void decode_merge_kernel(DecodeArgs a) {
 
 // fp32 path: one wavefront per (request, query head), lanes stride over the keys, two
 // passes (maximum, then weighted sum); writes its result as the only split of the row.
-template <int kD>
-__global__ __launch_bounds__(256) void decode_f32_kernel(DecodeArgs a) {
+// kLazy (lazy_rope contexts): stored keys are turned to their position as they are read, in
+// fp32, inside the dot product (see the fp32 prefill kernel); refs.by_ref: stored rows are read
+// in their caches.
+template <int kD, bool kLazy>
+__global__ __launch_bounds__(256) void decode_f32_kernel(DecodeArgs a, LazyRefs refs) {
   const int lane = threadIdx.x & 63;
   const int64_t row = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
   if (row >= static_cast<int64_t>(a.n_requests) * a.n_q_heads) return;
@@ -378,8 +496,33 @@ __global__ __launch_bounds__(256) void decode_f32_kernel(DecodeArgs a) {
     const float4 t = *reinterpret_cast<const float4*>(qp + d);
     q[d] = t.x; q[d + 1] = t.y; q[d + 2] = t.z; q[d + 3] = t.w;
   }
+  const int32_t* inst_of = kLazy ? a.src_inst + a.ctx_off[b] : nullptr;
+  const int32_t* row_of = kLazy ? a.src_row + a.ctx_off[b] : nullptr;
+  auto row_ptr = [&](int j, const float* ctx_base, const void* const* tab) {
+    if constexpr (kLazy) {
+      const int inst = inst_of[j];
+      if (inst >= 0 && refs.by_ref)
+        return static_cast<const float*>(tab[inst]) + g * kD + static_cast<int64_t>(row_of[j]) * row_elems;
+    }
+    return ctx_base + static_cast<int64_t>(slot_of[j]) * row_elems;
+  };
   auto logit = [&](int j) {
-    const float* kp = K + static_cast<int64_t>(slot_of[j]) * row_elems;
+    const float* kp = row_ptr(j, K, refs.k);
+    if constexpr (kLazy) {
+      const int inst = inst_of[j];
+      if (inst >= 0) {
+        const float* ct = a.rope_cos + static_cast<int64_t>(inst) * (kD / 2);
+        const float* st = a.rope_sin + static_cast<int64_t>(inst) * (kD / 2);
+        float acc = 0.f;
+        for (int i = 0; i < kD / 2; ++i) {
+          const int ix = a.interleaved ? 2 * i : i, iy = a.interleaved ? 2 * i + 1 : i + kD / 2;
+          const float x = kp[ix], y = kp[iy], c = ct[i], s = st[i];
+          acc = fmaf(q[ix], x * c - y * s, acc);
+          acc = fmaf(q[iy], x * s + y * c, acc);
+        }
+        return acc * a.scale;
+      }
+    }
     float acc = 0.f;
 #pragma unroll
     for (int d = 0; d < kD; d += 4) {
@@ -402,7 +545,7 @@ __global__ __launch_bounds__(256) void decode_f32_kernel(DecodeArgs a) {
   for (int j = lane; j < n_ctx; j += 64) {
     const float w = expf(logit(j) - m);
     z += w;
-    const float* vp = V + static_cast<int64_t>(slot_of[j]) * row_elems;
+    const float* vp = row_ptr(j, V, refs.v);
 #pragma unroll
     for (int d = 0; d < kD; d += 4) {
       const float4 t = *reinterpret_cast<const float4*>(vp + d);
@@ -455,16 +598,23 @@ hipError_t decode_static_scratch(float** ptr, size_t* bytes) {
   return hipSuccess;
 }
 
-hipError_t launch_decode(int dtype, const DecodeArgs& a, hipStream_t stream) {
+hipError_t launch_decode(int dtype, const DecodeArgs& a, const LazyRefs* lazy, hipStream_t stream) {
   const int64_t rows = static_cast<int64_t>(a.n_requests) * a.n_q_heads;
   if (rows <= 0) return hipSuccess;
   if (dtype == MPIC_F32) {
     const dim3 grid(static_cast<unsigned>((rows + 3) / 4)), block(256);
+    const LazyRefs refs = lazy ? *lazy : LazyRefs{};
     if (a.head_dim == 64) {
-      hipLaunchKernelGGL((decode_f32_kernel<64>), grid, block, 0, stream, a);
+      if (lazy)
+        hipLaunchKernelGGL((decode_f32_kernel<64, true>), grid, block, 0, stream, a, refs);
+      else
+        hipLaunchKernelGGL((decode_f32_kernel<64, false>), grid, block, 0, stream, a, refs);
       hipLaunchKernelGGL((decode_merge_kernel<float, 64>), dim3(static_cast<unsigned>(rows)), dim3(64), 0, stream, a);
     } else {
-      hipLaunchKernelGGL((decode_f32_kernel<128>), grid, block, 0, stream, a);
+      if (lazy)
+        hipLaunchKernelGGL((decode_f32_kernel<128, true>), grid, block, 0, stream, a, refs);
+      else
+        hipLaunchKernelGGL((decode_f32_kernel<128, false>), grid, block, 0, stream, a, refs);
       hipLaunchKernelGGL((decode_merge_kernel<float, 128>), dim3(static_cast<unsigned>(rows)), dim3(128), 0, stream, a);
     }
     return hipGetLastError();
@@ -474,13 +624,21 @@ hipError_t launch_decode(int dtype, const DecodeArgs& a, hipStream_t stream) {
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
   e = opt_in.ensure(dev, [] {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(decode_bf16_kernel),
+    const hipError_t e0 = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_bf16_kernel<NoLazy>),
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+    if (e0 != hipSuccess) return e0;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(decode_bf16_kernel<LazyRefs>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
   });
   if (e != hipSuccess) return e;
   const int group = a.n_q_heads / a.n_kv_heads;
   const dim3 grid(a.n_splits, a.n_kv_heads * ((group + 31) / 32), a.n_requests);
-  if (a.max_ctx > 0) hipLaunchKernelGGL(decode_bf16_kernel, grid, dim3(THREADS), LDS_BYTES, stream, a);
+  if (a.max_ctx > 0) {
+    if (lazy)
+      hipLaunchKernelGGL(decode_bf16_kernel<LazyRefs>, grid, dim3(THREADS), LDS_BYTES, stream, a, *lazy);
+    else
+      hipLaunchKernelGGL(decode_bf16_kernel<NoLazy>, grid, dim3(THREADS), LDS_BYTES, stream, a, NoLazy{});
+  }
   hipLaunchKernelGGL((decode_merge_kernel<__bf16, 128>), dim3(static_cast<unsigned>(rows)), dim3(128), 0, stream, a);
   return hipGetLastError();
 }

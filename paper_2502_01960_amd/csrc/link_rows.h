@@ -106,8 +106,10 @@ __device__ inline Loaded<T> load_item_at(const AssembleArgs& a, const AssembleSr
     if (kt == nullptr) return r;  // source still in flight: a later launch links this row
     ksrc = kt + srow * row_elems;
     vsrc = vt + srow * row_elems;
-    ct = a.rope_cos + static_cast<int64_t>(inst) * half;
-    st = a.rope_sin + static_cast<int64_t>(inst) * half;
+    if (a.rope_cos) {  // (null: stored keys are copied as stored)
+      ct = a.rope_cos + static_cast<int64_t>(inst) * half;
+      st = a.rope_sin + static_cast<int64_t>(inst) * half;
+    }
   }
   T* kdst = static_cast<T*>(a.k_ctx) + slot * row_elems;
   T* vdst = static_cast<T*>(a.v_ctx) + slot * row_elems;

@@ -253,6 +253,61 @@ void build_tiles(mpic_plan& p, int group, int n_kv_heads) {
   while (!p.tiles.empty() && p.tiles.back().n_rows == 0) p.tiles.pop_back();
 }
 
+// Key blocks of a lazy_rope plan (see KeyBlock).  A block ends where the source of the keys
+// changes (next chunk instance, or stored rows <-> fresh rows), where a tile that was cut
+// along the keys starts a new piece (so that a piece owns whole blocks), and after BN keys.
+// The tiles are then restated in block indices of their request, once per kernel shape.
+void build_key_blocks(mpic_plan& p) {
+  const int B = p.n_requests;
+  std::vector<std::vector<int32_t>> cuts(B);
+  for (const AttnTile& t : p.tiles)
+    if (t.n_rows > 0 && t.key0 > 0) cuts[t.req].push_back(t.key0);
+  for (auto& c : cuts) {
+    std::sort(c.begin(), c.end());
+    c.erase(std::unique(c.begin(), c.end()), c.end());
+  }
+  for (int s = 0; s < kNumBlockSizes; ++s) {
+    const int32_t bn = kBlockSizes[s];
+    auto& blocks = p.kblk[s];
+    auto& first = p.kblk_first[s];
+    blocks.clear();
+    first.assign(1, 0);
+    for (int b = 0; b < B; ++b) {
+      const int32_t ctx0 = p.ctx_off[b], n = p.ctx_off[b + 1] - ctx0;
+      size_t next_cut = 0;
+      for (int32_t pos = 0; pos < n;) {
+        while (next_cut < cuts[b].size() && cuts[b][next_cut] <= pos) ++next_cut;
+        const int32_t limit = next_cut < cuts[b].size() ? std::min(n, cuts[b][next_cut]) : n;
+        const int32_t inst = p.src_inst[ctx0 + pos];
+        int32_t end = pos + 1;
+        while (end < limit && p.src_inst[ctx0 + end] == inst) ++end;
+        for (int32_t q = pos; q < end; q += bn) blocks.push_back(KeyBlock{q, std::min(bn, end - q), inst, b});
+        pos = end;
+      }
+      first.push_back(static_cast<int32_t>(blocks.size()));
+    }
+    p.kblk_flat[s].resize(blocks.size() * 4);
+    if (!blocks.empty()) std::memcpy(p.kblk_flat[s].data(), blocks.data(), blocks.size() * sizeof(KeyBlock));
+    p.lazy_tiles[s].clear();
+    if (bn == 32) continue;  // the decode kernel splits its blocks at launch
+    // block that holds position `pos` of request b, relative to the request's first block
+    auto block_of = [&](int b, int32_t pos) {
+      const KeyBlock* lo = blocks.data() + first[b];
+      const KeyBlock* hi = blocks.data() + first[b + 1];
+      const KeyBlock* it = std::upper_bound(lo, hi, pos, [](int32_t v, const KeyBlock& k) { return v < k.pos0; });
+      return static_cast<int32_t>(it - lo) - 1;
+    };
+    p.lazy_tiles[s] = p.tiles;
+    for (AttnTile& t : p.lazy_tiles[s]) {
+      if (t.n_rows <= 0) continue;
+      const int32_t b0 = block_of(t.req, t.key0);  // key0 is a block start: 0 or a cut
+      const int32_t b1 = block_of(t.req, t.n_keys - 1) + 1;
+      t.key0 = b0;
+      t.n_keys = b1;
+    }
+  }
+}
+
 // Rotary tables of the fresh rows, for contexts whose fresh Q/K arrive without positions:
 // one table row per distinct position id of the batch (requests with the same layout share
 // all of them) and an index per fresh row.  cos/sin of p * w_i are evaluated in double
@@ -316,7 +371,8 @@ extern "C" int mpic_create(mpic_ctx** out, const mpic_config* config) {
   const mpic_config& c = *config;
   if (c.n_q_heads <= 0 || c.n_kv_heads <= 0 || c.head_dim <= 0 || c.n_q_heads % c.n_kv_heads != 0 ||
       (c.head_dim & 1) || !(c.rope_theta > 0.0) || !std::isfinite(c.rope_theta) || c.page_size < 0 ||
-      (c.rope_interleaved != 0 && c.rope_interleaved != 1) || (c.fresh_pre_rope != 0 && c.fresh_pre_rope != 1))
+      (c.rope_interleaved != 0 && c.rope_interleaved != 1) || (c.fresh_pre_rope != 0 && c.fresh_pre_rope != 1) ||
+      (c.lazy_rope != 0 && c.lazy_rope != 1))
     return MPIC_ERR_INVALID;
   if (c.dtype == MPIC_F32) {
     if (c.head_dim != 64 && c.head_dim != 128) return MPIC_ERR_UNSUPPORTED;
@@ -505,6 +561,7 @@ extern "C" int mpic_plan_create_selected(mpic_ctx* ctx, int32_t n_requests, cons
       }
     if (ctx->cfg.fresh_pre_rope) mpic::build_fresh_rope(*p, ctx->cfg);
     mpic::build_tiles(*p, ctx->group, ctx->cfg.n_kv_heads);
+    if (ctx->cfg.lazy_rope) mpic::build_key_blocks(*p);
     {
       auto clamp = [](int64_t x) { return static_cast<int32_t>(std::min<int64_t>(x, INT32_MAX)); };
       p->launch_est = {clamp(p->est_makespan_blocks), clamp(p->est_idle_blocks),
@@ -538,6 +595,16 @@ extern "C" int mpic_plan_get(const mpic_plan* plan, int32_t what, const int32_t*
     case MPIC_PLAN_INST_REQ: v = &plan->inst_req; break;
     case MPIC_PLAN_RUNS: v = &plan->runs; break;
     case MPIC_PLAN_LAUNCH_ESTIMATE: v = &plan->launch_est; break;
+    case MPIC_PLAN_KEY_BLOCKS_32: v = &plan->kblk_flat[0]; break;
+    case MPIC_PLAN_KEY_BLOCKS_64: v = &plan->kblk_flat[1]; break;
+    case MPIC_PLAN_KEY_BLOCKS_96: v = &plan->kblk_flat[2]; break;
+    case MPIC_PLAN_LAZY_TILES_64:
+    case MPIC_PLAN_LAZY_TILES_96: {
+      const auto& t = plan->lazy_tiles[what == MPIC_PLAN_LAZY_TILES_64 ? 1 : 2];
+      *host_ptr = reinterpret_cast<const int32_t*>(t.data());
+      *n = t.size() * 8;
+      return MPIC_OK;
+    }
     case MPIC_PLAN_ATTN_TILES:
       *host_ptr = reinterpret_cast<const int32_t*>(plan->tiles.data());
       *n = plan->tiles.size() * 8;

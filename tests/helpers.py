@@ -6,7 +6,7 @@ import torch
 
 import workloads
 import paper_2502_01960_amd as mpic
-from oracle import attend, build_plan, decode_attend, link_kv, position_fresh
+from oracle import attend, build_plan, decode_attend, link_kv, link_kv_unshifted, position_fresh
 
 
 class Problem:
@@ -14,6 +14,7 @@ class Problem:
     interleaved = False
     pre_rope = False
     block_keys = 0        # shape of the bf16 attention kernel: 0 = the library's choice, 64 or 96
+    lazy = False          # context with lazy_rope: stored keys are never rewritten, queries are turned back
 
     def __init__(self, cfg_id, *, k=None, layer=0, paged=None, interleaved=False, pre_rope=False, **layout_kw):
         self.sh = sh = workloads.shape(cfg_id)
@@ -48,6 +49,14 @@ class Problem:
         return link_kv(self.oplan, ck, cv, f64(self.fresh_k), f64(self.fresh_v), self.sh.rope_theta,
                        self.interleaved, self.pre_rope)
 
+    def oracle_link_unshifted(self):
+        """(K, V, shift): the linked context with stored keys left as stored (float64)."""
+        f64 = lambda t: t.to(torch.float64).numpy()
+        ck = {s: f64(kv[0]) for s, kv in self.chunks.items()}
+        cv = {s: f64(kv[1]) for s, kv in self.chunks.items()}
+        return link_kv_unshifted(self.oplan, ck, cv, f64(self.fresh_k), f64(self.fresh_v), self.sh.rope_theta,
+                                 self.interleaved, self.pre_rope)
+
     def oracle_attend(self, K, V, rows=None):
         q = self.q.to(torch.float64).numpy()
         if self.pre_rope:
@@ -60,7 +69,7 @@ class Problem:
         dev = torch.device("cuda:0")
         dt = mpic.MPIC_F32 if sh.dtype == "f32" else mpic.MPIC_BF16
         self.ctx = mpic.Context(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, dt, sh.rope_theta,
-                                int(self.interleaved), self.page_size, int(self.pre_rope))
+                                int(self.interleaved), self.page_size, int(self.pre_rope), int(self.lazy))
         if self.block_keys:
             self.ctx.set_option(mpic.MPIC_OPT_ATTN_BLOCK_KEYS, self.block_keys)
         self.plan = mpic.Plan(self.ctx, self.requests, self.k, self.page_tables, self.n_pool_pages)
@@ -90,6 +99,25 @@ class Problem:
     def gpu_attend(self, lse=True):
         mpic.mpic_selective_attn(self.ctx.handle, self.plan.handle, self.d_q, self.k_ctx, self.v_ctx,
                                  self.sh.softmax_scale, self.out, self.lse if lse else None)
+
+    def gpu_link_fresh_only(self):
+        """Only the rows of the recompute set reach the context (caches linked by reference)."""
+        mpic.mpic_assemble_kv_parts(self.ctx.handle, self.plan.handle, None, self.d_fk, self.d_fv, self.k_ctx, self.v_ctx,
+                                    mpic.MPIC_PART_FRESH)
+
+    def gpu_attend_in_place(self, lse=True):
+        mpic.mpic_selective_attn_in_place(self.ctx.handle, self.plan.handle, self.d_q, self.srcs, self.k_ctx, self.v_ctx,
+                                          self.sh.softmax_scale, self.out, self.lse if lse else None)
+
+    def gpu_decode_in_place(self, q, new_k, new_v):
+        dev = self.k_ctx.device
+        out = torch.full(tuple(q.shape), float("nan"), dtype=self.sh.torch_dtype, device=dev)
+        l = torch.full(tuple(q.shape[:2]), float("nan"), dtype=torch.float32, device=dev)
+        mpic.mpic_decode_attn_in_place(self.ctx.handle, self.plan.handle, q.to(dev),
+                                       None if new_k is None else new_k.to(dev), None if new_v is None else new_v.to(dev),
+                                       self.srcs, self.k_ctx, self.v_ctx, self.sh.softmax_scale, out, l)
+        torch.cuda.synchronize()
+        return out.to(torch.float64).cpu().numpy(), l.to(torch.float64).cpu().numpy()
 
     # ---- decode step after the prefill --------------------------------------
     def decode_inputs(self):

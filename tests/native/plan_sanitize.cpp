@@ -11,9 +11,10 @@
 
 namespace mpic {
 hipError_t launch_assemble(int, const AssembleArgs&, const AssembleSrcTable&, hipStream_t) { return hipSuccess; }
-hipError_t launch_attn_bf16(const AttnArgs&, const AssembleArgs*, const AssembleSrcTable*, hipStream_t) { return hipSuccess; }
-hipError_t launch_attn_f32(const AttnArgs&, int64_t, hipStream_t) { return hipSuccess; }
-hipError_t launch_decode(int, const DecodeArgs&, hipStream_t) { return hipSuccess; }
+hipError_t launch_attn_bf16(const AttnArgs&, const AssembleArgs*, const AssembleSrcTable*, const LazyRefs*, hipStream_t) { return hipSuccess; }
+hipError_t launch_attn_f32(const AttnArgs&, int64_t, const LazyRefs*, hipStream_t) { return hipSuccess; }
+hipError_t launch_decode(int, const DecodeArgs&, const LazyRefs*, hipStream_t) { return hipSuccess; }
+hipError_t decode_static_scratch(float**, size_t*) { return hipErrorInvalidDevice; }
 }  // namespace mpic
 
 #define CHECK(c) do { if (!(c)) { std::fprintf(stderr, "check failed: %s (line %d)\n", #c, __LINE__); return 1; } } while (0)
@@ -31,6 +32,7 @@ int main() {
     cfg.rope_theta = 1e4 + iter;
     cfg.page_size = (iter % 3 == 0) ? 16 : 0;
     cfg.fresh_pre_rope = iter % 2;
+    cfg.lazy_rope = (iter / 2) % 2;  // lazy plans build their key-block lists too
     mpic_ctx* ctx = nullptr;
     CHECK(mpic_create(&ctx, &cfg) == MPIC_OK);
     const int B = rnd(1, 4);

@@ -67,7 +67,7 @@ int assemble_parts(mpic_ctx* ctx, mpic_plan* plan, const mpic_chunk_src* srcs, i
   return MPIC_OK;
 }
 int attend(mpic_ctx* ctx, mpic_plan* plan, const void*, int64_t, const void*, const void*, int64_t n_ctx_slots, double,
-           void*, float*, void* stream, const NextLink* next, int32_t) {
+           void*, float*, void* stream, const NextLink* next, int32_t, const SrcRefs*) {
   if (next)
     return assemble_parts(ctx, plan, next->srcs, next->n_srcs, nullptr, nullptr, 0, next->k_ctx, next->v_ctx, n_ctx_slots,
                           MPIC_PART_CACHED, stream);

@@ -13,7 +13,8 @@ import paper_2502_01960_amd as mpic
 from oracle import build_plan
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-INT_FIELDS = [f for f in mpic.PLAN_FIELDS if f not in ("attn_tiles", "launch_estimate")]
+INT_FIELDS = [f for f in mpic.PLAN_FIELDS
+              if f not in ("attn_tiles", "launch_estimate") and not f.startswith(("key_blocks", "lazy_tiles"))]
 
 
 def _ctx(hq=4, hkv=2, d=128, dtype=mpic.MPIC_BF16, theta=1e4, page_size=0):
@@ -139,6 +140,81 @@ def test_paged_plan_matches_oracle(reqs, default_k, ps, rnd):
     got = mpic.Plan(ctx, reqs, default_k, tables, len(pool))
     for f in INT_FIELDS:
         assert np.array_equal(got.get(f), want[f]), f
+
+
+def _check_key_blocks(plan, want, group):
+    """lazy_rope plans: for every block size the blocks list the keys of every request in order,
+    each position exactly once; a block never straddles a change of source (one chunk instance,
+    or fresh rows) and its stored rows are consecutive rows of the cache; every piece of a tile
+    that was cut along the keys owns whole blocks; the tiles restated in block indices cover
+    exactly the keys of the tiles stated in keys."""
+    ctx_off = want["ctx_off"]
+    tiles = plan.get("attn_tiles")
+    for bn in (32, 64, 96):
+        blocks = plan.get(f"key_blocks_{bn}")
+        first = {}
+        at = {}
+        for i, (pos0, n_valid, inst, req) in enumerate(blocks.tolist()):
+            first.setdefault(req, i)
+            assert 1 <= n_valid <= bn
+            assert pos0 == at.get(req, 0), "blocks must list the positions of a request in order, without gaps"
+            at[req] = pos0 + n_valid
+            src = want["src_inst"][ctx_off[req] + pos0: ctx_off[req] + pos0 + n_valid]
+            assert (src == inst).all(), "a block holds keys of one source only"
+            if inst >= 0:
+                rows = want["src_row"][ctx_off[req] + pos0: ctx_off[req] + pos0 + n_valid]
+                assert (np.diff(rows) == 1).all()
+        for b in range(len(ctx_off) - 1):
+            assert at.get(b, 0) == ctx_off[b + 1] - ctx_off[b], "every position of the request in exactly one block"
+        reqs = blocks[:, 3]
+        assert (np.diff(reqs) >= 0).all()
+        if bn == 32:
+            continue
+        lazy = plan.get(f"lazy_tiles_{bn}")
+        assert lazy.shape == tiles.shape
+        starts = {(t[0], t[1], t[2], t[5]) for t in tiles.tolist() if t[3] > 0}
+        for t, l in zip(tiles.tolist(), lazy.tolist()):
+            assert t[:4] == l[:4] and t[6] == l[6]
+            if t[3] == 0:
+                continue
+            b, key_end, key0 = t[0], t[4], t[5]
+            mine = blocks[reqs == b][l[5]:l[4]]
+            assert len(mine) >= 1 and mine[0][0] == key0, "a piece starts at a block start"
+            last = mine[-1]
+            assert last[0] <= key_end - 1 < last[0] + last[1], "the last block holds the tile's last key"
+            if (t[0], t[1], t[2], key_end) in starts:     # another piece of the same rows starts where this one ends:
+                assert last[0] + last[1] == key_end, "a piece that is followed by another owns whole blocks"
+
+
+@pytest.mark.parametrize("cfg", [2, 3, 4, 5])
+def test_key_blocks_of_lazy_plans_on_benchmark_layouts(cfg):
+    sh = workloads.shape(cfg)
+    reqs, _, _ = workloads.layout(cfg)
+    tables, pool = (None, 0)
+    if sh.page_size:
+        tables, pool = workloads.gen_page_tables(sh, [workloads.request_len(r) for r in reqs])
+    ctx = mpic.Context(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, mpic.MPIC_BF16, sh.rope_theta, 0, sh.page_size, 0, 1)
+    for k in ([0, 16, 1024] if cfg == 4 else [sh.default_k]):
+        want = build_plan(reqs, k, sh.page_size, tables)
+        got = mpic.Plan(ctx, reqs, k, tables, pool)
+        for f in INT_FIELDS:
+            assert np.array_equal(got.get(f), want[f]), (cfg, k, f)
+        _check_key_blocks(got, want, sh.n_q_heads // sh.n_kv_heads)
+    # a context without lazy_rope has no such lists
+    plain = mpic.Plan(_ctx(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, mpic.MPIC_BF16, sh.rope_theta, sh.page_size), reqs,
+                      sh.default_k, tables, pool)
+    assert len(plain.get("key_blocks_64")) == 0 and len(plain.get("lazy_tiles_96")) == 0
+
+
+@settings(max_examples=80, deadline=None)
+@given(st.lists(st.lists(segment, min_size=0, max_size=6), min_size=1, max_size=4),
+       st.integers(0, 40), st.sampled_from([(4, 4), (8, 2), (28, 4), (7, 1)]))
+def test_key_blocks_of_lazy_plans_on_random_layouts(reqs, default_k, heads):
+    hq, hkv = heads
+    ctx = mpic.Context(hq, hkv, 128, mpic.MPIC_BF16, 1e4, 0, 0, 0, 1)
+    want = build_plan(reqs, default_k)
+    got = mpic.Plan(ctx, reqs, default_k)
+    _check_key_blocks(got, want, hq // hkv)
 
 
 def test_rope_tables_are_float64_accurate():
