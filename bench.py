@@ -306,6 +306,42 @@ def main():
     attn_each = each(attend_of_step, max(args.steps, 20))
     asm_ms = timed(assemble, args.steps)
 
+    # ---- caches linked by reference (lazy_rope context): no stored row is copied or rewritten; the step
+    # is the scatter of the fresh rows plus the attention launch that reads the caches in place ----
+    ctx_lz = mpic.Context(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, mpic.MPIC_BF16, sh.rope_theta, 0, sh.page_size,
+                          int(args.fresh_pre_rope), 1)
+    if args.attn_block_keys:
+        ctx_lz.set_option(mpic.MPIC_OPT_ATTN_BLOCK_KEYS, args.attn_block_keys)
+    plan_lz = mpic.Plan(ctx_lz, requests, sh.default_k, tables, pool)
+
+    def attend_in_place(s):
+        mpic.mpic_selective_attn_in_place(ctx_lz.handle, plan_lz.handle, s["q"], s["srcs"], s["k_ctx"], s["v_ctx"],
+                                          sh.softmax_scale, s["out"], None, stream)
+
+    def step_in_place(s):
+        mpic.mpic_assemble_kv_parts(ctx_lz.handle, plan_lz.handle, None, s["fk"], s["fv"], s["k_ctx"], s["v_ctx"],
+                                    mpic.MPIC_PART_FRESH, stream)
+        attend_in_place(s)
+
+    in_place = None
+    if len(plan_lz.get("inst_src")) <= 128:
+        for i in range(args.warmup):
+            step_in_place(sets[i % L])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step_in_place(sets[i % L])
+        torch.cuda.synchronize()
+        ip_step_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        ip_attn_ms = timed(attend_in_place, args.steps)
+        ip_fresh_ms = timed(lambda s: mpic.mpic_assemble_kv_parts(ctx_lz.handle, plan_lz.handle, None, s["fk"], s["fv"], s["k_ctx"],
+                                                                  s["v_ctx"], mpic.MPIC_PART_FRESH, stream), args.steps)
+        blocks = plan_lz.get("key_blocks_%d" % (args.attn_block_keys or 96))
+        in_place = {"ms_per_step": round(ip_step_ms, 5), "attention_ms": round(ip_attn_ms, 5), "fresh_rows_ms": round(ip_fresh_ms, 5),
+                    "padding_keys_pct": round(100.0 * (len(blocks) * (args.attn_block_keys or 96) / max(1, n_ctx) - 1.0), 3),
+                    "note": "lazy_rope context: fresh rows scattered into the context, stored rows read where their caches are "
+                            "stored, queries turned back per chunk instance; same outputs as the linked step within the gates"}
+
     # ---- clocks while the attention kernel runs back to back (the 2.5 PFLOP/s peak is a 2.4 GHz
     # figure; what the part holds under this load says how much of the gap is clock) ----
     device_state = None
@@ -552,6 +588,10 @@ def main():
         "decode_step": {"ms": round(dec_ms, 5), "GBps": round(dec_gbs, 2), "pct_hbm_peak": round(100 * dec_gbs / PEAK_HBM_GBS, 3),
                         "bytes": dec_bytes, "note": "one query per request over the linked context plus itself; two launches"},
         "k_distance": kd,
+        "in_place_step": None if in_place is None else dict(
+            in_place, TFLOPs=round(attn_flops / (in_place["ms_per_step"] * 1e-3) / 1e12, 3),
+            attention_TFLOPs=round(attn_flops / (in_place["attention_ms"] * 1e-3) / 1e12, 3),
+            linking_bytes_per_step_linked=asm_bytes, linking_bytes_per_step_in_place=4.0 * n_q * row_bytes),
         "other_schedule_step_ms": None if other_ms is None else round(other_ms, 5),
         "graph_replay_step_ms": round(graph_ms, 5),
         "plan_ms": round(plan_ms, 4),

@@ -202,9 +202,11 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
   // holds coordinates d = 16*ks + 8*hi + e: a rotate-half pair (d, d + 64) is (qf[ks],
   // qf[ks + 4]) element by element, an interleaved pair (2i, 2i + 1) is two neighbouring
   // elements of one fragment.
-  auto load_q = [&](int inst) __attribute__((always_inline)) {
+  auto fetch_q = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16 + hi * 8);
+  };
+  auto turn_q = [&](int inst) __attribute__((always_inline)) {
     const bool fwd = a.q_rot != nullptr;
     const bool back = kLazy && inst >= 0;
     if (!fwd && !back) return;
@@ -279,7 +281,8 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
   };
   int q_inst = kLazy ? desc_of(0).inst : -1;  // the instance whose shift qf is turned back by
   if constexpr (kLazy) {
-    load_q(q_inst);
+    fetch_q();
+    turn_q(q_inst);
   } else {
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16 + hi * 8);
@@ -336,8 +339,7 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
   constexpr int kLoadPairs = ROWS_LOADED_PER_WAVE / 4;
   struct RowOffs {
     u32x4_a4 q[kLoadPairs];
-    const char* kb;  // lazy: where the block's rows are stored (context or the chunk's cache)
-    const char* vb;
+    int inst;  // lazy: the chunk instance that stores the block's rows, -1 = the context
   };
   auto fetch_rows = [&](int blk) {
     blk = blk < n_iter ? blk : n_iter - 1;
@@ -346,12 +348,7 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
     RowOffs r;
 #pragma unroll
     for (int p = 0; p < kLoadPairs; ++p) r.q[p] = src[p];
-    if constexpr (kLazy) {
-      const int inst = desc_of(blk).inst;
-      const bool in_ctx = inst < 0 || !extra.by_ref;
-      r.kb = (in_ctx ? static_cast<const char*>(a.k_ctx) : static_cast<const char*>(extra.k[inst])) + g * ROW_BYTES;
-      r.vb = (in_ctx ? static_cast<const char*>(a.v_ctx) : static_cast<const char*>(extra.v[inst])) + g * ROW_BYTES;
-    }
+    if constexpr (kLazy) r.inst = extra.by_ref ? desc_of(blk).inst : -1;
     return r;
   };
   // `ro` holds the offsets of the block whose loads go out next.  It is refilled at the start
@@ -359,6 +356,9 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
   // shares its counter with the LDS reads and returns out of order, so whatever waits on
   // that counter next (the first fragment reads of a matrix part, a barrier) waits for it.
   RowOffs ro = fetch_rows(0);
+  int ld_inst = -1;  // lazy: the source the loader's base addresses point to
+  const char* ld_kb = kbase;
+  const char* ld_vb = vbase;
   auto issue_loads = [&](int blk) {
     const RowOffs cur = ro;
     // the loads go out back to back, each from its own address registers; this lane's row of
@@ -368,12 +368,17 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
     const uint32_t dv = lds_base + v_slot_off(blk) + row0 * ROW_BYTES;
     const void* gk[kLoadPairs];
     const void* gv[kLoadPairs];
-    const char* kb = kbase;
-    const char* vb = vbase;
     if constexpr (kLazy) {
-      kb = cur.kb;
-      vb = cur.vb;
+      // the base of the rows changes only where the source does: the two table entries are
+      // read then, not per block (a scalar load that the next instructions wait for)
+      if (cur.inst != ld_inst) {
+        ld_inst = cur.inst;
+        ld_kb = (ld_inst < 0 ? static_cast<const char*>(a.k_ctx) : static_cast<const char*>(extra.k[ld_inst])) + g * ROW_BYTES;
+        ld_vb = (ld_inst < 0 ? static_cast<const char*>(a.v_ctx) : static_cast<const char*>(extra.v[ld_inst])) + g * ROW_BYTES;
+      }
     }
+    const char* kb = kLazy ? ld_kb : kbase;
+    const char* vb = kLazy ? ld_vb : vbase;
 #pragma unroll
     for (int p = 0; p < kLoadPairs; ++p) {
       const uint32_t r = (cur.q[p][0] & sel0) | (cur.q[p][1] & sel1) | (cur.q[p][2] & sel2) | (cur.q[p][3] & sel3);
@@ -594,9 +599,10 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
     if (do_qk) {
       if (do_pv) pv_block(t - 1);
       if constexpr (kLazy) {
-        if (inst != q_inst) {  // the keys of this block lack another shift than the last one's
-          __builtin_amdgcn_sched_barrier(0);  // (keeps the reload out of the matrix parts around it)
-          load_q(inst);
+        if (inst != q_inst) {  // the keys of this block lack another shift than the last one's:
+          // the fragments were fetched again during the softmax phase before, now they are turned
+          __builtin_amdgcn_sched_barrier(0);  // (keeps the rotation out of the matrix parts around it)
+          turn_q(inst);
           q_inst = inst;
           __builtin_amdgcn_sched_barrier(0);
         }
@@ -609,39 +615,47 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
   };
   if constexpr (kLazy) {
     // the same two loops over the tile's key blocks: a block is needed while its first position
-    // is within the wave's reach; its descriptor is fetched one step ahead, at the start of the
-    // softmax phase like the row offsets
-    KeyBlock cur = desc_of(0);
+    // is within the wave's reach.  Descriptors are fetched two steps ahead at the start of the
+    // softmax phase, like the row offsets, so that nothing waits for a scalar load.  When the
+    // keys of the next block lack another shift than the query fragments are turned back by,
+    // the fragments are fetched again during the softmax phase (their registers are idle until
+    // the next matrix part, which then turns them before its first product).
     bool prev_needed = false;
     if (gp == 0) {
+      KeyBlock cur = desc_of(0), nxt = desc_of(1);
       for (int t = 0; t <= n_iter; ++t) {
         const bool needed = t < n_iter && cur.pos0 <= wave_hi_pos;
         even_sync(t);
         matrix_part(t, needed, prev_needed, cur.inst);
         __syncthreads();  // odd half step 2t+1
         ro = fetch_rows(t + AHEAD + 1);
-        const KeyBlock nxt = desc_of(t + 1);
+        const KeyBlock nxt2 = desc_of(t + 2);
+        if (t + 1 < n_iter && nxt.pos0 <= wave_hi_pos && nxt.inst != q_inst) fetch_q();
         if (needed) {
           kd = cur;
           softmax_block(t);
         }
         prev_needed = needed;
         cur = nxt;
+        nxt = nxt2;
       }
     } else {
+      KeyBlock sm = desc_of(0), nxt = desc_of(0);  // block of the softmax phase, of the matrix part after it
       for (int t = 0; t <= n_iter; ++t) {
         even_sync(t);
         ro = fetch_rows(t + AHEAD + 1);
-        const KeyBlock nxt = desc_of(t);
+        const KeyBlock nxt2 = desc_of(t + 1);
+        const bool needed = t < n_iter && nxt.pos0 <= wave_hi_pos;
+        if (needed && nxt.inst != q_inst) fetch_q();
         if (prev_needed) {
-          kd = cur;
+          kd = sm;
           softmax_block(t - 1);
         }
         __syncthreads();  // odd half step 2t+1
-        cur = nxt;
-        const bool needed = t < n_iter && cur.pos0 <= wave_hi_pos;
-        matrix_part(t, needed, prev_needed, cur.inst);
+        matrix_part(t, needed, prev_needed, nxt.inst);
         prev_needed = needed;
+        sm = nxt;
+        nxt = nxt2;
       }
     }
   } else {
