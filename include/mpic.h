@@ -564,7 +564,9 @@ int mpic_store_layer(mpic_store* store, uint64_t id, int32_t layer, mpic_chunk_s
  * fresh rows and attention run on `stream`, joined by events.  When every cache the plan
  * reads is in GPU memory there is nothing to fetch ahead: the stored rows of layer l+1 are
  * then linked by the attention launch of layer l (mpic_selective_attn_link_next), all on
- * `stream`.  The call returns when everything is enqueued; the host thread waits only for
+ * `stream`.  On a lazy_rope context such caches are not linked at all but read in place
+ * (mpic_selective_attn_in_place): the context buffers then receive the fresh rows only;
+ * caches of the other tiers are linked as stored.  The call returns when everything is enqueued; the host thread waits only for
  * file reads.
  * failed: [n_srcs] or NULL; on MPIC_ERR_CACHE_MISS failed[s] = 1 for every source whose
  * cache is missing from the store or failed to load.  Missing caches and unreadable or

@@ -642,6 +642,22 @@ int prefill_layers(mpic_ctx* ctx, mpic_plan* plan, mpic_store* st, const uint64_
   // 2.22 ms per layer for 8 requests x 16 chunks, while a 75K-token request gains from the fused
   // launch, 3.56 ms against 3.60 ms.  A context buffer shared by consecutive layers cannot be
   // written while it is read: those layers are linked by a launch of their own.
+  // lazy_rope context with every cache in GPU memory: the caches are linked by reference.  No
+  // stored row is copied; each layer is the scatter of its fresh rows and an attention launch
+  // that reads the caches where the store keeps them.
+  if (ctx->cfg.lazy_rope && rows_stored == 0 && n_inst <= static_cast<size_t>(mpic::kMaxInstPerLaunch)) {
+    for (int32_t l = 0; l < n_layers; ++l) {
+      fill_srcs(l, srcs);
+      rc = mpic::assemble_parts(ctx, plan, nullptr, 0, fresh_k[l], fresh_v[l], n_fresh_rows, k_ctx[l], v_ctx[l],
+                                n_ctx_slots, MPIC_PART_FRESH, stream);
+      if (rc != MPIC_OK) return rc;
+      const mpic::SrcRefs refs{srcs.data(), n_srcs};
+      rc = mpic::attend(ctx, plan, fresh_q[l], n_fresh_rows, k_ctx[l], v_ctx[l], n_ctx_slots, softmax_scale, out[l],
+                        lse ? lse[l] : nullptr, stream, nullptr, 0, &refs);
+      if (rc != MPIC_OK) return rc;
+    }
+    return MPIC_OK;
+  }
   if (rows_stored == 0 && mpic::can_link_in_attention(ctx, plan) && mpic::link_fits_attention_tail(ctx, plan)) {
     std::vector<mpic_chunk_src> next_srcs(std::max(n_srcs, 0));
     const size_t ctx_bytes = static_cast<size_t>(n_ctx_slots) * st->row_bytes;

@@ -176,7 +176,7 @@ class LayeredProblem:
     oracle.store.ChunkStore on the oracle side, both filled with the same seeded bytes)."""
 
     def __init__(self, cfg_id, n_layers, tiers, disk_dir, *, k=None, paged=None, io_threads=0, id_base=1000,
-                 custom=None, interleaved=False, pre_rope=False, **layout_kw):
+                 custom=None, interleaved=False, pre_rope=False, lazy=False, **layout_kw):
         from oracle.store import ChunkStore
         self.sh = sh = workloads.shape(cfg_id)
         self.n_layers = n_layers
@@ -193,9 +193,9 @@ class LayeredProblem:
             self.n_slots = max(1, sum(lens))
         self.ids = [id_base + s for s in range(self.n_src)]
         dt = mpic.MPIC_F32 if sh.dtype == "f32" else mpic.MPIC_BF16
-        self.interleaved, self.pre_rope = interleaved, pre_rope
+        self.interleaved, self.pre_rope, self.lazy = interleaved, pre_rope, lazy
         self.ctx = mpic.Context(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, dt, sh.rope_theta, int(interleaved),
-                                self.page_size, int(pre_rope))
+                                self.page_size, int(pre_rope), int(lazy))
         self.store = mpic.Store(self.ctx, n_layers, None if disk_dir is None else str(disk_dir), io_threads)
         self.model = ChunkStore()
         self.raw = {}

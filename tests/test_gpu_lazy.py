@@ -205,3 +205,37 @@ def test_lazy_rejections():
     K_ref, V_ref = q.oracle_link()
     O_ref, L_ref = q.oracle_attend(K_ref, V_ref)
     _check_outputs(q, O_ref, L_ref)
+
+
+def test_lazy_layers_through_the_pipeline(tmp_path):
+    """mpic_prefill_layers on a lazy_rope context.  Caches in the HBM tier are linked by reference:
+    the context receives the fresh rows only.  Caches in the host and disk tiers are linked as
+    stored (read over the bus, copied unrotated).  Outputs at the gates of the oracle either way."""
+    from helpers import LayeredProblem
+    HBM, HOST, DISK = mpic.MPIC_TIER_HBM, mpic.MPIC_TIER_HOST, mpic.MPIC_TIER_DISK
+    small = dict(n_chunks=3, chunk_len=300, text_len=24, batch=2)
+    for tiers in ((HBM,), (HOST, DISK), (HBM, HOST)):
+        p = LayeredProblem(3, 3, tiers, tmp_path if DISK in tiers else None, lazy=True, **small)
+        p.plan_for()
+        assert p.gpu_run() is None
+        ref = p.oracle_run()
+        p.check(ref, kv_layers=[])                      # outputs and log-sum-exp of every layer
+        slots = torch.from_numpy(p.oplan["dst_slot"].astype(np.int64)).to(p.k_ctx[0].device)
+        stored = torch.from_numpy(p.oplan["src_inst"] >= 0).to(slots.device)
+        for l in range(p.n_layers):
+            K, V, _, _ = ref[l]
+            k_log, v_log = p.k_ctx[l][slots], p.v_ctx[l][slots]
+            assert np.array_equal(v_log[~stored].to(torch.float64).cpu().numpy(), V[~stored.cpu().numpy()])
+            assert np.array_equal(k_log[~stored].to(torch.float64).cpu().numpy(), K[~stored.cpu().numpy()])
+            if tiers == (HBM,):
+                assert torch.isnan(k_log[stored].float()).all() and torch.isnan(v_log[stored].float()).all(), \
+                    "caches in GPU memory are linked by reference: their rows must not be copied"
+            else:
+                assert np.array_equal(v_log[stored].to(torch.float64).cpu().numpy(), V[stored.cpu().numpy()])
+                # stored keys as stored: row t of its cache, layer l
+                inst = p.oplan["src_inst"]
+                for g in np.nonzero(inst >= 0)[0][::17]:
+                    s_ = int(p.oplan["inst_src"][inst[g]])
+                    want = p.raw[s_][0][l][int(p.oplan["src_row"][g])]
+                    assert torch.equal(k_log[g].cpu().view(torch.int16), want.view(torch.int16))
+        p.close()
