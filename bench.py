@@ -52,6 +52,11 @@ def parse():
     ap.add_argument("--pipeline-tiers", default="disk,host,hbm",
                     help="tiers the mpic_prefill_layers leg is timed from, in this order (hbm alone needs no disk directory)")
     ap.add_argument("--disk-dir", default=None, help="directory of the store's disk tier (default: a temporary one)")
+    ap.add_argument("--mfma-ceiling", action="store_true",
+                    help="also regenerate the ablation table: the bf16 attention launch of this workload timed with parts of "
+                         "its inner loop left out (timing-only kernel variants that only the probe library contains)")
+    ap.add_argument("--no-sustained-probe", action="store_true",
+                    help="skip the matrix-core probe (sustained bf16 MFMA rate of this GPU with register operands)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain elementwise copy of 512 MiB (reads and writes 512 MiB per "
                          "launch): the reference dispatch for scaling hardware traffic counters")
@@ -93,6 +98,109 @@ def sample_clocks_under_load(run, seconds=3.0):
     return {"sclk_mhz_under_attention": int(sclk.group(1)), "mclk_mhz": int(mclk.group(1)) if mclk else None,
             "power_cap_w": float(cap.group(1)) if cap else None, "sclk_mhz_of_the_peak_figure": 2400,
             "source": "rocm-smi --showclocks --showmaxpower, sampled while the attention kernel ran back to back"}
+
+
+def probe_lib_path():
+    return os.path.join(ROOT, "paper_2502_01960_amd", "libmpic_probe.so")
+
+
+def sustained_mfma(torch, dev, with_clock):
+    """Sustained bf16 matrix-core rate of this GPU: 48 v_mfma_f32_32x32x16_bf16 per wavefront and block on
+    register operands (random values), 8 wavefronts per workgroup, one workgroup per compute unit;
+    alone, in the kernel's ping-pong schedule, and with the softmax work on the vector ALU beside it."""
+    import ctypes as C
+    if not os.path.exists(probe_lib_path()):
+        return None
+    lib = C.CDLL(probe_lib_path())
+    lib.mpic_probe_mfma.argtypes = [C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_double)]
+    lib.mpic_probe_mfma.restype = C.c_int
+    gen = torch.Generator(device=dev).manual_seed(0x4D504943)
+    seed = torch.randn((64 * 16 * 8,), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    n_wgs = 256 * 4
+    sink = torch.empty((n_wgs * 512,), dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream()
+    fl = C.c_double()
+    out = {"note": "probe: 48 v_mfma_f32_32x32x16_bf16 per wavefront and block on register operands (random bf16), 8 wavefronts "
+                   "per workgroup, one workgroup per compute unit, 4 workgroups per unit in sequence",
+           "peak_TFLOPs": PEAK_BF16_TFLOPS}
+
+    zeros = torch.zeros_like(seed)
+
+    def run(flags, n_blocks, operands=seed):
+        rc = lib.mpic_probe_mfma(flags, n_wgs, n_blocks, C.c_void_p(operands.data_ptr()), C.c_void_p(sink.data_ptr()),
+                                 C.c_void_p(stream.cuda_stream), C.byref(fl))
+        assert rc == 0, rc
+
+    # the same instruction stream on operands that are all zero: nothing toggles in the data paths, so
+    # what this run gains over "mfma_only" is what the power management takes from random operands
+    for name, flags, ops in (("mfma_only", 0, seed), ("mfma_pingpong", 1, seed), ("mfma_pingpong_softmax", 3, seed),
+                             ("mfma_only_zero_operands", 0, zeros)):
+        n_blocks = 300
+        run(flags, n_blocks, ops)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(10):
+            run(flags, n_blocks, ops)
+        e1.record(stream)
+        e1.synchronize()
+        ms = e0.elapsed_time(e1) / 10
+        out[name + "_TFLOPs"] = round(fl.value * n_wgs * n_blocks / (ms * 1e-3) / 1e12, 2)
+        if with_clock and flags in (0, 3):
+            st = sample_clocks_under_load(lambda: run(flags, n_blocks, ops), seconds=2.0)
+            if st:
+                out[name + "_sclk_mhz"] = st["sclk_mhz_under_attention"]
+    return out
+
+
+def ablation_table(args, torch, dev, sh, requests, tables, pool, n_slots, n_q, attn_flops):
+    """The bf16 attention launch of this workload timed with parts of its inner loop left out: timing-only
+    kernel variants that only the probe library contains.  It is loaded beside the product library through a
+    second instance of the binding module (same process: a second process on the GPU would halve both)."""
+    import importlib.util
+    if not os.path.exists(probe_lib_path()):
+        return None
+    spec = importlib.util.spec_from_file_location("mpic_probe_binding", os.path.join(ROOT, "paper_2502_01960_amd", "binding.py"))
+    pb = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(pb)
+    pb.lib_path = probe_lib_path
+    ctx = pb.Context(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, pb.MPIC_BF16, sh.rope_theta, 0, sh.page_size)
+    ctx.set_option(pb.MPIC_OPT_ATTN_BLOCK_KEYS, args.attn_block_keys or 96)
+    plan = pb.Plan(ctx, requests, sh.default_k, tables, pool)
+    gen = torch.Generator(device=dev).manual_seed(0x4D504943)
+    draw = lambda *shape: torch.randn(shape, generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    sets = []
+    for _ in range(max(2, args.layers)):
+        q = draw(n_q, sh.n_q_heads, sh.head_dim)
+        sets.append((q, draw(n_slots, sh.n_kv_heads, sh.head_dim), draw(n_slots, sh.n_kv_heads, sh.head_dim), torch.empty_like(q)))
+    stream = torch.cuda.current_stream()
+
+    def run(i):
+        q, k, v, o = sets[i % len(sets)]
+        pb.mpic_selective_attn(ctx.handle, plan.handle, q, k, v, sh.softmax_scale, o, None, stream)
+    run(0)     # uploads the plan
+    names = {0: "whole kernel", 1: "without the K/V loads", 2: "without the LDS fragment reads", 4: "without the softmax",
+             3: "without loads and LDS reads", 5: "without loads and softmax", 6: "without LDS reads and softmax",
+             7: "matrix instructions, barriers and the ping-pong skeleton only"}
+    out = {}
+    for mask in (0, 1, 2, 4, 3, 5, 6, 7):
+        ctx.set_option(1000, mask)     # kProbeOptionAblate of the probe library
+        for i in range(args.warmup):
+            run(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for i in range(args.steps):
+            run(i)
+        e1.record(stream)
+        e1.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        out[names[mask]] = {"ms": round(ms, 5), "TFLOPs_of_the_whole_kernels_work": round(attn_flops / (ms * 1e-3) / 1e12, 2)}
+    out["note"] = ("timing-only variants of attn_bf16_kernel (probe library, same launch, random inputs drawn on the GPU); "
+                   "rates are the whole kernel's algorithmic flops over each variant's time")
+    plan.close()
+    ctx.close()
+    return out
 
 
 def main():
@@ -545,6 +653,13 @@ def main():
                    sample=f"requests 0..{n_req - 1} of the batch: float64 link of all rows + attention of "
                           f"{'every' if every == 1 else f'every {every}th'} fresh row, all heads")
 
+    # ---- what the matrix cores sustain on this GPU with nothing in their way, and (on request) the
+    # attention launch with parts of its inner loop left out ----
+    sustained = None if args.no_sustained_probe else sustained_mfma(torch, dev, not args.no_device_state)
+    ablation = None
+    if args.mfma_ceiling:
+        ablation = ablation_table(args, torch, dev, sh, requests, tables, pool, n_slots, n_q, attn_flops)
+
     traffic = None
     tfile = os.path.join(ROOT, "profiles", "attn_traffic.json")
     if os.path.exists(tfile):
@@ -578,7 +693,13 @@ def main():
                      # HBM-side bytes per launch (FETCH_SIZE + WRITE_SIZE, scaled by the copy calibration)
                      "traffic": traffic["total_bytes"] if traffic else None, "traffic_detail": traffic,
                      "kernel": "attn_bf16_kernel<%d keys per block>" % (64 if not (fuse or L < 2) else args.attn_block_keys or 96),
-                     "avg_launch_ms": round(attn_ms, 5)},
+                     "avg_launch_ms": round(attn_ms, 5),
+                     # beside frac, never instead of it: the same rate against what this GPU's matrix cores sustain
+                     "sustained": sustained,
+                     "frac_of_sustained_mfma": None if not sustained else round(attn_tflops / sustained["mfma_only_TFLOPs"], 5),
+                     "frac_of_sustained_mfma_with_softmax_mix": None if not sustained else
+                     round(attn_tflops / sustained["mfma_pingpong_softmax_TFLOPs"], 5),
+                     "ablation": ablation},
         "cpu_baseline": cpu,
         "attention": {"ms": round(attn_ms, 5), "ms_median": round(float(np.median(attn_each)), 5),
                       "ms_min": round(float(attn_each.min()), 5), "TFLOPs": round(attn_tflops, 3),

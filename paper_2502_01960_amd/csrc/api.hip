@@ -555,6 +555,7 @@ int mpic::attend(mpic_ctx* ctx, mpic_plan* plan, const void* fresh_q,
   a.q_cos = plan->dev.fresh_cos;
   a.q_sin = plan->dev.fresh_sin;
   a.interleaved = c.rope_interleaved;
+  a.ablate = ctx->attn_ablate;
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   if (lazy) {
     mpic::LazyRefs lr;
@@ -767,6 +768,12 @@ extern "C" int mpic_set_option(mpic_ctx* ctx, int32_t option, int64_t value) {
       if (value != 0 && value != 64 && value != 96) return fail(ctx, MPIC_ERR_INVALID, "set_option: attention block must be 0, 64 or 96 keys");
       ctx->attn_block_keys = static_cast<int32_t>(value);
       return MPIC_OK;
+#ifdef MPIC_PROBE_BUILD
+    case mpic::kProbeOptionAblate:  // probe library only: timing runs of the bf16 kernel with parts left out
+      if (value < 0 || value > 7) return fail(ctx, MPIC_ERR_INVALID, "set_option: ablation mask must be 0..7");
+      ctx->attn_ablate = static_cast<int32_t>(value);
+      return MPIC_OK;
+#endif
     default:
       return fail(ctx, MPIC_ERR_INVALID, "set_option: unknown option");
   }

@@ -125,7 +125,7 @@ __device__ inline void link_share(const LinkNext& ln, int j) {
   }
 }
 
-template <int kBlockKeys, typename Extra>
+template <int kBlockKeys, typename Extra, int kAblate = 0>
 __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra extra) {
   using G = Geo<kBlockKeys>;
   constexpr int BN = G::BN, KB = G::KB, TILE_BYTES = G::TILE_BYTES, AHEAD = G::AHEAD;
@@ -437,9 +437,11 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
   bf16x8 pf[2 * KB] = {};
 
   auto k_frag = [&](const char* stage, int kb, int ks) {
+    if constexpr ((kAblate & kAblateLdsReads) != 0) return qf[(ks + kb) & 7];  // timing-only variant
     return *reinterpret_cast<const bf16x8*>(stage + k_row_off + kb * 32 * ROW_BYTES + ((k_col_x ^ (ks << 1)) << 4));
   };
   auto v_frag = [&](const char* stage, int kh, int db) {
+    if constexpr ((kAblate & kAblateLdsReads) != 0) return qf[(kh + db) & 7];  // timing-only variant
     const char* vp = stage + v_off + kh * 16 * ROW_BYTES + ((v_col_x ^ (db << 2)) << 4);
     const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(MPIC_LDS_PTR(s16x4, vp));
     const s16x4 up = __builtin_amdgcn_ds_read_tr16_b64_v4i16(MPIC_LDS_PTR(s16x4, vp + 8 * ROW_BYTES));
@@ -494,6 +496,17 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
   // softmax of block t: S^T (acc_s) -> P^T (pf), running sum and reference maximum
   KeyBlock kd{};  // lazy: descriptor of the block softmax_block works on
   auto softmax_block = [&](int t) {
+    if constexpr ((kAblate & kAblateSoftmax) != 0) {  // timing-only variant: the products stay connected, nothing else
+#pragma unroll
+      for (int i = 0; i < 2 * KB; ++i) {
+        const f32x4 raw = {acc_s[i / 2][(i & 1) * 8], acc_s[i / 2][(i & 1) * 8 + 1], acc_s[i / 2][(i & 1) * 8 + 2],
+                           acc_s[i / 2][(i & 1) * 8 + 3]};
+        pf[i] = __builtin_bit_cast(bf16x8, raw);
+      }
+      m_run = 0.f;
+      l_run += 1.f;
+      return;
+    }
     if constexpr (kLazy) {
       // keys of the block sit at positions pos0 .. pos0 + n_valid - 1; slots behind them are
       // padding; masked on blocks with padding and on the diagonal blocks
@@ -590,7 +603,11 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
       }
     }
     __syncthreads();
-    if (t + AHEAD < n_iter) issue_loads(t + AHEAD);
+    if constexpr ((kAblate & kAblateLoads) != 0) {  // timing-only variant: the rings are filled once
+      if (t + AHEAD < n_iter && t + AHEAD < G::K_SLOTS + G::V_SLOTS) issue_loads(t + AHEAD);
+    } else {
+      if (t + AHEAD < n_iter) issue_loads(t + AHEAD);
+    }
   };
   // matrix half step of block t: finish block t-1 (if this wave needed it), start block t (if it
   // needs it: blocks past the last key the wave can see are skipped; the barriers stay aligned)
@@ -775,6 +792,8 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
 
 namespace {
 
+inline int64_t n_pos_of(const AssembleArgs* next) { return next ? next->pos_end - next->pos_begin : 0; }
+
 template <int kBlockKeys>
 hipError_t launch_shape(const AttnArgs& a, const AssembleArgs* next, const AssembleSrcTable* next_tab,
                         const LazyRefs* lazy, int dev, hipStream_t stream) {
@@ -791,6 +810,32 @@ hipError_t launch_shape(const AttnArgs& a, const AssembleArgs* next, const Assem
                                hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES);
   });
   if (eo != hipSuccess) return eo;
+#ifdef MPIC_PROBE_BUILD
+  if (a.ablate != 0 && !lazy && n_pos_of(next) == 0) {
+    auto go = [&](auto mask) {
+      constexpr int kM = decltype(mask)::value;
+      static LdsOptIn probe_opt_in;
+      const hipError_t e = probe_opt_in.ensure(dev, [] {
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bf16_kernel<kBlockKeys, NoLink, kM>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES);
+      });
+      if (e != hipSuccess) return e;
+      hipLaunchKernelGGL((attn_bf16_kernel<kBlockKeys, NoLink, kM>), dim3(a.n_tiles), dim3(THREADS), G::LDS_BYTES, stream, a,
+                         NoLink{});
+      return hipSuccess;
+    };
+    switch (a.ablate) {
+      case 1: return go(std::integral_constant<int, 1>{});
+      case 2: return go(std::integral_constant<int, 2>{});
+      case 3: return go(std::integral_constant<int, 3>{});
+      case 4: return go(std::integral_constant<int, 4>{});
+      case 5: return go(std::integral_constant<int, 5>{});
+      case 6: return go(std::integral_constant<int, 6>{});
+      case 7: return go(std::integral_constant<int, 7>{});
+      default: return hipErrorInvalidValue;
+    }
+  }
+#endif
   if (lazy) {
     hipLaunchKernelGGL((attn_bf16_kernel<kBlockKeys, LazyRefs>), dim3(a.n_tiles), dim3(THREADS), G::LDS_BYTES, stream, a,
                        *lazy);

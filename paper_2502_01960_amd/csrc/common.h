@@ -102,6 +102,7 @@ struct mpic_ctx {
   // context has linked in the background: only that shape leaves registers for a wave of the
   // linking kernel beside it); 64 / 96 = fixed by mpic_set_option
   int32_t attn_block_keys = 0;
+  int32_t attn_ablate = 0;  // probe builds only, see kAblate*
   bool background_seen = false;
   // partial results of the decode step (one per key split), grown on demand
   void* decode_ws = nullptr;
@@ -239,7 +240,16 @@ struct AttnArgs {
   const int32_t* src_row;
   const float* rope_cos;
   const float* rope_sin;
+  int32_t ablate;  // probe builds only (kAblate*): parts of the bf16 kernel's inner loop that a timing run leaves out
 };
+// Timing-only variants of the bf16 attention kernel.  They exist only in the probe library
+// (built with -DMPIC_PROBE_BUILD next to the product library, which has none of them) and
+// compute nothing meaningful: each leaves one part of the inner loop out, with every access
+// still in bounds, so that the cost of that part can be read off the difference in run time.
+enum { kAblateLoads = 1,     // K/V blocks are staged only until every ring slot holds rows once
+       kAblateLdsReads = 2,  // operand fragments are taken from registers instead of LDS
+       kAblateSoftmax = 4 }; // no exponentials, sums or conversions between the two products
+constexpr int kProbeOptionAblate = 1000;  // mpic_set_option of the probe library: value = mask of kAblate*
 // Contexts with lazy_rope: stored keys are never turned to their global position.  The kernel
 // walks the request's key blocks (KeyBlock: all keys of a block come from consecutive rows of
 // one source and lack the same shift) and turns its *queries* back by that shift whenever the
