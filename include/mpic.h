@@ -136,12 +136,18 @@ enum {
   MPIC_PLAN_KEY_BLOCKS_32 = 16, /* lazy_rope contexts: [n_blocks][4] (first position, keys,    */
   MPIC_PLAN_KEY_BLOCKS_64 = 17, /* chunk instance or -1 = fresh rows, request): the keys of    */
   MPIC_PLAN_KEY_BLOCKS_96 = 18, /* every request cut into blocks of at most 32 / 64 / 96 keys  */
-                             /* that never straddle a change of source, request after request; */
-                             /* the decode kernel walks the first list, the two shapes of the  */
-                             /* attention kernel the others                                    */
-  MPIC_PLAN_LAZY_TILES_64 = 19, /* lazy_rope contexts: MPIC_PLAN_ATTN_TILES with (end key,     */
-  MPIC_PLAN_LAZY_TILES_96 = 20, /* first key) replaced by (end block, first block) counted     */
-                             /* from the request's first block of that list                    */
+                             /* that never straddle a change of source; request after request, */
+                             /* inside a request the blocks of fresh rows first, then those of */
+                             /* stored rows, each part in position order.  The decode kernel   */
+                             /* walks the first list, the two shapes of the attention kernel   */
+                             /* the others                                                     */
+  MPIC_PLAN_LAZY_TILES_64 = 19, /* lazy_rope contexts: [n_tiles][4] for every entry of         */
+  MPIC_PLAN_LAZY_TILES_96 = 20, /* MPIC_PLAN_ATTN_TILES the blocks it visits, as (f0, f1, s0,  */
+                             /* s1): fresh blocks f0..f1-1 and stored blocks s0..s1-1 of its   */
+                             /* request, counted inside their parts                            */
+  MPIC_PLAN_KEY_BLOCK_PARTS_32 = 21, /* lazy_rope contexts: [B][3] (first fresh block, first   */
+  MPIC_PLAN_KEY_BLOCK_PARTS_64 = 22, /* stored block, end) of every request in the list above  */
+  MPIC_PLAN_KEY_BLOCK_PARTS_96 = 23,
   MPIC_PLAN_ATTN_TILES = 14  /* [n_tiles][8] launch order of the attention kernel: (request,   */
                              /* kv head, first flattened row, rows, end key, first key, slot   */
                              /* of the partial result or -1, 0); flattened row = (fresh row -  */

@@ -14,7 +14,8 @@ MPIC_F32, MPIC_BF16 = 0, 1
 PLAN_FIELDS = dict(ctx_off=0, q_off=1, q_pos=2, q_req=3, slot_map=4, src_inst=5, src_row=6,
                    dst_slot=7, inst_src=8, inst_delta=9, inst_len=10, inst_k=11, inst_req=12,
                    runs=13, attn_tiles=14, launch_estimate=15, key_blocks_32=16, key_blocks_64=17,
-                   key_blocks_96=18, lazy_tiles_64=19, lazy_tiles_96=20)
+                   key_blocks_96=18, lazy_tiles_64=19, lazy_tiles_96=20, key_block_parts_32=21,
+                   key_block_parts_64=22, key_block_parts_96=23)
 
 
 class MpicError(RuntimeError):
@@ -223,10 +224,13 @@ def mpic_plan_get(plan, what):
     out = np.ctypeslib.as_array(p, shape=(n.value,)).copy() if n.value else np.zeros(0, np.int32)
     if code == PLAN_FIELDS["runs"]:
         out = out.reshape(-1, 4)
-    elif code in (PLAN_FIELDS["attn_tiles"], PLAN_FIELDS["lazy_tiles_64"], PLAN_FIELDS["lazy_tiles_96"]):
+    elif code == PLAN_FIELDS["attn_tiles"]:
         out = out.reshape(-1, 8)
-    elif code in (PLAN_FIELDS["key_blocks_32"], PLAN_FIELDS["key_blocks_64"], PLAN_FIELDS["key_blocks_96"]):
+    elif code in (PLAN_FIELDS["key_blocks_32"], PLAN_FIELDS["key_blocks_64"], PLAN_FIELDS["key_blocks_96"],
+                  PLAN_FIELDS["lazy_tiles_64"], PLAN_FIELDS["lazy_tiles_96"]):
         out = out.reshape(-1, 4)
+    elif code in (PLAN_FIELDS["key_block_parts_32"], PLAN_FIELDS["key_block_parts_64"], PLAN_FIELDS["key_block_parts_96"]):
+        out = out.reshape(-1, 3)
     return out
 
 

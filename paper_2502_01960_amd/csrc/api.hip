@@ -77,8 +77,8 @@ int upload_plan(mpic_ctx* ctx, mpic_plan* p) {
   const size_t o_tiles = put(p->tiles.data(), p->tiles.size() * sizeof(AttnTile));
   const size_t o_merges = put(p->merges.data(), p->merges.size() * sizeof(AttnMerge));
   // lazy_rope contexts: key blocks, their row-offset tables in both views, tiles in block indices
-  size_t o_kblk[kNumBlockSizes] = {}, o_first[kNumBlockSizes] = {}, o_vctx[kNumBlockSizes] = {},
-         o_vref[kNumBlockSizes] = {}, o_ltiles[kNumBlockSizes] = {};
+  size_t o_kblk[kNumBlockSizes] = {}, o_first[kNumBlockSizes] = {}, o_mid[kNumBlockSizes] = {}, o_vctx[kNumBlockSizes] = {},
+         o_vref[kNumBlockSizes] = {}, o_range[kNumBlockSizes] = {};
   const bool lazy = ctx->cfg.lazy_rope != 0;
   if (lazy) {
     for (int s = 0; s < kNumBlockSizes; ++s) {
@@ -100,7 +100,8 @@ int upload_plan(mpic_ctx* ctx, mpic_plan* p) {
       o_first[s] = put(p->kblk_first[s].data(), p->kblk_first[s].size() * 4);
       o_vctx[s] = put(vctx.data(), vctx.size() * 4);
       o_vref[s] = put(vref.data(), vref.size() * 4);
-      o_ltiles[s] = put(p->lazy_tiles[s].data(), p->lazy_tiles[s].size() * sizeof(AttnTile));
+      o_mid[s] = put(p->kblk_mid[s].data(), p->kblk_mid[s].size() * 4);
+      o_range[s] = put(p->lazy_range[s].data(), p->lazy_range[s].size() * 4);
     }
   }
   image.resize(image.size() + 256, 0);
@@ -139,7 +140,8 @@ int upload_plan(mpic_ctx* ctx, mpic_plan* p) {
       d.kblk_first[s] = reinterpret_cast<int32_t*>(base + o_first[s]);
       d.voff_ctx[s] = reinterpret_cast<uint32_t*>(base + o_vctx[s]);
       d.voff_ref[s] = reinterpret_cast<uint32_t*>(base + o_vref[s]);
-      d.lazy_tiles[s] = reinterpret_cast<AttnTile*>(base + o_ltiles[s]);
+      d.kblk_mid[s] = reinterpret_cast<int32_t*>(base + o_mid[s]);
+      d.lazy_range[s] = reinterpret_cast<int32_t*>(base + o_range[s]);
     }
   }
   d.block = base;
@@ -158,6 +160,8 @@ int fill_lazy_refs(mpic_ctx* ctx, const mpic_plan* plan, int bn, const SrcRefs* 
   LazyRefs r{};
   r.blocks = plan->dev.kblk[s];
   r.first = plan->dev.kblk_first[s];
+  r.mid = plan->dev.kblk_mid[s];
+  r.range = plan->dev.lazy_range[s];
   r.voff = refs ? plan->dev.voff_ref[s] : plan->dev.voff_ctx[s];
   r.rope_cos = plan->dev.rope_cos;
   r.rope_sin = plan->dev.rope_sin;
@@ -568,7 +572,6 @@ int mpic::attend(mpic_ctx* ctx, mpic_plan* plan, const void* fresh_q,
       a.rope_sin = plan->dev.rope_sin;
       MPIC_HIP(ctx, mpic::launch_attn_f32(a, plan->n_q, &lr, stream));
     } else {
-      a.tiles = plan->dev.lazy_tiles[mpic::block_size_index(a.block_keys)];
       MPIC_HIP(ctx, mpic::launch_attn_bf16(a, nullptr, nullptr, &lr, stream));
     }
     if (next)

@@ -155,13 +155,20 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
   // context row offsets in 16-byte units; read with scalar loads (the table is padded so
   // that reading up to 64 entries past the last key of the tile stays in bounds)
   const __attribute__((address_space(4))) uint32_t* off_of;
-  int vb0 = 0;  // lazy: this tile's first key block in the batch's list (its tile counts in blocks)
+  // lazy: the tile visits fresh blocks [fb, fb + nf) and then stored blocks [sb, sb + ns) of the
+  // batch's block list (its request's fresh part and stored part); step t of the walk is block bid(t)
+  int fb = 0, nf = 0, sb = 0, ns = 0;
   if constexpr (kLazy) {
-    vb0 = extra.first[b] + tile.key0;
-    off_of = (const __attribute__((address_space(4))) uint32_t*)(extra.voff + static_cast<int64_t>(vb0) * BN);
+    const i32x4 rg = *(const __attribute__((address_space(4))) i32x4*)(extra.range + 4 * static_cast<int64_t>(blockIdx.x));
+    fb = extra.first[b] + rg[0];
+    nf = rg[1] - rg[0];
+    sb = extra.mid[b] + rg[2];
+    ns = rg[3] - rg[2];
+    off_of = (const __attribute__((address_space(4))) uint32_t*)extra.voff;
   } else {
     off_of = (const __attribute__((address_space(4))) uint32_t*)(a.kv_off16 + a.ctx_off[b] + key0);
   }
+  auto bid = [&](int t) __attribute__((always_inline)) { return t < nf ? fb + t : sb + (t - nf); };
   const char* kbase = static_cast<const char*>(a.k_ctx) + g * ROW_BYTES;
   const char* vbase = static_cast<const char*>(a.v_ctx) + g * ROW_BYTES;
   const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(MPIC_LDS_PTR(char, lds)));
@@ -178,13 +185,13 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
   // (lazy: positions stay absolute, the blocks carry theirs; a piece owns whole blocks)
   const int my_pos = kLazy ? (valid ? a.q_pos[fresh_row] : 0x3fffffff)
                            : min(valid ? a.q_pos[fresh_row] - key0 : 0x7fffffff, n_keys - 1);
-  const int n_iter = kLazy ? tile.n_keys - tile.key0 : (n_keys + BN - 1) / BN;
+  const int n_iter = kLazy ? nf + ns : (n_keys + BN - 1) / BN;
   // descriptor of key block blk of this tile (lazy only; a scalar load)
   auto desc_of = [&](int blk) __attribute__((always_inline)) {
     blk = blk < n_iter ? blk : n_iter - 1;
     KeyBlock d{};
     if constexpr (kLazy) {
-      const i32x4 raw = *(const __attribute__((address_space(4))) i32x4*)(extra.blocks + vb0 + blk);
+      const i32x4 raw = *(const __attribute__((address_space(4))) i32x4*)(extra.blocks + bid(blk));
       d.pos0 = raw[0];
       d.n_valid = raw[1];
       d.inst = raw[2];
@@ -192,7 +199,8 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
     return d;
   };
   // does the row see any key of this tile (or piece)?
-  const int piece_pos0 = kLazy ? desc_of(0).pos0 : 0;
+  // first position of the tile (or piece): the smaller of its first fresh and first stored block's
+  const int piece_pos0 = kLazy ? min(desc_of(0).pos0, desc_of(nf < n_iter ? nf : 0).pos0) : 0;
   auto sees = [&]() { return my_pos >= piece_pos0; };
   const __bf16* qp = static_cast<const __bf16*>(a.q) + (fresh_row * a.n_q_heads + head) * D;
   bf16x8 qf[8];
@@ -343,8 +351,8 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
   };
   auto fetch_rows = [&](int blk) {
     blk = blk < n_iter ? blk : n_iter - 1;
-    const __attribute__((address_space(4))) u32x4_a4* src =
-        reinterpret_cast<const __attribute__((address_space(4))) u32x4_a4*>(off_of + blk * BN + wave * ROWS_LOADED_PER_WAVE);
+    const __attribute__((address_space(4))) u32x4_a4* src = reinterpret_cast<const __attribute__((address_space(4))) u32x4_a4*>(
+        off_of + (kLazy ? static_cast<int64_t>(bid(blk)) : static_cast<int64_t>(blk)) * BN + wave * ROWS_LOADED_PER_WAVE);
     RowOffs r;
 #pragma unroll
     for (int p = 0; p < kLoadPairs; ++p) r.q[p] = src[p];

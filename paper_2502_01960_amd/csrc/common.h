@@ -71,7 +71,8 @@ struct PlanDevice {
   int32_t* kblk_first[kNumBlockSizes] = {};   // [B+1] first block of each request
   uint32_t* voff_ctx[kNumBlockSizes] = {};    // [n_blocks * BN + pad] row offsets (16-byte units), every row in the context
   uint32_t* voff_ref[kNumBlockSizes] = {};    // the same with stored rows addressed inside their source
-  AttnTile* lazy_tiles[kNumBlockSizes] = {};  // tiles with (key0, n_keys) replaced by (first block, end block) of the request
+  int32_t* kblk_mid[kNumBlockSizes] = {};     // [B] first stored block of each request
+  int32_t* lazy_range[kNumBlockSizes] = {};   // [n_tiles][4] block ranges of every tile: fresh [f0, f1), stored [s0, s1)
   void* block = nullptr;  // the single allocation all of the above point into
   int device = -1;
 };
@@ -135,8 +136,10 @@ struct mpic_plan {
   // attention tiles in block indices (empty for the decode block size)
   std::vector<mpic::KeyBlock> kblk[mpic::kNumBlockSizes];
   std::vector<int32_t> kblk_first[mpic::kNumBlockSizes];
-  std::vector<mpic::AttnTile> lazy_tiles[mpic::kNumBlockSizes];
-  std::vector<int32_t> kblk_flat[mpic::kNumBlockSizes];  // the blocks as int32 quadruples, for mpic_plan_get
+  std::vector<int32_t> kblk_mid[mpic::kNumBlockSizes];    // [B] first stored block of every request (its fresh blocks come first)
+  std::vector<int32_t> lazy_range[mpic::kNumBlockSizes];  // [n_tiles][4] fresh blocks [f0, f1) and stored blocks [s0, s1) of every tile
+  std::vector<int32_t> kblk_flat[mpic::kNumBlockSizes];   // the blocks as int32 quadruples, for mpic_plan_get
+  std::vector<int32_t> kblk_parts[mpic::kNumBlockSizes];  // [B][3] first fresh block, first stored block, end, for mpic_plan_get
   std::vector<int32_t> fresh_rot;            // contexts with fresh_pre_rope only
   std::vector<float> fresh_cos, fresh_sin;   // one row per distinct position id
   mpic::PlanDevice dev;
@@ -258,7 +261,9 @@ constexpr int kProbeOptionAblate = 1000;  // mpic_set_option of the probe librar
 // or the chunk's cache itself when the caches are linked by reference.
 struct LazyRefs {
   const KeyBlock* blocks;  // key blocks of the batch for this kernel's block size
-  const int32_t* first;    // [B+1] first block of every request
+  const int32_t* first;    // [B+1] first block of every request (its fresh blocks, then its stored blocks)
+  const int32_t* mid;      // [B] first stored block of every request
+  const int32_t* range;    // [n_tiles][4] attention kernel: fresh blocks [f0, f1) and stored blocks [s0, s1) of every tile
   const uint32_t* voff;    // [n_blocks][BN] row offsets (16-byte units) from the block's base
   const float* rope_cos;   // [n_inst][D/2] cos / sin of every instance's shift
   const float* rope_sin;

@@ -256,7 +256,11 @@ void build_tiles(mpic_plan& p, int group, int n_kv_heads) {
 // Key blocks of a lazy_rope plan (see KeyBlock).  A block ends where the source of the keys
 // changes (next chunk instance, or stored rows <-> fresh rows), where a tile that was cut
 // along the keys starts a new piece (so that a piece owns whole blocks), and after BN keys.
-// The tiles are then restated in block indices of their request, once per kernel shape.
+// The list of a request holds its fresh blocks first and its stored blocks after them, each
+// part in position order: a kernel that walks a tile in list order changes the shift its
+// queries are turned back by once per chunk instance instead of twice (softmax does not care
+// about the order of the keys; the mask goes by the positions the blocks carry).  The tiles are
+// restated as two ranges of block indices, once per kernel shape.
 void build_key_blocks(mpic_plan& p) {
   const int B = p.n_requests;
   std::vector<std::vector<int32_t>> cuts(B);
@@ -270,10 +274,15 @@ void build_key_blocks(mpic_plan& p) {
     const int32_t bn = kBlockSizes[s];
     auto& blocks = p.kblk[s];
     auto& first = p.kblk_first[s];
+    auto& mid = p.kblk_mid[s];
     blocks.clear();
     first.assign(1, 0);
+    mid.clear();
+    std::vector<KeyBlock> fresh, stored;
     for (int b = 0; b < B; ++b) {
       const int32_t ctx0 = p.ctx_off[b], n = p.ctx_off[b + 1] - ctx0;
+      fresh.clear();
+      stored.clear();
       size_t next_cut = 0;
       for (int32_t pos = 0; pos < n;) {
         while (next_cut < cuts[b].size() && cuts[b][next_cut] <= pos) ++next_cut;
@@ -281,29 +290,36 @@ void build_key_blocks(mpic_plan& p) {
         const int32_t inst = p.src_inst[ctx0 + pos];
         int32_t end = pos + 1;
         while (end < limit && p.src_inst[ctx0 + end] == inst) ++end;
-        for (int32_t q = pos; q < end; q += bn) blocks.push_back(KeyBlock{q, std::min(bn, end - q), inst, b});
+        for (int32_t q = pos; q < end; q += bn) (inst < 0 ? fresh : stored).push_back(KeyBlock{q, std::min(bn, end - q), inst, b});
         pos = end;
       }
+      blocks.insert(blocks.end(), fresh.begin(), fresh.end());
+      mid.push_back(static_cast<int32_t>(blocks.size()));
+      blocks.insert(blocks.end(), stored.begin(), stored.end());
       first.push_back(static_cast<int32_t>(blocks.size()));
     }
     p.kblk_flat[s].resize(blocks.size() * 4);
     if (!blocks.empty()) std::memcpy(p.kblk_flat[s].data(), blocks.data(), blocks.size() * sizeof(KeyBlock));
-    p.lazy_tiles[s].clear();
+    p.lazy_range[s].clear();
     if (bn == 32) continue;  // the decode kernel splits its blocks at launch
-    // block that holds position `pos` of request b, relative to the request's first block
-    auto block_of = [&](int b, int32_t pos) {
-      const KeyBlock* lo = blocks.data() + first[b];
-      const KeyBlock* hi = blocks.data() + first[b + 1];
-      const KeyBlock* it = std::upper_bound(lo, hi, pos, [](int32_t v, const KeyBlock& k) { return v < k.pos0; });
-      return static_cast<int32_t>(it - lo) - 1;
+    // blocks of [lo, hi) whose first position is below `pos` (the parts are in position order)
+    auto below = [&](int32_t lo, int32_t hi, int32_t pos) {
+      const KeyBlock* it = std::lower_bound(blocks.data() + lo, blocks.data() + hi, pos,
+                                            [](const KeyBlock& k, int32_t v) { return k.pos0 < v; });
+      return static_cast<int32_t>(it - (blocks.data() + lo));
     };
-    p.lazy_tiles[s] = p.tiles;
-    for (AttnTile& t : p.lazy_tiles[s]) {
-      if (t.n_rows <= 0) continue;
-      const int32_t b0 = block_of(t.req, t.key0);  // key0 is a block start: 0 or a cut
-      const int32_t b1 = block_of(t.req, t.n_keys - 1) + 1;
-      t.key0 = b0;
-      t.n_keys = b1;
+    // per tile: fresh blocks [f0, f1) and stored blocks [s0, s1), counted inside their parts.  A
+    // piece starts at a forced block boundary, so every block with a first position in
+    // [first key, end key) belongs to it, and only those
+    p.lazy_range[s].reserve(p.tiles.size() * 4);
+    for (const AttnTile& t : p.tiles) {
+      if (t.n_rows <= 0) {
+        p.lazy_range[s].insert(p.lazy_range[s].end(), {0, 0, 0, 0});
+        continue;
+      }
+      const int32_t f_lo = first[t.req], f_hi = mid[t.req], s_hi = first[t.req + 1];
+      p.lazy_range[s].insert(p.lazy_range[s].end(), {below(f_lo, f_hi, t.key0), below(f_lo, f_hi, t.n_keys),
+                                                      below(f_hi, s_hi, t.key0), below(f_hi, s_hi, t.n_keys)});
     }
   }
 }
@@ -561,7 +577,14 @@ extern "C" int mpic_plan_create_selected(mpic_ctx* ctx, int32_t n_requests, cons
       }
     if (ctx->cfg.fresh_pre_rope) mpic::build_fresh_rope(*p, ctx->cfg);
     mpic::build_tiles(*p, ctx->group, ctx->cfg.n_kv_heads);
-    if (ctx->cfg.lazy_rope) mpic::build_key_blocks(*p);
+    if (ctx->cfg.lazy_rope) {
+      mpic::build_key_blocks(*p);
+      for (int s = 0; s < mpic::kNumBlockSizes; ++s) {
+        p->kblk_parts[s].clear();
+        for (int b = 0; b < n_requests; ++b)
+          p->kblk_parts[s].insert(p->kblk_parts[s].end(), {p->kblk_first[s][b], p->kblk_mid[s][b], p->kblk_first[s][b + 1]});
+      }
+    }
     {
       auto clamp = [](int64_t x) { return static_cast<int32_t>(std::min<int64_t>(x, INT32_MAX)); };
       p->launch_est = {clamp(p->est_makespan_blocks), clamp(p->est_idle_blocks),
@@ -598,13 +621,11 @@ extern "C" int mpic_plan_get(const mpic_plan* plan, int32_t what, const int32_t*
     case MPIC_PLAN_KEY_BLOCKS_32: v = &plan->kblk_flat[0]; break;
     case MPIC_PLAN_KEY_BLOCKS_64: v = &plan->kblk_flat[1]; break;
     case MPIC_PLAN_KEY_BLOCKS_96: v = &plan->kblk_flat[2]; break;
-    case MPIC_PLAN_LAZY_TILES_64:
-    case MPIC_PLAN_LAZY_TILES_96: {
-      const auto& t = plan->lazy_tiles[what == MPIC_PLAN_LAZY_TILES_64 ? 1 : 2];
-      *host_ptr = reinterpret_cast<const int32_t*>(t.data());
-      *n = t.size() * 8;
-      return MPIC_OK;
-    }
+    case MPIC_PLAN_LAZY_TILES_64: v = &plan->lazy_range[1]; break;
+    case MPIC_PLAN_LAZY_TILES_96: v = &plan->lazy_range[2]; break;
+    case MPIC_PLAN_KEY_BLOCK_PARTS_32: v = &plan->kblk_parts[0]; break;
+    case MPIC_PLAN_KEY_BLOCK_PARTS_64: v = &plan->kblk_parts[1]; break;
+    case MPIC_PLAN_KEY_BLOCK_PARTS_96: v = &plan->kblk_parts[2]; break;
     case MPIC_PLAN_ATTN_TILES:
       *host_ptr = reinterpret_cast<const int32_t*>(plan->tiles.data());
       *n = plan->tiles.size() * 8;

@@ -14,7 +14,7 @@ from helpers import Problem, assert_bf16_close, assert_f32_close, err_stats
 pytestmark = pytest.mark.gpu
 
 INT_FIELDS = [f for f in mpic.PLAN_FIELDS
-              if f not in ("attn_tiles", "launch_estimate") and not f.startswith(("key_blocks", "lazy_tiles"))]
+              if f not in ("attn_tiles", "launch_estimate") and not f.startswith(("key_block", "lazy_tiles"))]
 
 
 def _check_plan(p):

@@ -14,7 +14,7 @@ from oracle import build_plan
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 INT_FIELDS = [f for f in mpic.PLAN_FIELDS
-              if f not in ("attn_tiles", "launch_estimate") and not f.startswith(("key_blocks", "lazy_tiles"))]
+              if f not in ("attn_tiles", "launch_estimate") and not f.startswith(("key_block", "lazy_tiles"))]
 
 
 def _ctx(hq=4, hkv=2, d=128, dtype=mpic.MPIC_BF16, theta=1e4, page_size=0):
@@ -143,47 +143,56 @@ def test_paged_plan_matches_oracle(reqs, default_k, ps, rnd):
 
 
 def _check_key_blocks(plan, want, group):
-    """lazy_rope plans: for every block size the blocks list the keys of every request in order,
-    each position exactly once; a block never straddles a change of source (one chunk instance,
-    or fresh rows) and its stored rows are consecutive rows of the cache; every piece of a tile
-    that was cut along the keys owns whole blocks; the tiles restated in block indices cover
-    exactly the keys of the tiles stated in keys."""
+    """lazy_rope plans: for every block size the blocks list the keys of every request, each position
+    exactly once: first the blocks of fresh rows, then the blocks of stored rows, each part in position
+    order; a block never straddles a change of source (one chunk instance, or fresh rows) and its stored
+    rows are consecutive rows of the cache; a piece of a tile that was cut along the keys owns whole
+    blocks; the two block ranges of a tile hold exactly the blocks that start inside its key range."""
     ctx_off = want["ctx_off"]
     tiles = plan.get("attn_tiles")
     for bn in (32, 64, 96):
         blocks = plan.get(f"key_blocks_{bn}")
-        first = {}
-        at = {}
-        for i, (pos0, n_valid, inst, req) in enumerate(blocks.tolist()):
-            first.setdefault(req, i)
-            assert 1 <= n_valid <= bn
-            assert pos0 == at.get(req, 0), "blocks must list the positions of a request in order, without gaps"
-            at[req] = pos0 + n_valid
-            src = want["src_inst"][ctx_off[req] + pos0: ctx_off[req] + pos0 + n_valid]
-            assert (src == inst).all(), "a block holds keys of one source only"
-            if inst >= 0:
-                rows = want["src_row"][ctx_off[req] + pos0: ctx_off[req] + pos0 + n_valid]
-                assert (np.diff(rows) == 1).all()
-        for b in range(len(ctx_off) - 1):
-            assert at.get(b, 0) == ctx_off[b + 1] - ctx_off[b], "every position of the request in exactly one block"
-        reqs = blocks[:, 3]
-        assert (np.diff(reqs) >= 0).all()
+        parts = plan.get(f"key_block_parts_{bn}")
+        assert len(parts) == len(ctx_off) - 1
+        at_end = 0
+        for b, (lo, mid, hi) in enumerate(parts.tolist()):
+            assert lo == at_end and lo <= mid <= hi
+            at_end = hi
+            n = ctx_off[b + 1] - ctx_off[b]
+            covered = np.zeros(n, dtype=np.int32)
+            for part, (x, y) in (("fresh", (lo, mid)), ("stored", (mid, hi))):
+                last = -1
+                for (pos0, n_valid, inst, req) in blocks[x:y].tolist():
+                    assert req == b and 1 <= n_valid <= bn
+                    assert (inst < 0) == (part == "fresh")
+                    assert pos0 > last, "each part lists its blocks in position order"
+                    last = pos0
+                    covered[pos0:pos0 + n_valid] += 1
+                    src = want["src_inst"][ctx_off[b] + pos0: ctx_off[b] + pos0 + n_valid]
+                    assert (src == inst).all(), "a block holds keys of one source only"
+                    if inst >= 0:
+                        rows = want["src_row"][ctx_off[b] + pos0: ctx_off[b] + pos0 + n_valid]
+                        assert (np.diff(rows) == 1).all()
+            assert (covered == 1).all(), "every position of the request in exactly one block"
+        assert at_end == len(blocks)
         if bn == 32:
             continue
-        lazy = plan.get(f"lazy_tiles_{bn}")
-        assert lazy.shape == tiles.shape
-        starts = {(t[0], t[1], t[2], t[5]) for t in tiles.tolist() if t[3] > 0}
-        for t, l in zip(tiles.tolist(), lazy.tolist()):
-            assert t[:4] == l[:4] and t[6] == l[6]
+        ranges = plan.get(f"lazy_tiles_{bn}")
+        assert len(ranges) == len(tiles)
+        for t, (f0, f1, s0, s1) in zip(tiles.tolist(), ranges.tolist()):
             if t[3] == 0:
                 continue
             b, key_end, key0 = t[0], t[4], t[5]
-            mine = blocks[reqs == b][l[5]:l[4]]
-            assert len(mine) >= 1 and mine[0][0] == key0, "a piece starts at a block start"
-            last = mine[-1]
-            assert last[0] <= key_end - 1 < last[0] + last[1], "the last block holds the tile's last key"
-            if (t[0], t[1], t[2], key_end) in starts:     # another piece of the same rows starts where this one ends:
-                assert last[0] + last[1] == key_end, "a piece that is followed by another owns whole blocks"
+            lo, mid, hi = parts[b].tolist()
+            mine = np.concatenate([blocks[lo + f0:lo + f1], blocks[mid + s0:mid + s1]])
+            rest = np.concatenate([blocks[lo:lo + f0], blocks[lo + f1:mid], blocks[mid:mid + s0], blocks[mid + s1:hi]])
+            assert len(mine) >= 1
+            assert ((mine[:, 0] >= key0) & (mine[:, 0] < key_end)).all(), "the tile's blocks start inside its key range"
+            assert not ((rest[:, 0] >= key0) & (rest[:, 0] < key_end)).any(), "no other block starts there"
+            assert mine[:, 0].min() == key0, "a tile (or piece) starts at a block start"
+            # no earlier block reaches into the range (a piece owns whole blocks)
+            before = rest[rest[:, 0] < key0]
+            assert (before[:, 0] + before[:, 1] <= key0).all()
 
 
 @pytest.mark.parametrize("cfg", [2, 3, 4, 5])
