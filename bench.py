@@ -153,6 +153,48 @@ def sustained_mfma(torch, dev, with_clock):
     return out
 
 
+def streaming_read_probe(torch, dev, n_bytes, repeats=20):
+    """What one launch that only reads n_bytes from HBM takes on this GPU (16-byte loads, four in flight per
+    lane; best of a few grid sizes): the floor under a decode step that has to read that many bytes of keys and
+    values.  Four buffers are read in turn, so that none is still in the 256 MB Infinity Cache when its turn comes."""
+    import ctypes as C
+    if not os.path.exists(probe_lib_path()):
+        return None
+    lib = C.CDLL(probe_lib_path())
+    if not hasattr(lib, "mpic_probe_read"):
+        return None
+    lib.mpic_probe_read.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_void_p, C.c_void_p]
+    lib.mpic_probe_read.restype = C.c_int
+    n_bytes = int(n_bytes) // 4096 * 4096
+    gen = torch.Generator(device=dev).manual_seed(0x4D504943)
+    buf = torch.randint(0, 2 ** 31 - 1, (4, n_bytes // 4), generator=gen, device=dev, dtype=torch.int32)
+    stream = torch.cuda.current_stream()
+    best = None
+    for per_cu in (2, 4, 8, 16):
+        n_wgs = 256 * per_cu
+        sink = torch.empty((n_wgs + 1,), dtype=torch.float32, device=dev)
+
+        def run(i):
+            rc = lib.mpic_probe_read(C.c_void_p(buf[i % 4].data_ptr()), n_bytes, n_wgs, C.c_void_p(sink.data_ptr()),
+                                     C.c_void_p(stream.cuda_stream))
+            assert rc == 0, rc
+        for i in range(4):
+            run(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for i in range(repeats):
+            run(i)
+        e1.record(stream)
+        e1.synchronize()
+        ms = e0.elapsed_time(e1) / repeats
+        if best is None or ms < best["ms"]:
+            best = {"ms": round(ms, 5), "GBps": round(n_bytes / (ms * 1e-3) / 1e9, 1), "workgroups": n_wgs, "bytes": n_bytes}
+    best["pct_hbm_peak"] = round(100 * best["GBps"] / PEAK_HBM_GBS, 2)
+    best["note"] = "a launch that does nothing but read this many bytes once (libmpic_probe.so, probe_read_kernel), back to back"
+    return best
+
+
 def ablation_table(args, torch, dev, sh, requests, tables, pool, n_slots, n_q, attn_flops):
     """The bf16 attention launch of this workload timed with parts of its inner loop left out: timing-only
     kernel variants that only the probe library contains.  It is loaded beside the product library through a
@@ -182,22 +224,32 @@ def ablation_table(args, torch, dev, sh, requests, tables, pool, n_slots, n_q, a
     names = {0: "whole kernel", 1: "without the K/V loads", 2: "without the LDS fragment reads", 4: "without the softmax",
              3: "without loads and LDS reads", 5: "without loads and softmax", 6: "without LDS reads and softmax",
              7: "matrix instructions, barriers and the ping-pong skeleton only"}
+    # every variant twice: on the random operands, and on operands that are all zero -- there the clock does
+    # not give way to the power the data paths draw, so the second column is the instruction stream alone
+    zero_sets = [tuple(torch.zeros_like(t) for t in sets[0][:3]) + (sets[0][3],)]
     out = {}
     for mask in (0, 1, 2, 4, 3, 5, 6, 7):
         ctx.set_option(1000, mask)     # kProbeOptionAblate of the probe library
-        for i in range(args.warmup):
-            run(i)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(stream)
-        for i in range(args.steps):
-            run(i)
-        e1.record(stream)
-        e1.synchronize()
-        ms = e0.elapsed_time(e1) / args.steps
-        out[names[mask]] = {"ms": round(ms, 5), "TFLOPs_of_the_whole_kernels_work": round(attn_flops / (ms * 1e-3) / 1e12, 2)}
-    out["note"] = ("timing-only variants of attn_bf16_kernel (probe library, same launch, random inputs drawn on the GPU); "
-                   "rates are the whole kernel's algorithmic flops over each variant's time")
+        row = {}
+        for column, use in (("", sets), ("_zero_operands", zero_sets)):
+            def run_on(i):
+                q, k, v, o = use[i % len(use)]
+                pb.mpic_selective_attn(ctx.handle, plan.handle, q, k, v, sh.softmax_scale, o, None, stream)
+            for i in range(max(args.warmup, 10)):
+                run_on(i)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for i in range(args.steps):
+                run_on(i)
+            e1.record(stream)
+            e1.synchronize()
+            ms = e0.elapsed_time(e1) / args.steps
+            row["ms" + column] = round(ms, 5)
+            row["TFLOPs_of_the_whole_kernels_work" + column] = round(attn_flops / (ms * 1e-3) / 1e12, 2)
+        out[names[mask]] = row
+    out["note"] = ("timing-only variants of attn_bf16_kernel (probe library, same launch; random inputs drawn on the GPU, and "
+                   "all-zero inputs); rates are the whole kernel's algorithmic flops over each variant's time")
     plan.close()
     ctx.close()
     return out
@@ -404,6 +456,16 @@ def main():
             mpic.mpic_selective_attn_link_next(ctx.handle, plan.handle, i_s["q"], i_s["k_ctx"], i_s["v_ctx"], sh.softmax_scale,
                                                i_s["out"], nx["srcs"], nx["k_ctx"], nx["v_ctx"], None, stream)
         fused_launch_ms = timed(attend_link, args.steps)
+
+    # The same launch on operands that are all zero (queries, keys, values): the instruction stream and the
+    # memory traffic are unchanged, only the bits that toggle in the data paths are gone.  What it gains is
+    # what the part's power management takes from the launch on real operands (lower clock under higher power).
+    zq = torch.zeros_like(sets[0]["q"])
+    zk, zv = torch.zeros_like(sets[0]["k_ctx"]), torch.zeros_like(sets[0]["v_ctx"])
+    zero_set = dict(q=zq, k_ctx=zk, v_ctx=zv, out=sets[0]["out"])
+    zero_ms = timed(lambda s_: attend_of_step(zero_set), args.steps)
+    attend_of_step(sets[0])    # (out of set 0 holds real results again)
+    del zq, zk, zv, zero_set
 
     other_ms = None
     if L >= 2:
@@ -681,6 +743,7 @@ def main():
     # ---- what the matrix cores sustain on this GPU with nothing in their way, and (on request) the
     # attention launch with parts of its inner loop left out ----
     sustained = None if args.no_sustained_probe else sustained_mfma(torch, dev, not args.no_device_state)
+    read_floor = None if args.no_sustained_probe else streaming_read_probe(torch, dev, dec_bytes)
     ablation = None
     if args.mfma_ceiling:
         ablation = ablation_table(args, torch, dev, sh, requests, tables, pool, n_slots, n_q, attn_flops)
@@ -720,6 +783,11 @@ def main():
                      "kernel": "attn_bf16_kernel<%d keys per block, NoLink> (attention alone, event-timed back-to-back launches)"
                                % (64 if not (fuse or L < 2) else args.attn_block_keys or 96),
                      "avg_launch_ms": round(attn_ms, 5),
+                     "same_launch_on_zero_operands": {"avg_launch_ms": round(zero_ms, 5),
+                                                      "TFLOPs": round(attn_flops / (zero_ms * 1e-3) / 1e12, 3),
+                                                      "frac": round(attn_flops / (zero_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 5),
+                                                      "note": "not a result: the launch with every bit of Q, K and V zero, i.e. at the "
+                                                              "clock the part holds when the data paths draw no switching power"},
                      # the launch of the timed step when it is the fused one: attention + the next layer's stored rows
                      "fused_launch": None if fused_launch_ms is None else {
                          "kernel": "attn_bf16_kernel<%d keys per block, LinkNext>" % (args.attn_block_keys or 96),
@@ -740,7 +808,10 @@ def main():
         "assembly": {"ms": round(asm_ms, 5), "GBps": round(asm_gbs, 2), "pct_hbm_peak": round(100 * asm_gbs / PEAK_HBM_GBS, 3),
                      "bytes": asm_bytes},
         "decode_step": {"ms": round(dec_ms, 5), "GBps": round(dec_gbs, 2), "pct_hbm_peak": round(100 * dec_gbs / PEAK_HBM_GBS, 3),
-                        "bytes": dec_bytes, "note": "one query per request over the linked context plus itself; two launches"},
+                        "bytes": dec_bytes, "note": "one query per request over the linked context plus itself; two launches",
+                        # beside pct_hbm_peak, never instead of it: a launch that only reads the same number of bytes
+                        "read_only_launch": read_floor,
+                        "frac_of_read_only_launch": None if not read_floor else round(read_floor["ms"] / dec_ms, 4)},
         "k_distance": kd,
         "in_place_step": None if in_place is None else dict(
             in_place, TFLOPs=round(attn_flops / (in_place["ms_per_step"] * 1e-3) / 1e12, 3),

@@ -8,7 +8,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmpic.so")
 PROBE_LIB = os.path.join(HERE, "libmpic_probe.so")   # measurement aid (bench.py --mfma-ceiling), not part of the product library
-PROBE_SOURCES = ["probe_mfma.hip"]
+PROBE_SOURCES = ["probe_mfma.hip", "probe_read.hip"]
 SOURCES = ["plan.cpp", "api.hip", "assemble.hip", "attn_f32.hip", "attn_bf16.hip", "decode.hip", "select.hip", "store.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed fp32 instructions are switched off for device code
