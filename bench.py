@@ -328,7 +328,7 @@ def main():
         k_ctx = torch.empty((n_slots, sh.n_kv_heads, sh.head_dim), dtype=torch.bfloat16, device=dev)
         v_ctx = torch.empty_like(k_ctx)
         out = torch.empty_like(q)
-        sets.append(dict(index=layer, srcs=srcs, q=q, fk=fk, fv=fv, k_ctx=k_ctx, v_ctx=v_ctx, out=out))
+        sets.append(dict(index=layer, srcs=srcs, srcs_c=mpic.ChunkSources(srcs), q=q, fk=fk, fv=fv, k_ctx=k_ctx, v_ctx=v_ctx, out=out))
     stream = torch.cuda.current_stream()
     # A context that links in the background switches its attention kernel to the shape that leaves
     # room for the linking waves (64 keys per block instead of 96), so the two-stream and the
@@ -338,7 +338,7 @@ def main():
     plan_bg = mpic.Plan(ctx_bg, requests, sh.default_k, tables, pool)
 
     def assemble(s, srcs=None):
-        mpic.mpic_assemble_kv(ctx.handle, plan.handle, srcs or s["srcs"], s["fk"], s["fv"], s["k_ctx"], s["v_ctx"], stream)
+        mpic.mpic_assemble_kv(ctx.handle, plan.handle, srcs or s["srcs_c"], s["fk"], s["fv"], s["k_ctx"], s["v_ctx"], stream)
 
     def attend(s, c=None, p=None):
         mpic.mpic_selective_attn((c or ctx).handle, (p or plan).handle, s["q"], s["k_ctx"], s["v_ctx"], sh.softmax_scale,
@@ -363,7 +363,7 @@ def main():
     def link_cached(i, srcs=None, mode=mpic.MPIC_SRC_HOST_STAGED):
         s = sets[i % L]
         side.wait_event(ev_free[i % L])   # the attention that last read this context has finished
-        mpic.mpic_assemble_kv_parts(ctx_bg.handle, plan_bg.handle, srcs or s["srcs"], None, None, s["k_ctx"], s["v_ctx"],
+        mpic.mpic_assemble_kv_parts(ctx_bg.handle, plan_bg.handle, srcs or s["srcs_c"], None, None, s["k_ctx"], s["v_ctx"],
                                     mpic.MPIC_PART_CACHED | mpic.MPIC_PART_BACKGROUND, side, mode)
         ev_cached[i % L].record(side)
 
@@ -388,7 +388,7 @@ def main():
     # the attention launch of step i, in workgroups that run while that attention drains.
     def run_fused(n):
         s0 = sets[0]
-        mpic.mpic_assemble_kv_parts(ctx.handle, plan.handle, s0["srcs"], None, None, s0["k_ctx"], s0["v_ctx"],
+        mpic.mpic_assemble_kv_parts(ctx.handle, plan.handle, s0["srcs_c"], None, None, s0["k_ctx"], s0["v_ctx"],
                                     mpic.MPIC_PART_CACHED, stream)
         for i in range(n):
             s, nx = sets[i % L], sets[(i + 1) % L]
@@ -396,7 +396,7 @@ def main():
                                         mpic.MPIC_PART_FRESH, stream)
             if i + 1 < n:
                 mpic.mpic_selective_attn_link_next(ctx.handle, plan.handle, s["q"], s["k_ctx"], s["v_ctx"],
-                                                   sh.softmax_scale, s["out"], nx["srcs"], nx["k_ctx"], nx["v_ctx"],
+                                                   sh.softmax_scale, s["out"], nx["srcs_c"], nx["k_ctx"], nx["v_ctx"],
                                                    None, stream)
             else:
                 attend(s)
@@ -457,7 +457,7 @@ def main():
         def attend_link(i_s):
             nx = sets[(i_s["index"] + 1) % L]
             mpic.mpic_selective_attn_link_next(ctx.handle, plan.handle, i_s["q"], i_s["k_ctx"], i_s["v_ctx"], sh.softmax_scale,
-                                               i_s["out"], nx["srcs"], nx["k_ctx"], nx["v_ctx"], None, stream)
+                                               i_s["out"], nx["srcs_c"], nx["k_ctx"], nx["v_ctx"], None, stream)
         fused_launch_ms = timed(attend_link, args.steps)
 
     # The same launch on operands that are all zero (queries, keys, values): the instruction stream and the
@@ -513,7 +513,7 @@ def main():
     plan_lz = mpic.Plan(ctx_lz, requests, sh.default_k, tables, pool)
 
     def attend_in_place(s):
-        mpic.mpic_selective_attn_in_place(ctx_lz.handle, plan_lz.handle, s["q"], s["srcs"], s["k_ctx"], s["v_ctx"],
+        mpic.mpic_selective_attn_in_place(ctx_lz.handle, plan_lz.handle, s["q"], s["srcs_c"], s["k_ctx"], s["v_ctx"],
                                           sh.softmax_scale, s["out"], None, stream)
 
     def step_in_place(s):
@@ -556,7 +556,7 @@ def main():
             mpic.mpic_assemble_kv_parts(ctx.handle, plan.handle, None, s0["fk"], s0["fv"], s0["k_ctx"], s0["v_ctx"],
                                         mpic.MPIC_PART_FRESH, None)
             mpic.mpic_selective_attn_link_next(ctx.handle, plan.handle, s0["q"], s0["k_ctx"], s0["v_ctx"],
-                                               sh.softmax_scale, s0["out"], s1["srcs"], s1["k_ctx"], s1["v_ctx"],
+                                               sh.softmax_scale, s0["out"], s1["srcs_c"], s1["k_ctx"], s1["v_ctx"],
                                                None, None)
         else:
             mpic.mpic_assemble_kv(ctx.handle, plan.handle, s0["srcs"], s0["fk"], s0["fv"], s0["k_ctx"], s0["v_ctx"], None)

@@ -282,7 +282,19 @@ def mpic_assemble_kv(ctx, plan, srcs, fresh_k, fresh_v, k_ctx, v_ctx, stream=Non
                            MPIC_PART_CACHED | MPIC_PART_FRESH, stream, host_mode)
 
 
+class ChunkSources:
+    """Chunk sources marshalled once (the mpic_chunk_src array of a list as mpic_assemble_kv takes
+    it), for callers that hand the same list to many calls: pass the object wherever a list of
+    sources is accepted.  It keeps the tensors alive."""
+
+    def __init__(self, srcs, host_mode=MPIC_SRC_HOST_STAGED):
+        self.arr, self.n = _src_array(list(srcs or []), host_mode)
+        self.keep = srcs
+
+
 def _src_array(srcs, host_mode):
+    if isinstance(srcs, ChunkSources):
+        return srcs.arr, srcs.n
     srcs = srcs or []
     arr = (_ChunkSrc * max(1, len(srcs)))()
     for i, src in enumerate(srcs):
