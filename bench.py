@@ -223,12 +223,17 @@ def ablation_table(args, torch, dev, sh, requests, tables, pool, n_slots, n_q, a
     run(0)     # uploads the plan
     names = {0: "whole kernel", 1: "without the K/V loads", 2: "without the LDS fragment reads", 4: "without the softmax",
              3: "without loads and LDS reads", 5: "without loads and softmax", 6: "without LDS reads and softmax",
-             7: "matrix instructions, barriers and the ping-pong skeleton only"}
+             7: "matrix instructions, barriers and the ping-pong skeleton only",
+             8: "all loads issued, but every block staged from the rows of the tile's first block (cache hits)",
+             # what the loads cost on top of the skeleton (mask 6 above is skeleton + loads), taken apart
+             6 | 8: "skeleton + loads from the rows of the first block (cache hits)",
+             6 | 32: "skeleton + loads, no wait for them inside the loop",
+             6 | 64: "skeleton + the address arithmetic of the loads, no load issued"}
     # every variant twice: on the random operands, and on operands that are all zero -- there the clock does
     # not give way to the power the data paths draw, so the second column is the instruction stream alone
     zero_sets = [tuple(torch.zeros_like(t) for t in sets[0][:3]) + (sets[0][3],)]
     out = {}
-    for mask in (0, 1, 2, 4, 3, 5, 6, 7):
+    for mask in (0, 1, 2, 4, 3, 5, 6, 7, 8, 6 | 8, 6 | 32, 6 | 64):
         ctx.set_option(1000, mask)     # kProbeOptionAblate of the probe library
         row = {}
         for column, use in (("", sets), ("_zero_operands", zero_sets)):

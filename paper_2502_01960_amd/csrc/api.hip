@@ -773,7 +773,7 @@ extern "C" int mpic_set_option(mpic_ctx* ctx, int32_t option, int64_t value) {
       return MPIC_OK;
 #ifdef MPIC_PROBE_BUILD
     case mpic::kProbeOptionAblate:  // probe library only: timing runs of the bf16 kernel with parts left out
-      if (value < 0 || value > 7) return fail(ctx, MPIC_ERR_INVALID, "set_option: ablation mask must be 0..7");
+      if (value < 0 || value > 127) return fail(ctx, MPIC_ERR_INVALID, "set_option: ablation mask must be 0..127 (a mask the kernel is not built for fails at the launch)");
       ctx->attn_ablate = static_cast<int32_t>(value);
       return MPIC_OK;
 #endif

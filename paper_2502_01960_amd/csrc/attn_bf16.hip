@@ -351,6 +351,7 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
   };
   auto fetch_rows = [&](int blk) {
     blk = blk < n_iter ? blk : n_iter - 1;
+    if constexpr ((kAblate & kAblateSameRows) != 0) blk = 0;  // timing-only variant
     const __attribute__((address_space(4))) u32x4_a4* src = reinterpret_cast<const __attribute__((address_space(4))) u32x4_a4*>(
         off_of + (kLazy ? static_cast<int64_t>(bid(blk)) : static_cast<int64_t>(blk)) * BN + wave * ROWS_LOADED_PER_WAVE);
     RowOffs r;
@@ -394,7 +395,10 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
       gk[p] = kb + (static_cast<uint64_t>(r + kx) << 4);
       gv[p] = vb + (static_cast<uint64_t>(r + ld_v16) << 4);
     }
-    if constexpr (kLoadPairs == 3) {
+    if constexpr ((kAblate & kAblateAddressesOnly) != 0) {  // timing-only variant: the addresses are formed, nothing is loaded
+#pragma unroll
+      for (int p = 0; p < kLoadPairs; ++p) asm volatile("" : : "v"(gk[p]), "v"(gv[p]), "s"(dk), "s"(dv));
+    } else if constexpr (kLoadPairs == 3) {
       load6_to_lds_16B(gk[0], gv[0], gk[1], gv[1], gk[2], gv[2], dk, dv, dk + 4 * ROW_BYTES, dv + 4 * ROW_BYTES,
                        dk + 8 * ROW_BYTES, dv + 8 * ROW_BYTES);
     } else {
@@ -601,7 +605,9 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
 
   // even half step 2t: block t must be complete in LDS, then the loads of block t+2 go out
   auto even_sync = [&](int t) {
-    if (t < n_iter) {
+    if constexpr ((kAblate & kAblateNoLoadWaits) != 0) {  // timing-only variant (with kAblateLdsReads: nothing reads the rings)
+      if (t == n_iter) MPIC_WAIT_VMCNT(0);  // no load is in flight when the workgroup gives its LDS back
+    } else if (t < n_iter) {
       // this wave's share of block t has landed when at most the loads of the blocks issued
       // after it are still outstanding
       if (AHEAD == 2 && t + 1 < n_iter) {
@@ -840,6 +846,10 @@ hipError_t launch_shape(const AttnArgs& a, const AssembleArgs* next, const Assem
       case 5: return go(std::integral_constant<int, 5>{});
       case 6: return go(std::integral_constant<int, 6>{});
       case 7: return go(std::integral_constant<int, 7>{});
+      case 8: return go(std::integral_constant<int, 8>{});
+      case 6 | 8: return go(std::integral_constant<int, 6 | 8>{});
+      case 6 | 32: return go(std::integral_constant<int, 6 | 32>{});
+      case 6 | 64: return go(std::integral_constant<int, 6 | 64>{});
       default: return hipErrorInvalidValue;
     }
   }

@@ -251,7 +251,11 @@ struct AttnArgs {
 // still in bounds, so that the cost of that part can be read off the difference in run time.
 enum { kAblateLoads = 1,     // K/V blocks are staged only until every ring slot holds rows once
        kAblateLdsReads = 2,  // operand fragments are taken from registers instead of LDS
-       kAblateSoftmax = 4 }; // no exponentials, sums or conversions between the two products
+       kAblateSoftmax = 4,   // no exponentials, sums or conversions between the two products
+       kAblateSameRows = 8,  // every block is staged from the rows of the tile's first block (the loads are issued, their
+                             // data come from the nearest cache)
+       kAblateNoLoadWaits = 32,    // no wait for staged blocks inside the loop (only with kAblateLdsReads)
+       kAblateAddressesOnly = 64 };// the addresses of the direct loads are formed, the loads are not issued
 constexpr int kProbeOptionAblate = 1000;  // mpic_set_option of the probe library: value = mask of kAblate*
 // Contexts with lazy_rope: stored keys are never turned to their global position.  The kernel
 // walks the request's key blocks (KeyBlock: all keys of a block come from consecutive rows of
