@@ -399,13 +399,13 @@ __global__ __launch_bounds__(THREADS, 2) void attn_bf16_kernel(AttnArgs a, Extra
 #pragma unroll
       for (int p = 0; p < kLoadPairs; ++p) asm volatile("" : : "v"(gk[p]), "v"(gv[p]), "s"(dk), "s"(dv));
     } else if constexpr (kLoadPairs == 3) {
-      load6_to_lds_16B(gk[0], gv[0], gk[1], gv[1], gk[2], gv[2], dk, dv, dk + 4 * ROW_BYTES, dv + 4 * ROW_BYTES,
-                       dk + 8 * ROW_BYTES, dv + 8 * ROW_BYTES);
+      load3x2_to_lds_16B(static_cast<const char*>(gk[0]), static_cast<const char*>(gk[1]), static_cast<const char*>(gk[2]),
+                         static_cast<const char*>(gv[0]), static_cast<const char*>(gv[1]), static_cast<const char*>(gv[2]), dk, dv);
     } else {
-#pragma unroll
-      for (int p = 0; p < kLoadPairs; p += 2)
-        load4_to_lds_16B(gk[p], gv[p], gk[p + 1], gv[p + 1], dk + 4 * p * ROW_BYTES, dv + 4 * p * ROW_BYTES,
-                         dk + 4 * (p + 1) * ROW_BYTES, dv + 4 * (p + 1) * ROW_BYTES);
+      static_assert(kLoadPairs == 2 || kLoadPairs == 3, "rows staged per wavefront and block");
+      static_assert(4 * ROW_BYTES == 1024, "the loaders step 1024 bytes from one load to the next");
+      load2x2_to_lds_16B(static_cast<const char*>(gk[0]), static_cast<const char*>(gk[1]), static_cast<const char*>(gv[0]),
+                         static_cast<const char*>(gv[1]), dk, dv);
     }
   };
 
