@@ -133,8 +133,13 @@ def sustained_mfma(torch, dev, with_clock):
 
     # the same instruction stream on operands that are all zero: nothing toggles in the data paths, so
     # what this run gains over "mfma_only" is what the power management takes from random operands
+    # (flag 8: the fragments of the matrix instructions are read from LDS the way the kernel reads them; flag 4:
+    # the same work divided the other way, one wavefront per SIMD with 64 query columns and the softmax
+    # interleaved into its own instruction stream instead of hidden behind a second wavefront)
     for name, flags, ops in (("mfma_only", 0, seed), ("mfma_pingpong", 1, seed), ("mfma_pingpong_softmax", 3, seed),
-                             ("mfma_only_zero_operands", 0, zeros)):
+                             ("mfma_pingpong_softmax_lds_reads", 11, seed), ("one_wave_per_simd_softmax", 4, seed),
+                             ("one_wave_per_simd_softmax_lds_reads", 12, seed), ("mfma_only_zero_operands", 0, zeros),
+                             ("mfma_pingpong_softmax_lds_reads_zero_operands", 11, zeros)):
         n_blocks = 300
         run(flags, n_blocks, ops)
         torch.cuda.synchronize()
@@ -806,6 +811,8 @@ def main():
                      # beside frac, never instead of it: the same rate against what this GPU's matrix cores sustain
                      "sustained": sustained,
                      "frac_of_sustained_mfma": None if not sustained else round(attn_tflops / sustained["mfma_only_TFLOPs"], 5),
+                     "frac_of_sustained_mfma_with_softmax_and_lds_reads": None if not sustained else round(
+                         attn_tflops / sustained["mfma_pingpong_softmax_lds_reads_TFLOPs"], 5),
                      "frac_of_sustained_mfma_with_softmax_mix": None if not sustained else
                      round(attn_tflops / sustained["mfma_pingpong_softmax_TFLOPs"], 5),
                      "ablation": ablation},

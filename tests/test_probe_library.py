@@ -54,11 +54,11 @@ def test_probe_entry_points_run_and_mask_zero_is_the_product_kernel():
     seed = torch.randn((64 * 16 * 8,), device=dev).to(torch.bfloat16)
     sink = torch.full((64 * 512 + 1,), float("nan"), dtype=torch.float32, device=dev)
     fl = ctypes.c_double()
-    for flags in (0, 1, 3):
+    for flags in (0, 1, 3, 11, 4, 12):
         assert lib.mpic_probe_mfma(flags, 64, 5, seed.data_ptr(), sink.data_ptr(), stream.cuda_stream, ctypes.byref(fl)) == 0
     assert lib.mpic_probe_mfma(2, 64, 5, seed.data_ptr(), sink.data_ptr(), stream.cuda_stream, ctypes.byref(fl)) == -1
     assert lib.mpic_probe_mfma(0, 0, 5, seed.data_ptr(), sink.data_ptr(), stream.cuda_stream, ctypes.byref(fl)) == -1
-    assert fl.value == 8.0 * 48.0 * 32768.0
+    assert fl.value == 8.0 * 48.0 * 32768.0          # (= 4 * 96 * 32768 of the one-wavefront division)
     torch.cuda.synchronize()
     assert torch.isfinite(sink[:64 * 512]).all()
     buf = torch.zeros((1 << 20,), dtype=torch.int32, device=dev)
